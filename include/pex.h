@@ -1,0 +1,131 @@
+/*
+ * pex.h -- C ABI of libpex: per-example gradient statistics of a dense layer in a
+ * sequence model, and the optimizer updates that consume them, for AMD MI355X (gfx950).
+ *
+ * Problem (Sec. 2.3, "Dense layers in sequence-level architectures"; paper -> here:
+ * H -> X, Lambda -> G, L -> T, D -> din, F -> dout):
+ *     X[B,T,din]  activations entering the layer,
+ *     G[B,T,dout] cotangents (d loss / d layer output),
+ *     M_b = X_b^T G_b   the per-example weight gradient (din x dout), never stored,
+ *     S   = sum_b phi(M_b),  phi in {identity, elementwise square, sign}.
+ *
+ * Conventions common to every entry point
+ *   - Every pointer is DEVICE memory owned by the caller, dense, row-major, last
+ *     dimension contiguous, no strides.  The library never allocates, frees or
+ *     keeps a pointer.  X and G must be 16-byte aligned, fp32 buffers 16-byte aligned.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream).  No entry point synchronises the device or reads results back.
+ *   - Arguments are validated on the host first; a call that returns anything but
+ *     PEX_OK has launched nothing.
+ *   - Outputs are overwritten, not accumulated into.  Inputs are read-only.
+ *   - No exceptions cross this boundary; errors are return codes only.
+ *   - Results are run-to-run deterministic (no floating-point atomics).
+ */
+#ifndef PEX_H
+#define PEX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PEX_OK = 0,
+    PEX_ERR_NULL = 1,       /* a required pointer is NULL */
+    PEX_ERR_SHAPE = 2,      /* a dimension is < 1, too large for the kernels' 32-bit row indexing, or B < 2 where B >= 2 is needed */
+    PEX_ERR_DTYPE = 3,      /* unknown pex_dtype */
+    PEX_ERR_PHI = 4,        /* unknown pex_phi / pex_adam_variant */
+    PEX_ERR_ALIGN = 5,      /* a pointer is not 16-byte aligned */
+    PEX_ERR_WORKSPACE = 6,  /* workspace is NULL or smaller than the matching *_workspace_bytes() */
+    PEX_ERR_HIP = 7         /* the HIP runtime reported an error at launch */
+} pex_status;
+
+typedef enum { PEX_F32 = 0, PEX_BF16 = 1 } pex_dtype;                          /* storage type of X and of G (same for both) */
+typedef enum { PEX_PHI_IDENTITY = 0, PEX_PHI_SQUARE = 1, PEX_PHI_SIGN = 2 } pex_phi;
+typedef enum { PEX_ADAM = 0, PEX_MICROADAM = 1, PEX_MICROADAM_VAR = 2, PEX_MICROADAM_MSQ = 3 } pex_adam_variant;
+
+typedef void *pex_stream_t; /* a hipStream_t */
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char *pex_status_string(pex_status s);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int pex_version(void);
+
+/*
+ * pex_stat -- S = sum_b phi(X_b^T G_b)  (Sec. 2.3: M = einsum(BLD,BLF->BDF), phi, reduce over B;
+ * phi = identity is the ordinary batch weight gradient, phi = square is B * nu_micro of Eq. (nu_defs),
+ * phi = sign is B * (avg o sign) of Sec. 3.1).
+ *
+ *   X  [B,T,din], G [B,T,dout]  device, dtype `dt` (bf16 payloads are multiplied exactly and summed in
+ *                               fp32; fp32 payloads use true fp32 products), read-only.
+ *   S  [din,dout] fp32 device, overwritten.  For phi = sign the entries are integers in [-B, B]
+ *                               (sgn(0) = 0) stored as fp32, exact for B < 2^24.
+ *   workspace / workspace_bytes device scratch of at least pex_stat_workspace_bytes(...) bytes with the
+ *                               same (B,T,din,dout,dt,phi); may be NULL when that query returns 0.  It
+ *                               holds partial sums over groups of examples when the batch is split over
+ *                               workgroups; it never holds a per-example gradient, and its size is at most
+ *                               a small multiple of din*dout*4, independent of B.
+ *   The contraction over T of one example is never split across workgroups (phi is applied to the complete
+ *   sum over the sequence), the sum over b is taken in a fixed order.
+ *   Any B,T,din,dout >= 1 is accepted (B*T, din, dout each < 2^31).
+ */
+size_t pex_stat_workspace_bytes(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt, pex_phi phi);
+pex_status pex_stat(const void *X, const void *G, int64_t B, int64_t T, int64_t din, int64_t dout,
+                    pex_dtype dt, pex_phi phi, float *S, void *workspace, size_t workspace_bytes,
+                    pex_stream_t stream);
+
+/*
+ * pex_token_sq -- S_tok = (X o X)^T (G o G) = sum_{b,t} (x_bt o x_bt)(g_bt o g_bt)^T  (Sec. 2.3,
+ * "per-token second moments").  A proxy statistic: tokens are not independent computational paths in a
+ * transformer, so this is not a per-token gradient second moment.
+ *   Same buffers and conventions as pex_stat.  For bf16 inputs each squared operand is formed in fp32 and
+ *   rounded to bf16 (round to nearest even) before the contraction; all terms are >= 0, so every entry
+ *   carries a relative error of at most about 2^-7.  fp32 inputs are squared and multiplied in fp32.
+ */
+size_t pex_token_sq_workspace_bytes(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt);
+pex_status pex_token_sq(const void *X, const void *G, int64_t B, int64_t T, int64_t din, int64_t dout,
+                        pex_dtype dt, float *S_tok, void *workspace, size_t workspace_bytes,
+                        pex_stream_t stream);
+
+/*
+ * pex_adam_update -- one elementwise step of Algorithm 1 (App. E) over n parameters, in place.
+ *   mu_t   = grad_scale * S_id                      (mean gradient)
+ *   nu_mic = sq_scale   * S_sq                      (nu_micro of Eq. (nu_defs); unused and may be NULL for PEX_ADAM)
+ *   m  <- beta1*m + (1-beta1)*mu_t
+ *   nu_t = mu_t^2                                   PEX_ADAM
+ *        = nu_mic                                   PEX_MICROADAM
+ *        = (nu_mic - mu_t^2) / (1 - 1/B)            PEX_MICROADAM_VAR   (sigma^2-hat, Eq. (musq_sigsq_est))
+ *        = (mu_t^2 - nu_mic/B) / (1 - 1/B)          PEX_MICROADAM_MSQ   (mu^2-hat,    Eq. (musq_sigsq_est))
+ *   v  <- beta2*v + (1-beta2)*nu_t                  (stored unclamped; may be negative for MSQ)
+ *   mh = m/(1-beta1^step), vh = v/(1-beta2^step);   VAR and MSQ: vh <- max(0, vh)  (Sec. 3.2.3)
+ *   theta <- theta - lr * mh/(sqrt(vh + eps_root) + eps) - weight_decay*theta
+ * theta, m, v, S_id, S_sq: fp32 device arrays of n elements, 16-byte aligned.  step >= 1.
+ * VAR and MSQ need B >= 2 (PEX_ERR_SHAPE otherwise).  With cotangents of the summed loss use
+ * grad_scale = sq_scale = 1/B; with cotangents of the mean loss use grad_scale = 1, sq_scale = B.
+ */
+typedef struct {
+    float lr, beta1, beta2, eps, eps_root, weight_decay, grad_scale, sq_scale;
+    int64_t step;
+    int32_t B;
+} pex_adam_params;
+pex_status pex_adam_update(float *theta, float *m, float *v, const float *S_id, const float *S_sq,
+                           int64_t n, pex_adam_variant variant, const pex_adam_params *p /* host */,
+                           pex_stream_t stream);
+
+/*
+ * pex_signsgd_update -- MicroSignSGD = EMA o avg o sign (Sec. 3.1), in place over n parameters:
+ *   m <- beta*m + (1-beta) * S_sign/B ;  d = debias ? m/(1-beta^step) : m ;
+ *   theta <- theta - lr*d - weight_decay*theta
+ * theta, m, S_sign: fp32 device arrays of n elements, 16-byte aligned.  B >= 1, step >= 1.
+ */
+pex_status pex_signsgd_update(float *theta, float *m, const float *S_sign, int64_t n, float lr,
+                              float beta, float weight_decay, int32_t B, int32_t debias, int64_t step,
+                              pex_stream_t stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PEX_H */

@@ -1,0 +1,177 @@
+"""paper_2510_00236_amd -- thin Python binding of libpex (HIP, gfx950).
+
+Argument marshalling only: every step of the path runs in the library's HIP kernels.  PyTorch supplies
+device memory and streams.  There is no CPU fallback: if ``libpex.so`` is missing or a tensor is not on
+the GPU the call raises.
+
+Functions mirror the C ABI in ``include/pex.h``:
+``pex_stat``, ``pex_token_sq``, ``pex_adam_update``, ``pex_signsgd_update`` and the workspace queries.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpex.so")
+
+PEX_OK = 0
+PEX_F32, PEX_BF16 = 0, 1
+PEX_PHI_IDENTITY, PEX_PHI_SQUARE, PEX_PHI_SIGN = 0, 1, 2
+PEX_ADAM, PEX_MICROADAM, PEX_MICROADAM_VAR, PEX_MICROADAM_MSQ = 0, 1, 2, 3
+PHI = {"identity": PEX_PHI_IDENTITY, "square": PEX_PHI_SQUARE, "sign": PEX_PHI_SIGN}
+VARIANT = {"adam": PEX_ADAM, "microadam": PEX_MICROADAM, "microadam_var": PEX_MICROADAM_VAR,
+           "microadam_msq": PEX_MICROADAM_MSQ}
+
+EXPORTS = ("pex_status_string", "pex_version", "pex_stat_workspace_bytes", "pex_stat",
+           "pex_token_sq_workspace_bytes", "pex_token_sq", "pex_adam_update", "pex_signsgd_update")
+
+
+class PexError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libpex: {msg} (status {code})")
+        self.code = code
+
+
+class AdamParams(ctypes.Structure):
+    """Mirror of ``pex_adam_params``."""
+    _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float),
+                ("eps", ctypes.c_float), ("eps_root", ctypes.c_float), ("weight_decay", ctypes.c_float),
+                ("grad_scale", ctypes.c_float), ("sq_scale", ctypes.c_float),
+                ("step", ctypes.c_int64), ("B", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libpex.so (built by ``python -m paper_2510_00236_amd.build``); raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is not built; run `python -m paper_2510_00236_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        i64, i32, p, sz, f = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_float
+        L.pex_status_string.argtypes = [ctypes.c_int]
+        L.pex_status_string.restype = ctypes.c_char_p
+        L.pex_version.restype = ctypes.c_int
+        L.pex_stat_workspace_bytes.argtypes = [i64, i64, i64, i64, ctypes.c_int, ctypes.c_int]
+        L.pex_stat_workspace_bytes.restype = sz
+        L.pex_stat.argtypes = [p, p, i64, i64, i64, i64, ctypes.c_int, ctypes.c_int, p, p, sz, p]
+        L.pex_stat.restype = ctypes.c_int
+        L.pex_token_sq_workspace_bytes.argtypes = [i64, i64, i64, i64, ctypes.c_int]
+        L.pex_token_sq_workspace_bytes.restype = sz
+        L.pex_token_sq.argtypes = [p, p, i64, i64, i64, i64, ctypes.c_int, p, p, sz, p]
+        L.pex_token_sq.restype = ctypes.c_int
+        L.pex_adam_update.argtypes = [p, p, p, p, p, i64, ctypes.c_int, ctypes.POINTER(AdamParams), p]
+        L.pex_adam_update.restype = ctypes.c_int
+        L.pex_signsgd_update.argtypes = [p, p, p, i64, f, f, f, i32, i32, i64, p]
+        L.pex_signsgd_update.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def status_string(code: int) -> str:
+    return lib().pex_status_string(int(code)).decode()
+
+
+def _check(code: int):
+    if code != PEX_OK:
+        raise PexError(code, status_string(code))
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.float32:
+        return PEX_F32
+    if t.dtype == torch.bfloat16:
+        return PEX_BF16
+    raise TypeError(f"X and G must be float32 or bfloat16, got {t.dtype}")
+
+
+def _dev(t, name):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live in GPU memory (libpex has no CPU path)")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _shapes(X, G):
+    if X.dim() != 3 or G.dim() != 3 or X.shape[:2] != G.shape[:2]:
+        raise ValueError(f"expected X[B,T,din] and G[B,T,dout], got {tuple(X.shape)} and {tuple(G.shape)}")
+    if X.dtype != G.dtype:
+        raise TypeError("X and G must share a dtype")
+    B, T, din = X.shape
+    return int(B), int(T), int(din), int(G.shape[2])
+
+
+def pex_stat_workspace_bytes(B, T, din, dout, dtype_code, phi) -> int:
+    return int(lib().pex_stat_workspace_bytes(B, T, din, dout, dtype_code, PHI.get(phi, phi)))
+
+
+def pex_token_sq_workspace_bytes(B, T, din, dout, dtype_code) -> int:
+    return int(lib().pex_token_sq_workspace_bytes(B, T, din, dout, dtype_code))
+
+
+def _workspace(nbytes, like, workspace):
+    import torch
+    if workspace is None:
+        if nbytes == 0:
+            return None, 0, 0
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=like.device)
+    return workspace, workspace.data_ptr(), workspace.numel() * workspace.element_size()
+
+
+def pex_stat(X, G, phi, S=None, workspace=None, stream=None):
+    """S[din,dout] = sum_b phi(X_b^T G_b), fp32.  ``phi`` is 'identity' | 'square' | 'sign' (or its code)."""
+    import torch
+    B, T, din, dout = _shapes(X, G)
+    dt = _dtype_code(X)
+    code = PHI.get(phi, phi)
+    if S is None:
+        S = torch.empty(din, dout, dtype=torch.float32, device=X.device)
+    ws, wptr, wbytes = _workspace(pex_stat_workspace_bytes(B, T, din, dout, dt, code), X, workspace)
+    _check(lib().pex_stat(_dev(X, "X"), _dev(G, "G"), B, T, din, dout, dt, code, _dev(S, "S"), wptr, wbytes,
+                          _stream(stream)))
+    return S
+
+
+def pex_token_sq(X, G, S=None, workspace=None, stream=None):
+    """S_tok[din,dout] = (X o X)^T (G o G), fp32."""
+    import torch
+    B, T, din, dout = _shapes(X, G)
+    dt = _dtype_code(X)
+    if S is None:
+        S = torch.empty(din, dout, dtype=torch.float32, device=X.device)
+    ws, wptr, wbytes = _workspace(pex_token_sq_workspace_bytes(B, T, din, dout, dt), X, workspace)
+    _check(lib().pex_token_sq(_dev(X, "X"), _dev(G, "G"), B, T, din, dout, dt, _dev(S, "S"), wptr, wbytes,
+                              _stream(stream)))
+    return S
+
+
+def pex_adam_update(theta, m, v, S_id, S_sq, variant, params: AdamParams, stream=None):
+    """One in-place step of the Adam family (Algorithm 1).  ``S_sq`` may be None for plain Adam."""
+    code = VARIANT.get(variant, variant)
+    n = theta.numel()
+    for name, t in (("m", m), ("v", v), ("S_id", S_id)) + ((("S_sq", S_sq),) if S_sq is not None else ()):
+        if t.numel() != n:
+            raise ValueError(f"{name} has {t.numel()} elements, theta has {n}")
+    _check(lib().pex_adam_update(_dev(theta, "theta"), _dev(m, "m"), _dev(v, "v"), _dev(S_id, "S_id"),
+                                 _dev(S_sq, "S_sq") if S_sq is not None else None, n, code,
+                                 ctypes.byref(params), _stream(stream)))
+
+
+def pex_signsgd_update(theta, m, S_sign, lr, beta, weight_decay, B, debias=False, step=1, stream=None):
+    """One in-place MicroSignSGD step (EMA o avg o sign)."""
+    n = theta.numel()
+    if m.numel() != n or S_sign.numel() != n:
+        raise ValueError("theta, m and S_sign must have the same number of elements")
+    _check(lib().pex_signsgd_update(_dev(theta, "theta"), _dev(m, "m"), _dev(S_sign, "S_sign"), n, lr, beta,
+                                    weight_decay, int(B), int(bool(debias)), int(step), _stream(stream)))

@@ -1,0 +1,168 @@
+// pex_api.hip -- the C ABI of libpex: host-side validation, planning and kernel dispatch.
+// Every entry point validates first and launches nothing on error.
+#include <cstdlib>
+
+#include "pex_internal.h"
+
+namespace pex {
+
+static int env_int(const char* name, int dflt)
+{
+    const char* s = getenv(name);
+    if (!s || !*s) return dflt;
+    return atoi(s);
+}
+
+StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt, Mode mode)
+{
+    StatPlan p{};
+    const bool per_example = (mode == MODE_SQUARE || mode == MODE_SIGN);
+    // PEX_FORCE_GENERIC=1 routes bf16 through the SIMT kernel (a tuning/debugging aid, not a fallback:
+    // both kernels are device code of this library).
+    const bool force_generic = env_int("PEX_FORCE_GENERIC", 0) != 0;
+    p.variant = env_int("PEX_MFMA_VARIANT", -1);
+    if (p.variant < 0) p.variant = 0;
+    p.kernel = (dt == PEX_BF16 && !force_generic && mfma_bf16_supports(B, T, din, dout, mode, p.variant)) ? 1 : 0;
+
+    // The unit the batch axis is split in: whole examples when phi is applied per example (the sum over
+    // the sequence must be complete before phi), slabs of 64 rows of the flattened [B*T] axis otherwise.
+    int64_t tiles, target, units;
+    if (p.kernel == 1) {
+        int bm, bn;
+        mfma_tile_shape(p.variant, mode, &bm, &bn);
+        tiles = ((din + bm - 1) / bm) * ((dout + bn - 1) / bn);
+        target = 256;    // one workgroup per compute unit
+    } else {
+        tiles = ((din + 63) / 64) * ((dout + 63) / 64);
+        target = 1024;   // four small workgroups per compute unit
+    }
+    const int64_t slab = 64;
+    units = per_example ? B : (B * T + slab - 1) / slab;
+    int64_t nsplit = (target + tiles - 1) / tiles;
+    const int max_split = env_int("PEX_MAX_SPLIT", 16);
+    if (nsplit > max_split) nsplit = max_split;
+    if (nsplit > units) nsplit = units;
+    if (nsplit < 1) nsplit = 1;
+    int64_t per = (units + nsplit - 1) / nsplit;
+    nsplit = (units + per - 1) / per;      // no empty group
+    p.nsplit = (int)nsplit;
+    p.per_split = per_example ? per : per * slab;
+    p.ws_bytes = nsplit > 1 ? (size_t)nsplit * (size_t)din * (size_t)dout * sizeof(float) : 0;
+    return p;
+}
+
+static pex_status check_stat_args(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout,
+                                  pex_dtype dt, const float* S)
+{
+    if (!X || !G || !S) return PEX_ERR_NULL;
+    if (dt != PEX_F32 && dt != PEX_BF16) return PEX_ERR_DTYPE;
+    if (B < 1 || T < 1 || din < 1 || dout < 1) return PEX_ERR_SHAPE;
+    const int64_t lim = (int64_t)1 << 31;
+    if (din >= lim || dout >= lim || B >= lim || T >= lim || B * T >= lim) return PEX_ERR_SHAPE;
+    if (((uintptr_t)X | (uintptr_t)G | (uintptr_t)S) & 15u) return PEX_ERR_ALIGN;
+    return PEX_OK;
+}
+
+static pex_status run_stat(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt,
+                           Mode mode, float* S, void* workspace, size_t workspace_bytes, hipStream_t stream)
+{
+    const StatPlan plan = plan_stat(B, T, din, dout, dt, mode);
+    float* out = S;
+    if (plan.nsplit > 1) {
+        if (!workspace || workspace_bytes < plan.ws_bytes) return PEX_ERR_WORKSPACE;
+        if ((uintptr_t)workspace & 15u) return PEX_ERR_ALIGN;
+        out = (float*)workspace;
+    }
+    hipError_t e;
+    if (plan.kernel == 1) e = launch_stat_mfma_bf16(X, G, B, T, din, dout, mode, plan, out, stream);
+    else e = launch_stat_generic(X, G, B, T, din, dout, dt, mode, plan, out, stream);
+    if (e != hipSuccess) return PEX_ERR_HIP;
+    if (plan.nsplit > 1) {
+        e = launch_reduce_partials((const float*)workspace, plan.nsplit, din * dout, S, stream);
+        if (e != hipSuccess) return PEX_ERR_HIP;
+    }
+    return PEX_OK;
+}
+
+}  // namespace pex
+
+using namespace pex;
+
+extern "C" {
+
+const char* pex_status_string(pex_status s)
+{
+    switch (s) {
+    case PEX_OK: return "PEX_OK";
+    case PEX_ERR_NULL: return "PEX_ERR_NULL: a required pointer is NULL";
+    case PEX_ERR_SHAPE: return "PEX_ERR_SHAPE: a dimension is out of range";
+    case PEX_ERR_DTYPE: return "PEX_ERR_DTYPE: unknown storage type";
+    case PEX_ERR_PHI: return "PEX_ERR_PHI: unknown phi or optimizer variant";
+    case PEX_ERR_ALIGN: return "PEX_ERR_ALIGN: a pointer is not 16-byte aligned";
+    case PEX_ERR_WORKSPACE: return "PEX_ERR_WORKSPACE: workspace missing or too small";
+    case PEX_ERR_HIP: return "PEX_ERR_HIP: the HIP runtime reported an error";
+    }
+    return "PEX: unknown status";
+}
+
+int pex_version(void) { return 100; }
+
+size_t pex_stat_workspace_bytes(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt, pex_phi phi)
+{
+    if (B < 1 || T < 1 || din < 1 || dout < 1) return 0;
+    if (dt != PEX_F32 && dt != PEX_BF16) return 0;
+    if (phi != PEX_PHI_IDENTITY && phi != PEX_PHI_SQUARE && phi != PEX_PHI_SIGN) return 0;
+    return plan_stat(B, T, din, dout, dt, (Mode)phi).ws_bytes;
+}
+
+pex_status pex_stat(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt,
+                    pex_phi phi, float* S, void* workspace, size_t workspace_bytes, pex_stream_t stream)
+{
+    const pex_status st = check_stat_args(X, G, B, T, din, dout, dt, S);
+    if (st != PEX_OK) return st;
+    if (phi != PEX_PHI_IDENTITY && phi != PEX_PHI_SQUARE && phi != PEX_PHI_SIGN) return PEX_ERR_PHI;
+    return run_stat(X, G, B, T, din, dout, dt, (Mode)phi, S, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+size_t pex_token_sq_workspace_bytes(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt)
+{
+    if (B < 1 || T < 1 || din < 1 || dout < 1) return 0;
+    if (dt != PEX_F32 && dt != PEX_BF16) return 0;
+    return plan_stat(B, T, din, dout, dt, MODE_TOKEN_SQ).ws_bytes;
+}
+
+pex_status pex_token_sq(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt,
+                        float* S_tok, void* workspace, size_t workspace_bytes, pex_stream_t stream)
+{
+    const pex_status st = check_stat_args(X, G, B, T, din, dout, dt, S_tok);
+    if (st != PEX_OK) return st;
+    return run_stat(X, G, B, T, din, dout, dt, MODE_TOKEN_SQ, S_tok, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+pex_status pex_adam_update(float* theta, float* m, float* v, const float* S_id, const float* S_sq, int64_t n,
+                           pex_adam_variant variant, const pex_adam_params* p, pex_stream_t stream)
+{
+    if (!theta || !m || !v || !S_id || !p) return PEX_ERR_NULL;
+    if (variant != PEX_ADAM && variant != PEX_MICROADAM && variant != PEX_MICROADAM_VAR && variant != PEX_MICROADAM_MSQ)
+        return PEX_ERR_PHI;
+    if (variant != PEX_ADAM && !S_sq) return PEX_ERR_NULL;
+    if (n < 1 || p->step < 1 || p->B < 1) return PEX_ERR_SHAPE;
+    if ((variant == PEX_MICROADAM_VAR || variant == PEX_MICROADAM_MSQ) && p->B < 2) return PEX_ERR_SHAPE;
+    if (((uintptr_t)theta | (uintptr_t)m | (uintptr_t)v | (uintptr_t)S_id | (uintptr_t)S_sq) & 15u) return PEX_ERR_ALIGN;
+    return launch_adam_update(theta, m, v, S_id, S_sq, n, variant, *p, (hipStream_t)stream) == hipSuccess ? PEX_OK
+                                                                                                           : PEX_ERR_HIP;
+}
+
+pex_status pex_signsgd_update(float* theta, float* m, const float* S_sign, int64_t n, float lr, float beta,
+                              float weight_decay, int32_t B, int32_t debias, int64_t step, pex_stream_t stream)
+{
+    if (!theta || !m || !S_sign) return PEX_ERR_NULL;
+    if (n < 1 || B < 1 || step < 1) return PEX_ERR_SHAPE;
+    if (((uintptr_t)theta | (uintptr_t)m | (uintptr_t)S_sign) & 15u) return PEX_ERR_ALIGN;
+    return launch_signsgd_update(theta, m, S_sign, n, lr, beta, weight_decay, B, debias, step, (hipStream_t)stream) ==
+                   hipSuccess
+               ? PEX_OK
+               : PEX_ERR_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,45 @@
+// pex_internal.h -- declarations shared by the translation units of libpex (host side only).
+// Nothing here is visible through the C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "pex.h"
+
+namespace pex {
+
+// Which statistic a contraction kernel produces.  PHI_* match pex_phi; TOKEN_SQ is the per-token
+// square (operands squared on the load path, one plain contraction over K = B*T).
+enum Mode : int { MODE_IDENTITY = 0, MODE_SQUARE = 1, MODE_SIGN = 2, MODE_TOKEN_SQ = 3 };
+
+// How one call is carried out.  Chosen on the host from the shape alone, so the workspace query and
+// the launch always agree.
+struct StatPlan {
+    int kernel;        // 0 = generic SIMT kernel, 1 = bf16 MFMA kernel
+    int nsplit;        // number of groups the batch (or, for plain contractions, B*T) is split into
+    int64_t per_split; // examples (or rows of B*T) per group
+    int variant;       // tile variant of the MFMA kernel
+    size_t ws_bytes;   // nsplit > 1: nsplit * din * dout * 4, else 0
+};
+
+StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt, Mode mode);
+
+// Launchers.  `out` is S when plan.nsplit == 1, else the workspace holding [nsplit][din][dout] partials.
+hipError_t launch_stat_generic(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout,
+                               pex_dtype dt, Mode mode, const StatPlan& plan, float* out, hipStream_t stream);
+hipError_t launch_stat_mfma_bf16(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout,
+                                 Mode mode, const StatPlan& plan, float* out, hipStream_t stream);
+bool mfma_bf16_supports(int64_t B, int64_t T, int64_t din, int64_t dout, Mode mode, int variant);
+void mfma_tile_shape(int variant, Mode mode, int* bm, int* bn);
+
+// S[e] = sum_{s < nsplit} partial[s][e], s ascending (fixed order => deterministic).
+hipError_t launch_reduce_partials(const float* partial, int nsplit, int64_t n, float* S, hipStream_t stream);
+
+hipError_t launch_adam_update(float* theta, float* m, float* v, const float* S_id, const float* S_sq, int64_t n,
+                              pex_adam_variant variant, const pex_adam_params& p, hipStream_t stream);
+hipError_t launch_signsgd_update(float* theta, float* m, const float* S_sign, int64_t n, float lr, float beta,
+                                 float weight_decay, int32_t B, int32_t debias, int64_t step, hipStream_t stream);
+
+}  // namespace pex

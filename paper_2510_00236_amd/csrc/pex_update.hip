@@ -1,0 +1,138 @@
+// pex_update.hip -- elementwise optimizer updates that consume the statistics (Algorithm 1, App. E, with
+// the estimators of Eq. (musq_sigsq_est); MicroSignSGD of Sec. 3.1).  One pass, in place, bound by HBM
+// bandwidth: Adam family 20 B read + 12 B written per parameter (16 + 12 for plain Adam, which never
+// touches S_sq), MicroSignSGD 12 B read + 8 B written.  16-byte accesses, grid-stride, scalar tail.
+#include "pex_internal.h"
+
+namespace pex {
+namespace {
+
+struct AdamConsts {
+    float beta1, one_m_beta1, beta2, one_m_beta2;
+    float inv_bc1, inv_bc2;   // 1/(1-beta1^t), 1/(1-beta2^t)
+    float eps, eps_root, lr, wd, gs, qs;
+    float c_est, inv_B;       // 1/(1-1/B), 1/B
+};
+
+template <int VARIANT>
+__device__ __forceinline__ void adam_one(float& th, float& m, float& v, float sid, float ssq, const AdamConsts& k)
+{
+    const float mu_t = k.gs * sid;
+    const float nu_adam = mu_t * mu_t;
+    float nu_t;
+    if (VARIANT == PEX_ADAM) nu_t = nu_adam;
+    else {
+        const float nu_micro = k.qs * ssq;
+        if (VARIANT == PEX_MICROADAM) nu_t = nu_micro;
+        else if (VARIANT == PEX_MICROADAM_VAR) nu_t = k.c_est * (nu_micro - nu_adam);
+        else nu_t = k.c_est * (nu_adam - nu_micro * k.inv_B);
+    }
+    m = fmaf(k.beta1, m, k.one_m_beta1 * mu_t);
+    v = fmaf(k.beta2, v, k.one_m_beta2 * nu_t);
+    const float mh = m * k.inv_bc1;
+    float vh = v * k.inv_bc2;
+    if (VARIANT == PEX_MICROADAM_VAR || VARIANT == PEX_MICROADAM_MSQ) vh = fmaxf(0.f, vh);
+    const float u = mh / (sqrtf(vh + k.eps_root) + k.eps);
+    th = th - k.lr * u - k.wd * th;
+}
+
+template <int VARIANT>
+__global__ __launch_bounds__(256) void adam_update_kernel(float* __restrict__ theta, float* __restrict__ m,
+                                                          float* __restrict__ v, const float* __restrict__ S_id,
+                                                          const float* __restrict__ S_sq, int64_t n, AdamConsts k)
+{
+    const int64_t n4 = n / 4;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    float4* th4 = reinterpret_cast<float4*>(theta);
+    float4* m4 = reinterpret_cast<float4*>(m);
+    float4* v4 = reinterpret_cast<float4*>(v);
+    const float4* a4 = reinterpret_cast<const float4*>(S_id);
+    const float4* q4 = reinterpret_cast<const float4*>(S_sq);
+    for (int64_t e = gid; e < n4; e += stride) {
+        float4 t = th4[e], mm = m4[e], vv = v4[e];
+        const float4 a = a4[e];
+        float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (VARIANT != PEX_ADAM) q = q4[e];
+        adam_one<VARIANT>(t.x, mm.x, vv.x, a.x, q.x, k);
+        adam_one<VARIANT>(t.y, mm.y, vv.y, a.y, q.y, k);
+        adam_one<VARIANT>(t.z, mm.z, vv.z, a.z, q.z, k);
+        adam_one<VARIANT>(t.w, mm.w, vv.w, a.w, q.w, k);
+        th4[e] = t; m4[e] = mm; v4[e] = vv;
+    }
+    for (int64_t e = n4 * 4 + gid; e < n; e += stride) {
+        float t = theta[e], mm = m[e], vv = v[e];
+        adam_one<VARIANT>(t, mm, vv, S_id[e], VARIANT != PEX_ADAM ? S_sq[e] : 0.f, k);
+        theta[e] = t; m[e] = mm; v[e] = vv;
+    }
+}
+
+__global__ __launch_bounds__(256) void signsgd_update_kernel(float* __restrict__ theta, float* __restrict__ m,
+                                                             const float* __restrict__ S_sign, int64_t n, float lr,
+                                                             float beta, float one_m_beta_over_B, float wd, float debias_mul)
+{
+    const int64_t n4 = n / 4;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    float4* th4 = reinterpret_cast<float4*>(theta);
+    float4* m4 = reinterpret_cast<float4*>(m);
+    const float4* s4 = reinterpret_cast<const float4*>(S_sign);
+    auto one = [&](float& t, float& mm, float s) {
+        mm = fmaf(beta, mm, one_m_beta_over_B * s);
+        t = t - lr * (mm * debias_mul) - wd * t;
+    };
+    for (int64_t e = gid; e < n4; e += stride) {
+        float4 t = th4[e], mm = m4[e];
+        const float4 s = s4[e];
+        one(t.x, mm.x, s.x); one(t.y, mm.y, s.y); one(t.z, mm.z, s.z); one(t.w, mm.w, s.w);
+        th4[e] = t; m4[e] = mm;
+    }
+    for (int64_t e = n4 * 4 + gid; e < n; e += stride) {
+        float t = theta[e], mm = m[e];
+        one(t, mm, S_sign[e]);
+        theta[e] = t; m[e] = mm;
+    }
+}
+
+inline unsigned update_grid(int64_t n)
+{
+    int64_t blocks = (n / 4 + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    const int64_t cap = 256 * 16;   // 256 CUs x 16 resident workgroups: enough loads in flight, short tail
+    return (unsigned)(blocks > cap ? cap : blocks);
+}
+
+}  // namespace
+
+hipError_t launch_adam_update(float* theta, float* m, float* v, const float* S_id, const float* S_sq, int64_t n,
+                              pex_adam_variant variant, const pex_adam_params& p, hipStream_t stream)
+{
+    AdamConsts k;
+    k.beta1 = p.beta1; k.one_m_beta1 = 1.f - p.beta1;
+    k.beta2 = p.beta2; k.one_m_beta2 = 1.f - p.beta2;
+    k.inv_bc1 = (float)(1.0 / (1.0 - pow((double)p.beta1, (double)p.step)));
+    k.inv_bc2 = (float)(1.0 / (1.0 - pow((double)p.beta2, (double)p.step)));
+    k.eps = p.eps; k.eps_root = p.eps_root; k.lr = p.lr; k.wd = p.weight_decay;
+    k.gs = p.grad_scale; k.qs = p.sq_scale;
+    k.inv_B = 1.f / (float)p.B;
+    k.c_est = p.B > 1 ? (float)(1.0 / (1.0 - 1.0 / (double)p.B)) : 0.f;
+    const dim3 grid(update_grid(n)), block(256);
+    switch (variant) {
+    case PEX_ADAM: adam_update_kernel<PEX_ADAM><<<grid, block, 0, stream>>>(theta, m, v, S_id, S_sq, n, k); break;
+    case PEX_MICROADAM: adam_update_kernel<PEX_MICROADAM><<<grid, block, 0, stream>>>(theta, m, v, S_id, S_sq, n, k); break;
+    case PEX_MICROADAM_VAR: adam_update_kernel<PEX_MICROADAM_VAR><<<grid, block, 0, stream>>>(theta, m, v, S_id, S_sq, n, k); break;
+    case PEX_MICROADAM_MSQ: adam_update_kernel<PEX_MICROADAM_MSQ><<<grid, block, 0, stream>>>(theta, m, v, S_id, S_sq, n, k); break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_signsgd_update(float* theta, float* m, const float* S_sign, int64_t n, float lr, float beta,
+                                 float weight_decay, int32_t B, int32_t debias, int64_t step, hipStream_t stream)
+{
+    const float debias_mul = debias ? (float)(1.0 / (1.0 - pow((double)beta, (double)step))) : 1.f;
+    const float w = (1.f - beta) / (float)B;
+    signsgd_update_kernel<<<dim3(update_grid(n)), dim3(256), 0, stream>>>(theta, m, S_sign, n, lr, beta, w, weight_decay, debias_mul);
+    return hipGetLastError();
+}
+
+}  // namespace pex

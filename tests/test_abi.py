@@ -1,0 +1,103 @@
+"""The C ABI: libpex.so loads, exports every function include/pex.h declares, and validates its
+arguments on the host before touching the GPU.  No compute call is made here, so no GPU is needed."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2510_00236_amd as pex
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "pex.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b(pex_[a-z_0-9]+)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_header_and_library_agree():
+    names = _declared_functions()
+    assert set(names) == set(pex.EXPORTS), names
+    L = pex.lib()
+    for n in names:
+        assert hasattr(L, n), f"libpex.so does not export {n}"
+
+
+def test_version_and_status_strings():
+    assert pex.lib().pex_version() >= 100
+    seen = set()
+    for code in range(8):
+        s = pex.status_string(code)
+        assert s.startswith("PEX_") and s not in seen
+        seen.add(s)
+    assert "unknown" in pex.status_string(99)
+
+
+def test_struct_layout_matches_header():
+    # 8 floats, int64, int32 (+ padding): the layout a C compiler gives pex_adam_params
+    assert ctypes.sizeof(pex.AdamParams) == 48
+    assert pex.AdamParams.step.offset == 32 and pex.AdamParams.B.offset == 40
+
+
+def test_workspace_query_is_bounded_and_independent_of_B():
+    """The scratch holds partial sums over groups of examples, never a [B, din, dout] tensor."""
+    for (B, T, din, dout) in [(32, 256, 512, 2048), (64, 1024, 768, 768), (16, 2048, 2048, 8192), (4, 8192, 4096, 4096)]:
+        for phi in ("identity", "square", "sign"):
+            ws = pex.pex_stat_workspace_bytes(B, T, din, dout, pex.PEX_BF16, phi)
+            assert ws % (din * dout * 4) == 0
+            assert ws <= 16 * din * dout * 4
+            assert ws < B * din * dout * 4 or B <= 16
+        assert pex.pex_token_sq_workspace_bytes(B, T, din, dout, pex.PEX_BF16) <= 16 * din * dout * 4
+    assert pex.pex_stat_workspace_bytes(0, 1, 1, 1, pex.PEX_BF16, "square") == 0
+    assert pex.pex_stat_workspace_bytes(16, 2048, 2048, 8192, pex.PEX_BF16, "square") == 0
+
+
+def test_host_validation_launches_nothing():
+    """Bad arguments are turned into status codes before any pointer is used (fake addresses, never dereferenced)."""
+    L = pex.lib()
+    X, G, S = 0x1000, 0x2000, 0x3000
+    ok = (4, 16, 64, 64)
+    assert L.pex_stat(None, G, *ok, 0, 0, S, None, 0, None) == 1
+    assert L.pex_stat(X, G, *ok, 0, 0, None, None, 0, None) == 1
+    assert L.pex_stat(X, G, 0, 16, 64, 64, 0, 0, S, None, 0, None) == 2
+    assert L.pex_stat(X, G, 4, 16, -1, 64, 0, 0, S, None, 0, None) == 2
+    assert L.pex_stat(X, G, 1 << 20, 1 << 20, 64, 64, 0, 0, S, None, 0, None) == 2
+    assert L.pex_stat(X, G, *ok, 7, 0, S, None, 0, None) == 3
+    assert L.pex_stat(X, G, *ok, 0, 9, S, None, 0, None) == 4
+    assert L.pex_stat(X + 2, G, *ok, 0, 0, S, None, 0, None) == 5
+    assert L.pex_stat(X, G, *ok, 0, 0, S + 4, None, 0, None) == 5
+    need = pex.pex_stat_workspace_bytes(*ok, pex.PEX_F32, "square")
+    assert need > 0
+    assert L.pex_stat(X, G, *ok, 0, 1, S, None, 0, None) == 6
+    assert L.pex_stat(X, G, *ok, 0, 1, S, 0x4000, need - 1, None) == 6
+    assert L.pex_stat(X, G, *ok, 0, 1, S, 0x4004, need, None) == 5
+    assert L.pex_token_sq(X, None, *ok, 0, S, None, 0, None) == 1
+    assert L.pex_token_sq(X, G, 4, 0, 64, 64, 0, S, None, 0, None) == 2
+
+    p = pex.AdamParams(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, eps_root=0.0, weight_decay=0.0,
+                       grad_scale=1.0, sq_scale=1.0, step=1, B=4)
+    th, m, v, a, q = 0x1000, 0x2000, 0x3000, 0x4000, 0x5000
+    assert L.pex_adam_update(None, m, v, a, q, 16, 1, ctypes.byref(p), None) == 1
+    assert L.pex_adam_update(th, m, v, a, None, 16, 1, ctypes.byref(p), None) == 1     # MicroAdam needs S_sq
+    assert L.pex_adam_update(th, m, v, a, q, 16, 1, None, None) == 1
+    assert L.pex_adam_update(th, m, v, a, q, 0, 1, ctypes.byref(p), None) == 2
+    assert L.pex_adam_update(th, m, v, a, q, 16, 5, ctypes.byref(p), None) == 4
+    assert L.pex_adam_update(th + 4, m, v, a, q, 16, 1, ctypes.byref(p), None) == 5
+    p1 = pex.AdamParams(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, step=1, B=1)
+    assert L.pex_adam_update(th, m, v, a, q, 16, 2, ctypes.byref(p1), None) == 2        # Var needs B >= 2
+    assert L.pex_adam_update(th, m, v, a, q, 16, 3, ctypes.byref(p1), None) == 2
+    p0 = pex.AdamParams(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, step=0, B=4)
+    assert L.pex_adam_update(th, m, v, a, q, 16, 1, ctypes.byref(p0), None) == 2        # steps count from 1
+    assert L.pex_signsgd_update(th, None, a, 16, 1e-3, 0.9, 0.0, 4, 0, 1, None) == 1
+    assert L.pex_signsgd_update(th, m, a, 16, 1e-3, 0.9, 0.0, 0, 0, 1, None) == 2
+    assert L.pex_signsgd_update(th, m, a + 8, 16, 1e-3, 0.9, 0.0, 4, 0, 1, None) == 5
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    X = torch.zeros(2, 4, 8)
+    with pytest.raises(ValueError, match="GPU"):
+        pex.pex_stat(X, X.clone(), "square", S=torch.zeros(8, 8))

@@ -1,0 +1,142 @@
+"""GPU parity: libpex through its C ABI against the fp64 CPU oracle, element by element, on the same
+seeded inputs -- sizes the oracle finishes in seconds, spanning several tiles and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2510_00236_amd as pex
+import synth_inputs as si
+from parity_util import assert_real_stat, assert_sign_stat, TOKEN_SQ_BF16_BAR
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _run_all(X, G):
+    Xd, Gd = X.to(DEV), G.to(DEV)
+    out = {phi: pex.pex_stat(Xd, Gd, phi) for phi in ("identity", "square", "sign")}
+    out["token_sq"] = pex.pex_token_sq(Xd, Gd)
+    torch.cuda.synchronize()
+    return {k: v.cpu().numpy().astype(np.float64) for k, v in out.items()}
+
+
+def _compare(X, G, dtype, tag, elementwise=True):
+    got = _run_all(X, G)
+    Xn, Gn = si.widen(X), si.widen(G)
+    st = oracle.stat(Xn, Gn)
+    tok = oracle.token_sq(Xn, Gn)
+    assert_real_stat(got["identity"], st.S_id, dtype, f"{tag} identity", elementwise=False)
+    assert_real_stat(got["square"], st.S_sq, dtype, f"{tag} square", elementwise=elementwise)
+    assert_sign_stat(got["sign"], st.S_sign, st.amb, f"{tag} sign")
+    if dtype == "bf16":
+        assert_real_stat(got["token_sq"], tok, dtype, f"{tag} token_sq", elementwise=True, bar=TOKEN_SQ_BF16_BAR, eng=None)
+    else:
+        assert_real_stat(got["token_sq"], tok, dtype, f"{tag} token_sq", elementwise=True)
+    return got, st
+
+
+def test_config1_tiny_fp32():
+    X, G = si.make("c1_tiny", seed=0)
+    _compare(X, G, "f32", "c1")
+
+
+def test_config2_mlp_in_bf16():
+    X, G = si.make("c2_mlp_in", seed=0)
+    _compare(X, G, "bf16", "c2")
+
+
+# (B, T, din, dout, dtype): ragged tails in every dimension, on both kernels
+SHAPES = [
+    (3, 100, 200, 136, "bf16"),    # multiples of 8: MFMA path with zero-filled tile edges, T not a slab multiple
+    (5, 77, 520, 264, "bf16"),     # several tiles per dimension plus ragged edges
+    (2, 37, 70, 33, "bf16"),       # rows not 16-byte multiples: SIMT path on bf16
+    (2, 37, 70, 33, "f32"),
+    (3, 50, 129, 65, "f32"),
+    (7, 33, 256, 128, "bf16"),     # exactly one tile, odd T
+    (1, 64, 96, 160, "bf16"),      # B = 1
+    (40, 1, 128, 96, "bf16"),      # T = 1 (rank-one gradients)
+    (2, 16, 32, 32, "bf16"),       # smallest shape the MFMA path takes
+    (1, 1, 1, 1, "f32"),           # degenerate
+    (1, 1, 8, 8, "bf16"),
+]
+
+
+@pytest.mark.parametrize("B,T,din,dout,dtype", SHAPES)
+def test_ragged_and_edge_shapes(B, T, din, dout, dtype):
+    X, G = si.custom(B, T, din, dout, dtype=dtype, seed=B * 1000 + T)
+    # with B = 1 an entry of S_sq is a single squared cancelling sum: only the max-norm metric is meaningful
+    _compare(X, G, dtype, f"B{B} T{T} {din}x{dout} {dtype}", elementwise=(B >= 3))
+
+
+@pytest.mark.parametrize("B,T,din,dout,dtype", [(5, 48, 264, 136, "bf16"), (3, 19, 45, 51, "bf16"), (4, 16, 64, 64, "f32")])
+def test_integer_inputs_are_bit_exact(B, T, din, dout, dtype):
+    """Small-integer inputs: every product and partial sum is exact, so every statistic must match bit for bit."""
+    X, G = si.integer_valued(B, T, din, dout, dtype=dtype, seed=3)
+    got = _run_all(X, G)
+    Xn, Gn = si.widen(X), si.widen(G)
+    st = oracle.stat(Xn, Gn)
+    assert np.array_equal(got["identity"], st.S_id)
+    assert np.array_equal(got["square"], st.S_sq)
+    assert np.array_equal(got["sign"], st.S_sign)          # includes exact zeros: sgn(0) = 0
+    assert (st.S_sign != np.sign(st.S_id) * B).any()
+    assert np.array_equal(got["token_sq"], oracle.token_sq(Xn, Gn))
+
+
+def test_zero_example_gives_zero_sign():
+    """An example whose activations are all zero contributes sgn(0) = 0 everywhere."""
+    X, G = si.custom(3, 40, 64, 64, dtype="bf16", seed=5)
+    X[1] = 0
+    got = _run_all(X, G)
+    st = oracle.stat(si.widen(X), si.widen(G))
+    assert_sign_stat(got["sign"], st.S_sign, st.amb, "zero example")   # max|M_b| = 0: the band is empty, the zeros are exact
+    assert np.abs(got["sign"]).max() <= 2
+
+
+def test_run_to_run_determinism():
+    X, G = si.custom(16, 96, 512, 384, dtype="bf16", seed=7)
+    Xd, Gd = X.to(DEV), G.to(DEV)
+    for phi in ("identity", "square", "sign"):
+        a = pex.pex_stat(Xd, Gd, phi).clone()
+        b = pex.pex_stat(Xd, Gd, phi)
+        torch.cuda.synchronize()
+        assert torch.equal(a, b), phi
+    a = pex.pex_token_sq(Xd, Gd).clone()
+    assert torch.equal(a, pex.pex_token_sq(Xd, Gd))
+
+
+def test_batch_permutation_and_output_overwrite():
+    """S does not depend on the order of examples (Sec. 3.1) and is overwritten, not accumulated into."""
+    X, G = si.custom(6, 64, 256, 128, dtype="bf16", seed=8)
+    perm = torch.tensor([3, 0, 5, 1, 4, 2])
+    Xd, Gd = X.to(DEV), G.to(DEV)
+    S = torch.full((256, 128), 1e30, device=DEV)
+    pex.pex_stat(Xd, Gd, "sign", S=S)
+    S2 = pex.pex_stat(Xd[perm].contiguous(), Gd[perm].contiguous(), "sign")
+    torch.cuda.synchronize()
+    assert torch.equal(S, S2)
+    assert S.abs().max() <= 6
+
+
+def test_non_default_stream():
+    X, G = si.custom(4, 64, 128, 128, dtype="bf16", seed=9)
+    Xd, Gd = X.to(DEV), G.to(DEV)
+    ref = pex.pex_stat(Xd, Gd, "square")
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        out = pex.pex_stat(Xd, Gd, "square", stream=s)
+    s.synchronize()
+    assert torch.equal(ref, out)
+
+
+def test_workspace_errors_on_gpu():
+    X, G = si.custom(8, 32, 256, 128, dtype="bf16", seed=10)
+    Xd, Gd = X.to(DEV), G.to(DEV)
+    need = pex.pex_stat_workspace_bytes(8, 32, 256, 128, pex.PEX_BF16, "square")
+    assert need > 0
+    small = torch.empty(need - 16, dtype=torch.uint8, device=DEV)
+    with pytest.raises(pex.PexError) as ei:
+        pex.pex_stat(Xd, Gd, "square", workspace=small)
+    assert ei.value.code == 6

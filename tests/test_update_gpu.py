@@ -1,0 +1,103 @@
+"""GPU parity of the optimizer-update kernels against the fp64 elementwise oracle, over consecutive steps."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2510_00236_amd as pex
+import synth_inputs as si
+from oracle import update as ou
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+VARIANTS = [("adam", ou.ADAM), ("microadam", ou.MICROADAM), ("microadam_var", ou.MICROADAM_VAR),
+            ("microadam_msq", ou.MICROADAM_MSQ)]
+
+
+def _stats(n, B, seed, mean=0.05):
+    """Synthetic S_id, S_sq of B per-example gradients g_b ~ N(mean, 1) * 1e-2 (fp32, as pex_stat would emit)."""
+    g = torch.Generator().manual_seed(seed)
+    gb = (torch.randn(B, n, generator=g) + mean) * 1e-2
+    return gb.sum(0).contiguous(), (gb * gb).sum(0).contiguous()
+
+
+@pytest.mark.parametrize("name,code", VARIANTS)
+@pytest.mark.parametrize("n", [1 << 20, 1000003, 7])
+def test_adam_family_matches_oracle(name, code, n):
+    B, steps = 32, 3
+    theta0, m0, v0 = si.optimizer_state(n, seed=1)
+    th, m, v = theta0.to(DEV), m0.to(DEV), v0.to(DEV)
+    rth, rm, rv = theta0.double().numpy(), m0.double().numpy(), v0.double().numpy()
+    eps = 1e-6 if name == "microadam_msq" else 1e-8
+    for t in range(1, steps + 1):
+        S_id, S_sq = _stats(n, B, 100 + t)
+        kw = dict(lr=2.0 / 1024, beta1=0.9, beta2=0.95, eps=eps, eps_root=0.0, weight_decay=1e-4,
+                  grad_scale=1.0 / B, sq_scale=1.0 / B, step=t, B=B)
+        pex.pex_adam_update(th, m, v, S_id.to(DEV), None if name == "adam" else S_sq.to(DEV), name, pex.AdamParams(**kw))
+        rth, rm, rv = ou.adam_family_step(rth, rm, rv, S_id.numpy(), S_sq.numpy(), code, ou.AdamParams(**kw))
+        torch.cuda.synchronize()
+        gm, gv, gth = m.cpu().double().numpy(), v.cpu().double().numpy(), th.cpu().double().numpy()
+        # fp32 arithmetic on fp32 inputs: a few ulp on m; v of the Var/MSQ variants is a difference of two
+        # O(nu_micro) terms, so its error is measured against that scale.
+        np.testing.assert_allclose(gm, rm, rtol=2e-6, atol=4e-7 * np.abs(rm).max())
+        nu_scale = float((S_sq.double().numpy() / B).max())
+        np.testing.assert_allclose(gv, rv, rtol=4e-6, atol=4e-7 * nu_scale)
+        # theta moves by lr*u with |u| <~ 1/sqrt(1-beta2)...; compare the step, not theta itself
+        step_ref, step_got = rth - theta0.double().numpy(), gth - theta0.double().numpy()
+        tol = 2e-4 if name in ("microadam_var", "microadam_msq") else 2e-5
+        assert np.abs(step_got - step_ref).max() <= tol * np.abs(step_ref).max() + 1e-9, name
+        assert np.isfinite(gth).all()
+
+
+def test_msq_negative_estimates_are_clamped():
+    """mu^2-hat < 0 where the mean is ~0: v stays negative in memory, the step stays finite (Sec. 3.2.3)."""
+    n, B = 4096, 8
+    S_id = torch.zeros(n)
+    S_sq = torch.full((n,), 8.0e-4)
+    th, m, v = (torch.ones(n, device=DEV), torch.zeros(n, device=DEV), torch.zeros(n, device=DEV))
+    p = pex.AdamParams(lr=1e-2, beta1=0.9, beta2=0.95, eps=1e-6, eps_root=0.0, weight_decay=0.0,
+                       grad_scale=1.0 / B, sq_scale=1.0 / B, step=1, B=B)
+    pex.pex_adam_update(th, m, v, S_id.to(DEV), S_sq.to(DEV), "microadam_msq", p)
+    torch.cuda.synchronize()
+    assert (v < 0).all() and torch.isfinite(th).all() and torch.equal(th, torch.ones(n, device=DEV))
+
+
+@pytest.mark.parametrize("n", [1 << 20, 1000003, 5])
+@pytest.mark.parametrize("debias", [False, True])
+def test_microsignsgd_matches_oracle(n, debias):
+    B, beta, lr, wd = 64, 0.9, 3.47e-3, 1e-4
+    theta0, m0, _ = si.optimizer_state(n, seed=2)
+    th, m = theta0.to(DEV), m0.to(DEV)
+    rth, rm = theta0.double().numpy(), m0.double().numpy()
+    g = torch.Generator().manual_seed(5)
+    for t in range(1, 4):
+        S_sign = torch.randint(-B // 2, B // 2 + 1, (n,), generator=g).float() * 2   # same parity as B
+        pex.pex_signsgd_update(th, m, S_sign.to(DEV), lr, beta, wd, B, debias=debias, step=t)
+        rth, rm = ou.microsignsgd_step(rth, rm, S_sign.numpy(), lr, beta, wd, B, debias, t)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(m.cpu().double().numpy(), rm, rtol=2e-6, atol=4e-7)
+    assert (m.abs() <= 1).all()
+    d_ref, d_got = rth - theta0.double().numpy(), th.cpu().double().numpy() - theta0.double().numpy()
+    assert np.abs(d_got - d_ref).max() <= 2e-5 * np.abs(d_ref).max() + 1e-9
+
+
+def test_end_to_end_stat_then_update():
+    """Config-2 layer: statistics from pex_stat feed the MicroAdam update; compared with the oracle chain."""
+    import oracle
+    w = si.WORKLOADS["c2_mlp_in"]
+    X, G = si.make(w, seed=1)
+    Xd, Gd = X.to(DEV), G.to(DEV)
+    S_id, S_sq = pex.pex_stat(Xd, Gd, "identity"), pex.pex_stat(Xd, Gd, "square")
+    n = w.din * w.dout
+    theta0, m0, v0 = si.optimizer_state(n, seed=3)
+    th, m, v = theta0.to(DEV), m0.to(DEV), v0.to(DEV)
+    kw = dict(lr=2.0 / 1024, beta1=0.9, beta2=0.95, eps=1e-8, eps_root=0.0, weight_decay=0.0,
+              grad_scale=1.0 / w.B, sq_scale=1.0 / w.B, step=1, B=w.B)
+    pex.pex_adam_update(th, m, v, S_id.view(-1), S_sq.view(-1), "microadam", pex.AdamParams(**kw))
+    torch.cuda.synchronize()
+    st = oracle.stat(si.widen(X), si.widen(G))
+    rth, rm, rv = ou.adam_family_step(theta0.double().numpy(), m0.double().numpy(), v0.double().numpy(),
+                                      st.S_id.ravel(), st.S_sq.ravel(), ou.MICROADAM, ou.AdamParams(**kw))
+    np.testing.assert_allclose(v.cpu().double().numpy(), rv, rtol=1e-4)
+    d_ref, d_got = rth - theta0.double().numpy(), th.cpu().double().numpy() - theta0.double().numpy()
+    assert np.abs(d_got - d_ref).max() <= 1e-3 * np.abs(d_ref).max()

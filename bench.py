@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-example gradient statistic hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input for the 1B-scale layer pair
+(B=16, T=2048, 2048x8192 and 8192x2048, bf16): for each of the two layers
+    S_id  = pex_stat(identity),  S_sq = pex_stat(square)  ->  pex_adam_update(MicroAdam)
+    S_sgn = pex_stat(sign)                                 ->  pex_signsgd_update
+    S_tok = pex_token_sq
+Inputs are resident in HBM before the timed region.  `value` is the contraction work of the step
+(2*B*T*din*dout FLOP per statistic) divided by the wall time of the step, in TFLOP/s.
+
+Prints ONE JSON line.  `roofline` is measured live with HIP events around every launch of the dominant
+kernel (the phi = square contraction) on the stream it runs on; `cpu_baseline` times the fp64 oracle on a
+bounded sample of the same workload on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "per-example-stat TFLOP/s (Σ_b φ(X_bᵀG_b)) and % of MI355X MFMA peak"
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0
+
+LAYER_SETS = {
+    "c4_1b": ["c4_1b_up", "c4_1b_down"],
+    "c5_long": ["c5_long"],
+    "c3_gpt2": ["c3_gpt2_qkv", "c3_gpt2_proj", "c3_gpt2_fc", "c3_gpt2_fcproj"],
+    "c2_mlp_in": ["c2_mlp_in"],
+}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c4_1b", choices=sorted(LAYER_SETS))
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (per-example statistics shard over the batch axis, "
+              "one all-reduce of S per statistic; no multi-GPU path is built). Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2510_00236_amd as pex
+    import synth_inputs as si
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; libpex has no CPU path", file=sys.stderr)
+        return 2
+    pex.lib()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    layers = []
+    for name in LAYER_SETS[args.workload]:
+        w = si.WORKLOADS[name]
+        X, G = si.make(w, seed=args.seed)
+        n = w.din * w.dout
+        theta, m, v = si.optimizer_state(n, seed=args.seed)
+        L = dict(w=w, X=X.to(dev), G=G.to(dev), n=n,
+                 theta=theta.to(dev), m=m.to(dev), v=v.to(dev),
+                 theta_s=theta.to(dev), m_s=torch.zeros(n, device=dev),
+                 S_id=torch.empty(w.din, w.dout, device=dev), S_sq=torch.empty(w.din, w.dout, device=dev),
+                 S_sg=torch.empty(w.din, w.dout, device=dev), S_tk=torch.empty(w.din, w.dout, device=dev))
+        ws = max(pex.pex_stat_workspace_bytes(w.B, w.T, w.din, w.dout, pex.PEX_BF16, p) for p in ("identity", "square", "sign"))
+        ws = max(ws, pex.pex_token_sq_workspace_bytes(w.B, w.T, w.din, w.dout, pex.PEX_BF16))
+        L["ws"] = torch.empty(max(ws, 16), dtype=torch.uint8, device=dev)
+        L["keep_cpu"] = (X, G) if name == LAYER_SETS[args.workload][0] else None
+        layers.append(L)
+    torch.cuda.synchronize()
+
+    sq_events = []          # (start, stop) around every launch of the phi = square contraction
+    upd_events = []
+
+    def step(t: int, record: bool):
+        for L in layers:
+            w = L["w"]
+            pex.pex_stat(L["X"], L["G"], "identity", S=L["S_id"], workspace=L["ws"])
+            if record:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+            pex.pex_stat(L["X"], L["G"], "square", S=L["S_sq"], workspace=L["ws"])
+            if record:
+                e1.record()
+                sq_events.append((e0, e1, w))
+            p = pex.AdamParams(lr=2.0 / 1024, beta1=0.9, beta2=0.95, eps=1e-8, eps_root=0.0, weight_decay=0.0,
+                               grad_scale=1.0 / w.B, sq_scale=1.0 / w.B, step=t, B=w.B)
+            if record:
+                u0, u1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                u0.record()
+            pex.pex_adam_update(L["theta"], L["m"], L["v"], L["S_id"].view(-1), L["S_sq"].view(-1), "microadam", p)
+            if record:
+                u1.record()
+                upd_events.append((u0, u1, w))
+            pex.pex_stat(L["X"], L["G"], "sign", S=L["S_sg"], workspace=L["ws"])
+            pex.pex_signsgd_update(L["theta_s"], L["m_s"], L["S_sg"].view(-1), 3.47e-3, 0.9, 0.0, w.B, False, t)
+            pex.pex_token_sq(L["X"], L["G"], S=L["S_tk"], workspace=L["ws"])
+
+    for t in range(1, args.warmup + 1):
+        step(t, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(args.warmup + 1, args.warmup + args.steps + 1):
+        step(t, True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    flop_per_stat = [2.0 * L["w"].B * L["w"].T * L["w"].din * L["w"].dout for L in layers]
+    flop_per_step = 4.0 * sum(flop_per_stat)          # identity, square, sign, per-token square
+    ms_per_step = elapsed / args.steps * 1e3
+    value = flop_per_step / (elapsed / args.steps) / 1e12
+
+    # ---- roofline of the dominant kernel: the phi = square contraction, per launch
+    sq_ms = [a.elapsed_time(b) for a, b, _ in sq_events]
+    sq_flop = [2.0 * w.B * w.T * w.din * w.dout for _, _, w in sq_events]
+    sq_avg_ms = sum(sq_ms) / len(sq_ms)
+    achieved = (sum(sq_flop) / len(sq_flop)) / (sq_avg_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "stat_mfma_kernel<square> (pex_stat phi=square)",
+                "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "avg_launch_ms": round(sq_avg_ms, 4),
+                "launches": len(sq_ms), "traffic": None}
+    upd_ms = [a.elapsed_time(b) for a, b, _ in upd_events]
+    upd_bytes = [32.0 * w.din * w.dout for _, _, w in upd_events]
+    upd_gbs = (sum(upd_bytes) / len(upd_bytes)) / (sum(upd_ms) / len(upd_ms) * 1e-3) / 1e9
+    update_roofline = {"bound": "hbm", "kernel": "adam_update_kernel<microadam>", "achieved": round(upd_gbs, 1),
+                       "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(upd_gbs / PEAK_HBM_GBS, 4),
+                       "avg_launch_ms": round(sum(upd_ms) / len(upd_ms), 4)}
+
+    # ---- CPU baseline: the fp64 oracle as it stands, on a bounded sample of the first layer
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        X, G = layers[0]["keep_cpu"]
+        w = layers[0]["w"]
+        per_example = 2.0 * w.T * w.din * w.dout
+        # pilot on a thin slice to learn this host's rate, then size the sample for ~cpu_seconds of work
+        pr = min(w.din, 128)
+        Xp, Gp = si.widen(X[:1, :, :pr]), si.widen(G[:1])
+        c0 = time.perf_counter()
+        oracle.stat(Xp, Gp)
+        rate = 2.0 * w.T * pr * w.dout / (time.perf_counter() - c0)
+        budget = args.cpu_seconds * rate
+        nb = max(1, min(w.B, int(budget / per_example)))
+        rows = w.din
+        if nb == 1 and per_example > 2 * budget:
+            rows = max(64, int(w.din * budget / per_example) // 64 * 64)
+        Xs, Gs = si.widen(X[:nb, :, :rows]), si.widen(G[:nb])
+        c0 = time.perf_counter()
+        oracle.stat(Xs, Gs)
+        cs = time.perf_counter() - c0
+        cpu = {"value": round(2.0 * nb * w.T * rows * w.dout / cs / 1e12, 6), "unit": "TFLOP/s",
+               "cores": oracle.num_threads(), "kind": "oracle", "seconds": round(cs, 2),
+               "sample": f"{w.name}: first {nb} of {w.B} examples, {rows} of {w.din} rows of S, all three phi in "
+                         f"one fp64 pass (identity, square, sign)"}
+
+    out = {
+        "metric": METRIC, "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
+        "config": {"workload": args.workload, "layers": [L["w"].name for L in layers],
+                   "B": layers[0]["w"].B, "T": layers[0]["w"].T,
+                   "shapes": [[L["w"].din, L["w"].dout] for L in layers],
+                   "step": "per layer: pex_stat identity+square -> MicroAdam update; pex_stat sign -> MicroSignSGD update; pex_token_sq",
+                   "flop_per_step": flop_per_step, "seed": args.seed},
+        "roofline": roofline, "update_roofline": update_roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out, ensure_ascii=False))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -20,16 +20,21 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
     // PEX_FORCE_GENERIC=1 routes bf16 through the SIMT kernel (a tuning/debugging aid, not a fallback:
     // both kernels are device code of this library).
     const bool force_generic = env_int("PEX_FORCE_GENERIC", 0) != 0;
-    p.variant = env_int("PEX_MFMA_VARIANT", -1);
-    if (p.variant < 0) p.variant = 0;
-    p.kernel = (dt == PEX_BF16 && !force_generic && mfma_bf16_supports(B, T, din, dout, mode, p.variant)) ? 1 : 0;
+    // PEX_MFMA_VARIANT: 0 = register-staged kernel only, anything else = direct-to-LDS kernel where it applies
+    p.variant = env_int("PEX_MFMA_VARIANT", 1);
+    p.kernel = 0;
+    if (dt == PEX_BF16 && !force_generic) {
+        if (p.variant != 0 && dma_bf16_supports(B, T, din, dout, mode)) p.kernel = 2;
+        else if (mfma_bf16_supports(B, T, din, dout, mode, 0)) p.kernel = 1;
+    }
 
     // The unit the batch axis is split in: whole examples when phi is applied per example (the sum over
     // the sequence must be complete before phi), slabs of 64 rows of the flattened [B*T] axis otherwise.
     int64_t tiles, target, units;
-    if (p.kernel == 1) {
+    if (p.kernel != 0) {
         int bm, bn;
-        mfma_tile_shape(p.variant, mode, &bm, &bn);
+        if (p.kernel == 2) dma_tile_shape(mode, &bm, &bn);
+        else mfma_tile_shape(0, mode, &bm, &bn);
         tiles = ((din + bm - 1) / bm) * ((dout + bn - 1) / bn);
         target = 256;    // one workgroup per compute unit
     } else {
@@ -74,7 +79,8 @@ static pex_status run_stat(const void* X, const void* G, int64_t B, int64_t T, i
         out = (float*)workspace;
     }
     hipError_t e;
-    if (plan.kernel == 1) e = launch_stat_mfma_bf16(X, G, B, T, din, dout, mode, plan, out, stream);
+    if (plan.kernel == 2) e = launch_stat_dma_bf16(X, G, B, T, din, dout, mode, plan, out, stream);
+    else if (plan.kernel == 1) e = launch_stat_mfma_bf16(X, G, B, T, din, dout, mode, plan, out, stream);
     else e = launch_stat_generic(X, G, B, T, din, dout, dt, mode, plan, out, stream);
     if (e != hipSuccess) return PEX_ERR_HIP;
     if (plan.nsplit > 1) {

@@ -17,7 +17,7 @@ enum Mode : int { MODE_IDENTITY = 0, MODE_SQUARE = 1, MODE_SIGN = 2, MODE_TOKEN_
 // How one call is carried out.  Chosen on the host from the shape alone, so the workspace query and
 // the launch always agree.
 struct StatPlan {
-    int kernel;        // 0 = generic SIMT kernel, 1 = bf16 MFMA kernel
+    int kernel;        // 0 = generic SIMT kernel, 1 = bf16 MFMA kernel (register-staged), 2 = bf16 MFMA kernel (direct-to-LDS)
     int nsplit;        // number of groups the batch (or, for plain contractions, B*T) is split into
     int64_t per_split; // examples (or rows of B*T) per group
     int variant;       // tile variant of the MFMA kernel
@@ -33,6 +33,10 @@ hipError_t launch_stat_mfma_bf16(const void* X, const void* G, int64_t B, int64_
                                  Mode mode, const StatPlan& plan, float* out, hipStream_t stream);
 bool mfma_bf16_supports(int64_t B, int64_t T, int64_t din, int64_t dout, Mode mode, int variant);
 void mfma_tile_shape(int variant, Mode mode, int* bm, int* bn);
+hipError_t launch_stat_dma_bf16(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout,
+                                Mode mode, const StatPlan& plan, float* out, hipStream_t stream);
+bool dma_bf16_supports(int64_t B, int64_t T, int64_t din, int64_t dout, Mode mode);
+void dma_tile_shape(Mode mode, int* bm, int* bn);
 
 // S[e] = sum_{s < nsplit} partial[s][e], s ascending (fixed order => deterministic).
 hipError_t launch_reduce_partials(const float* partial, int nsplit, int64_t n, float* S, hipStream_t stream);

@@ -1,0 +1,318 @@
+// pex_stat_dma.hip -- bf16 MFMA kernel for S = sum_b phi(X_b^T G_b), direct-to-LDS variant (gfx950).
+//
+// Same mathematics as pex_stat_mfma.hip (Sec. 2.3: contract over the sequence, apply phi to the complete
+// per-example gradient tile in registers, sum over the batch), different data path:
+//   * 8 waves per workgroup, two per SIMD, so one wave's LDS waits, phi fold and barrier overlap the other
+//     wave's MFMAs.  A wave owns a WM x WN sub-tile; with 64 x 64 both fp32 register tiles (running M_b and
+//     sum of phi) fit in the 256 registers a wave gets at that occupancy.
+//   * Slabs of BK tokens go HBM -> LDS with buffer_load_dwordx4 ... lds: no VGPR staging, no LDS write
+//     instructions.  Out-of-range lanes of a buffer load write zeros, which gives the zero fill of ragged
+//     slab rows (via num_records of a per-slab descriptor) and ragged tile columns (via a poisoned lane
+//     offset) without a branch.
+//   * Each such instruction writes 1 KiB contiguous, so rows cannot be padded; instead the 16-byte chunks
+//     of slab row r are stored at chunk index c ^ 4*(r mod 4).  The transposing read ds_read_b64_tr_b16 of a
+//     16-lane group touches 4 consecutive rows x 32 bytes; the swizzle puts those in 4 different 64-byte
+//     bank groups.
+//   * NS slabs form a ring in LDS; loads run NS-1 slabs ahead of the MFMAs; one barrier per slab.
+#include "pex_internal.h"
+
+namespace pex {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) short short4_t;
+typedef __attribute__((ext_vector_type(8))) short short8_t;
+typedef __attribute__((ext_vector_type(16))) float float16_t;
+typedef __attribute__((ext_vector_type(4))) int int4_t;
+typedef short4_t __attribute__((address_space(3)))* lds_v4;
+typedef __attribute__((address_space(3))) void* lds_void;
+
+// One direct-to-LDS load: every lane fetches 16 bytes at (descriptor base + voff) and the wave's 1 KiB lands at
+// LDS byte address lds_addr + lane*16; lanes whose offset is outside the descriptor's range write zeros.
+// Issued as inline assembly so that the compiler does not serialise it against the LDS reads that follow
+// (it cannot tell that they touch a different slab of the ring); completion is tracked by hand with vmcnt.
+__device__ __forceinline__ void dma_load_16(uint32_t lds_addr, uint32_t voff, int4_t rsrc)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(rsrc)
+                 : "memory", "m0");
+}
+
+__device__ __forceinline__ int4_t make_rsrc(const void* base, uint32_t num_records)
+{
+    const uint64_t a = (uint64_t)base;
+    int4_t r;
+    r[0] = (int)(uint32_t)a;
+    r[1] = (int)((uint32_t)(a >> 32) & 0xffffu);     // stride 0, no swizzle
+    r[2] = (int)num_records;
+    r[3] = 0x00020000;                               // raw buffer, 32-bit data format
+    return r;
+}
+
+template <int BM_, int BN_, int WM_, int WN_, int BK_, int NS_>
+struct DmaTile {
+    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, BK = BK_, NS = NS_;
+    static constexpr int FM = WM / 32, FN = WN / 32;
+    static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN, NWAVES = WAVES_M * WAVES_N, NT = NWAVES * 64;
+    static constexpr int XROW = BM * 2, GROW = BN * 2;                 // bytes per slab row
+    static constexpr int X_BYTES = BK * XROW, G_BYTES = BK * GROW, STAGE = X_BYTES + G_BYTES;
+    static constexpr int LDS_BYTES = NS * STAGE;
+    static constexpr int NXI = X_BYTES / 1024 / NWAVES, NGI = G_BYTES / 1024 / NWAVES;   // loads per wave per slab
+    static constexpr int LPS = NXI + NGI;
+    static constexpr int RX = 1024 / XROW, RG = 1024 / GROW;           // slab rows covered by one load
+    static_assert(NWAVES == 8, "eight waves per workgroup");
+    static_assert(X_BYTES % (1024 * NWAVES) == 0 && G_BYTES % (1024 * NWAVES) == 0, "slab must divide over the waves");
+    static_assert(BK % 16 == 0 && XROW <= 1024 && GROW <= 1024, "tile limits");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS ring too large");
+};
+
+__device__ __forceinline__ void wait_vmcnt(int n)
+{
+    // s_waitcnt vmcnt(n) only (expcnt and lgkmcnt left at their maxima); gfx9 encoding
+    switch (n) {
+#define PEX_W(N) case N: __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (7 << 4) | (15 << 8) | (((N) >> 4) << 14)); break;
+        PEX_W(0) PEX_W(1) PEX_W(2) PEX_W(3) PEX_W(4) PEX_W(5) PEX_W(6) PEX_W(7) PEX_W(8) PEX_W(9) PEX_W(10) PEX_W(11)
+        PEX_W(12) PEX_W(13) PEX_W(14) PEX_W(15) PEX_W(16) PEX_W(18) PEX_W(20) PEX_W(24) PEX_W(30)
+#undef PEX_W
+    default: __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8)); break;
+    }
+}
+
+template <int MODE>
+__device__ __forceinline__ void fold_tile(float16_t& acc2, float16_t& acc)
+{
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const float m = acc[r];
+        if (MODE == MODE_SQUARE) acc2[r] = fmaf(m, m, acc2[r]);
+        else acc2[r] += (float)((m > 0.f) - (m < 0.f));
+        acc[r] = 0.f;
+    }
+}
+
+// Workgroup id -> (split, tile_m, tile_n): undo the round-robin assignment of consecutive ids to the 8 XCDs,
+// then walk tiles in groups of GROUP_M tile rows so the workgroups resident on one XCD form a compact patch.
+__device__ __forceinline__ void map_workgroup(int tiles_m, int tiles_n, int& split, int& tm, int& tn)
+{
+    const int n = gridDim.x, id = blockIdx.x;
+    const int xcd = id % 8, local = id / 8;
+    const int base = n / 8, rem = n % 8;
+    const int nid = xcd * base + (xcd < rem ? xcd : rem) + local;
+    const int tiles = tiles_m * tiles_n;
+    split = nid / tiles;
+    const int q = nid - split * tiles;
+    constexpr int GROUP_M = 4;
+    const int per_group = GROUP_M * tiles_n;
+    const int group = q / per_group;
+    const int first_m = group * GROUP_M;
+    const int gm = (tiles_m - first_m) < GROUP_M ? (tiles_m - first_m) : GROUP_M;
+    const int r = q - group * per_group;
+    tm = first_m + r % gm;
+    tn = r / gm;
+}
+
+template <typename TL, int MODE>
+__global__ __launch_bounds__(TL::NT, 1) void stat_dma_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ G,
+                                                             int64_t rows_total, int seg_len, int din, int dout,
+                                                             int64_t rows_per_split, int tiles_m, int tiles_n,
+                                                             float* __restrict__ out)
+{
+    constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK, NS = TL::NS, FM = TL::FM, FN = TL::FN;
+    constexpr int XROW = TL::XROW, GROW = TL::GROW, NXI = TL::NXI, NGI = TL::NGI, RX = TL::RX, RG = TL::RG;
+    constexpr bool PER_EXAMPLE = (MODE == MODE_SQUARE || MODE == MODE_SIGN);
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+
+    int split, tm, tn;
+    map_workgroup(tiles_m, tiles_n, split, tm, tn);
+    const int i0 = tm * BM, j0 = tn * BN;
+    const int64_t row_begin = (int64_t)split * rows_per_split;
+    int64_t row_end = row_begin + rows_per_split;
+    if (row_end > rows_total) row_end = rows_total;
+    const int slen = PER_EXAMPLE ? seg_len : (int)(row_end - row_begin);   // segment: one example, or the whole range
+    const int nseg = PER_EXAMPLE ? (int)((row_end - row_begin) / seg_len) : 1;
+    const int nst = (slen + BK - 1) / BK;
+    const int total = nseg * nst;
+
+    const int tid = threadIdx.x, lane = tid % 64;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void)lds;
+    const int wm = wave / TL::WAVES_N, wn = wave % TL::WAVES_N;
+
+    // ---- loader geometry.  Load q of a slab (q = wave*NXI + n) fills LDS bytes [q*1024, q*1024+1024) of the X
+    // part: slab rows q*RX .. q*RX+RX-1.  Lane L fills 16-byte slot (L mod XROW/16) of row q*RX + L/(XROW/16)
+    // with global chunk c = slot ^ 4*(row mod 4).
+    uint32_t xoff[NXI], goff[NGI];
+#pragma unroll
+    for (int n = 0; n < NXI; ++n) {
+        const int q = wave * NXI + n, r = q * RX + lane / (XROW / 16), slot = lane % (XROW / 16);
+        const int c = slot ^ (4 * (r & 3));
+        xoff[n] = (i0 + c * 8 < din) ? (uint32_t)(r * din + c * 8) * 2u : 0x80000000u;
+    }
+#pragma unroll
+    for (int n = 0; n < NGI; ++n) {
+        const int q = wave * NGI + n, r = q * RG + lane / (GROW / 16), slot = lane % (GROW / 16);
+        const int c = slot ^ (4 * (r & 3));
+        goff[n] = (j0 + c * 8 < dout) ? (uint32_t)(r * dout + c * 8) * 2u : 0x80000000u;
+    }
+    const int din_avail = din - i0, dout_avail = dout - j0;   // columns of this tile that exist
+
+    // issue the loads of slab g (all OOB -> zeros if g >= total, so every wave always has LPS loads per slab)
+    auto issue = [&](int g) {
+        int valid = 0;
+        int64_t rbase = 0;
+        if (g < total) {
+            const int seg = g / nst, off = (g - seg * nst) * BK;
+            rbase = row_begin + (int64_t)seg * slen + off;
+            valid = (slen - off) < BK ? (slen - off) : BK;
+        }
+        const uint32_t bx = lds_base + (uint32_t)((g % NS) * TL::STAGE);
+        const uint32_t bg = bx + TL::X_BYTES;
+        // descriptor: base at the tile's first column of slab row 0; num_records ends with the last valid row
+        const uint32_t nrx = valid > 0 ? (uint32_t)(((int64_t)(valid - 1) * din + din_avail) * 2) : 0u;
+        const uint32_t nrg = valid > 0 ? (uint32_t)(((int64_t)(valid - 1) * dout + dout_avail) * 2) : 0u;
+        const int4_t rx = make_rsrc(X + rbase * din + i0, nrx);
+        const int4_t rg = make_rsrc(G + rbase * dout + j0, nrg);
+#pragma unroll
+        for (int n = 0; n < NXI; ++n) dma_load_16(bx + (uint32_t)((wave * NXI + n) * 1024), xoff[n], rx);
+#pragma unroll
+        for (int n = 0; n < NGI; ++n) dma_load_16(bg + (uint32_t)((wave * NGI + n) * 1024), goff[n], rg);
+    };
+
+    // ---- fragment geometry for ds_read_b64_tr_b16 (lane i of a 16-lane group supplies row i/4, cols 4*(i%4)..+3
+    // and receives column i, rows 0..3).  Row r = 16*ks + 8*(blk/2) + 4*h + li/4, so r mod 4 = li/4.
+    const int blk = lane / 16, li = lane % 16;
+    const int frow = 8 * (blk / 2) + li / 4;
+    const int sw = 4 * (li / 4);                                    // swizzle term of this lane's rows
+    const int low = 2 * (blk % 2) * 16 + (li % 4) * 8;              // bytes: chunk 2*(blk%2) + (li%4)/2, half (li%4)%2
+    int a_addr[FM], b_addr[FN];
+#pragma unroll
+    for (int a = 0; a < FM; ++a) a_addr[a] = frow * XROW + ((((wm * TL::WM + a * 32) / 8) ^ sw) * 16) + low;
+#pragma unroll
+    for (int c = 0; c < FN; ++c) b_addr[c] = frow * GROW + ((((wn * TL::WN + c * 32) / 8) ^ sw) * 16) + low;
+
+    float16_t acc[FM][FN], acc2[FM][FN];
+#pragma unroll
+    for (int a = 0; a < FM; ++a)
+#pragma unroll
+        for (int c = 0; c < FN; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { acc[a][c][r] = 0.f; acc2[a][c][r] = 0.f; }
+
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s) issue(s);
+
+    int st_in_seg = 0;
+    for (int g = 0; g < total; ++g) {
+        wait_vmcnt((NS - 2) * TL::LPS);      // this wave's part of slab g has landed
+        __builtin_amdgcn_s_barrier();         // everyone's part has; everyone is done reading slab g-1
+        issue(g + NS - 1);                    // refill the buffer slab g-1 used
+        const unsigned char* bx = lds + (g % NS) * TL::STAGE;
+        const unsigned char* bg = bx + TL::X_BYTES;
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8_t af[FM], bfr[FN];
+#pragma unroll
+            for (int a = 0; a < FM; ++a) {
+                const unsigned char* p = bx + a_addr[a] + ks * 16 * XROW;
+                const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p));
+                const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p + 4 * XROW));
+                af[a] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            }
+#pragma unroll
+            for (int c = 0; c < FN; ++c) {
+                const unsigned char* p = bg + b_addr[c] + ks * 16 * GROW;
+                const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p));
+                const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p + 4 * GROW));
+                bfr[c] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            }
+#pragma unroll
+            for (int a = 0; a < FM; ++a)
+#pragma unroll
+                for (int c = 0; c < FN; ++c)
+                    acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[c], acc[a][c], 0, 0, 0);
+        }
+        if (PER_EXAMPLE) {
+            if (++st_in_seg == nst) {
+                st_in_seg = 0;
+#pragma unroll
+                for (int a = 0; a < FM; ++a)
+#pragma unroll
+                    for (int c = 0; c < FN; ++c) fold_tile<MODE>(acc2[a][c], acc[a][c]);
+            }
+        }
+    }
+    wait_vmcnt(0);   // drain the (all out-of-range) loads issued past the end before the LDS is released
+
+    // ---- epilogue: lane holds column (lane%32), rows 8*(r/4) + 4*(lane/32) + r%4 of each 32x32 tile
+    float* dst = out + (int64_t)split * din * dout;
+    const int jn = lane % 32, ib = 4 * (lane / 32);
+#pragma unroll
+    for (int a = 0; a < FM; ++a)
+#pragma unroll
+        for (int c = 0; c < FN; ++c) {
+            const int j = j0 + wn * TL::WN + c * 32 + jn;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int i = i0 + wm * TL::WM + a * 32 + 8 * (r / 4) + ib + (r % 4);
+                if (i < din && j < dout) dst[(int64_t)i * dout + j] = PER_EXAMPLE ? acc2[a][c][r] : acc[a][c][r];
+            }
+        }
+}
+
+// per-example phi: 256 x 128 block, 64 x 64 per wave; plain contraction: 256 x 256 block, 128 x 64 per wave
+using TilePhi = DmaTile<256, 128, 64, 64, 64, 3>;
+using TileId = DmaTile<256, 256, 128, 64, 32, 4>;
+
+template <typename TL, int MODE>
+hipError_t launch_one(const uint16_t* X, const uint16_t* G, int64_t B, int64_t T, int64_t din, int64_t dout,
+                      const StatPlan& plan, float* out, hipStream_t stream)
+{
+    constexpr bool PER_EXAMPLE = (MODE == MODE_SQUARE || MODE == MODE_SIGN);
+    const int tiles_m = (int)((din + TL::BM - 1) / TL::BM), tiles_n = (int)((dout + TL::BN - 1) / TL::BN);
+    const int64_t rows_per_split = PER_EXAMPLE ? plan.per_split * T : plan.per_split;
+    auto kern = stat_dma_kernel<TL, MODE>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const dim3 grid((unsigned)(tiles_m * tiles_n * plan.nsplit)), block(TL::NT);
+    kern<<<grid, block, TL::LDS_BYTES, stream>>>(X, G, B * T, (int)T, (int)din, (int)dout, rows_per_split, tiles_m,
+                                                 tiles_n, out);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+void dma_tile_shape(Mode mode, int* bm, int* bn)
+{
+    if (mode == MODE_IDENTITY) { *bm = TileId::BM; *bn = TileId::BN; }
+    else { *bm = TilePhi::BM; *bn = TilePhi::BN; }
+}
+
+bool dma_bf16_supports(int64_t B, int64_t T, int64_t din, int64_t dout, Mode mode)
+{
+    if (mode == MODE_TOKEN_SQ) return false;            // squares are formed on the register path
+    if (din % 8 != 0 || dout % 8 != 0 || din < 32 || dout < 32 || B * T < 16) return false;
+    // per-slab descriptors and lane offsets are 32-bit byte counts: one slab of rows must stay below 2 GiB
+    const int64_t bk = 64;
+    if (bk * din * 2 >= ((int64_t)1 << 31) || bk * dout * 2 >= ((int64_t)1 << 31)) return false;
+    return true;
+}
+
+hipError_t launch_stat_dma_bf16(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout, Mode mode,
+                                const StatPlan& plan, float* out, hipStream_t stream)
+{
+    const uint16_t* x = (const uint16_t*)X;
+    const uint16_t* g = (const uint16_t*)G;
+    switch (mode) {
+    case MODE_IDENTITY: return launch_one<TileId, MODE_IDENTITY>(x, g, B, T, din, dout, plan, out, stream);
+    case MODE_SQUARE: return launch_one<TilePhi, MODE_SQUARE>(x, g, B, T, din, dout, plan, out, stream);
+    case MODE_SIGN: return launch_one<TilePhi, MODE_SIGN>(x, g, B, T, din, dout, plan, out, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace pex

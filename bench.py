@@ -128,7 +128,7 @@ def main() -> int:
     sq_flop = [2.0 * w.B * w.T * w.din * w.dout for _, _, w in sq_events]
     sq_avg_ms = sum(sq_ms) / len(sq_ms)
     achieved = (sum(sq_flop) / len(sq_flop)) / (sq_avg_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "stat_mfma_kernel<square> (pex_stat phi=square)",
+    roofline = {"bound": "mfma", "kernel": "stat_dma_kernel<square> (pex_stat phi=square)",
                 "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "avg_launch_ms": round(sq_avg_ms, 4),
                 "launches": len(sq_ms), "traffic": None}

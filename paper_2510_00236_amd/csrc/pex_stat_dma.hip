@@ -14,6 +14,8 @@
 //     16-lane group touches 4 consecutive rows x 32 bytes; the swizzle puts those in 4 different 64-byte
 //     bank groups.
 //   * NS slabs form a ring in LDS; loads run NS-1 slabs ahead of the MFMAs; one barrier per slab.
+#include <cstdlib>
+
 #include "pex_internal.h"
 
 namespace pex {
@@ -63,7 +65,7 @@ struct DmaTile {
     static constexpr int RX = 1024 / XROW, RG = 1024 / GROW;           // slab rows covered by one load
     static_assert(NWAVES == 8, "eight waves per workgroup");
     static_assert(X_BYTES % (1024 * NWAVES) == 0 && G_BYTES % (1024 * NWAVES) == 0, "slab must divide over the waves");
-    static_assert(BK % 16 == 0 && XROW <= 1024 && GROW <= 1024, "tile limits");
+    static_assert(BK % 32 == 0 && XROW <= 1024 && GROW <= 1024, "tile limits (an even number of k-steps per slab)");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS ring too large");
 };
 
@@ -199,39 +201,60 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_dma_kernel(const uint16_t* __r
 #pragma unroll
             for (int r = 0; r < 16; ++r) { acc[a][c][r] = 0.f; acc2[a][c][r] = 0.f; }
 
-#pragma unroll
-    for (int s = 0; s < NS - 1; ++s) issue(s);
-
-    int st_in_seg = 0;
-    for (int g = 0; g < total; ++g) {
-        wait_vmcnt((NS - 2) * TL::LPS);      // this wave's part of slab g has landed
-        __builtin_amdgcn_s_barrier();         // everyone's part has; everyone is done reading slab g-1
-        issue(g + NS - 1);                    // refill the buffer slab g-1 used
+    // ---- main loop.  Fragments are read one k-step ahead of the MFMAs that use them.  The barrier that makes
+    // slab g+1 visible sits before the last MFMA block of slab g, so the first fragments of slab g+1 are in
+    // flight while that block runs; the buffer of slab g is refilled (slab g+NS) right after the barrier, once
+    // every wave has its last fragments of slab g in registers.
+    constexpr int KS = BK / 16;
+    auto load_frags = [&](int g, int ks, bf16x8_t (&af)[FM], bf16x8_t (&bfr)[FN]) {
         const unsigned char* bx = lds + (g % NS) * TL::STAGE;
         const unsigned char* bg = bx + TL::X_BYTES;
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8_t af[FM], bfr[FN];
-#pragma unroll
-            for (int a = 0; a < FM; ++a) {
-                const unsigned char* p = bx + a_addr[a] + ks * 16 * XROW;
-                const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p));
-                const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p + 4 * XROW));
-                af[a] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-            }
-#pragma unroll
-            for (int c = 0; c < FN; ++c) {
-                const unsigned char* p = bg + b_addr[c] + ks * 16 * GROW;
-                const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p));
-                const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p + 4 * GROW));
-                bfr[c] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-            }
-#pragma unroll
-            for (int a = 0; a < FM; ++a)
-#pragma unroll
-                for (int c = 0; c < FN; ++c)
-                    acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[c], acc[a][c], 0, 0, 0);
+        for (int a = 0; a < FM; ++a) {
+            const unsigned char* p = bx + a_addr[a] + ks * 16 * XROW;
+            const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p));
+            const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p + 4 * XROW));
+            af[a] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         }
+#pragma unroll
+        for (int c = 0; c < FN; ++c) {
+            const unsigned char* p = bg + b_addr[c] + ks * 16 * GROW;
+            const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p));
+            const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p + 4 * GROW));
+            bfr[c] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        }
+    };
+    auto mfma_block = [&](const bf16x8_t (&af)[FM], const bf16x8_t (&bfr)[FN]) {
+#pragma unroll
+        for (int a = 0; a < FM; ++a)
+#pragma unroll
+            for (int c = 0; c < FN; ++c)
+                acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[c], acc[a][c], 0, 0, 0);
+    };
+
+    bf16x8_t fa[2][FM], fb[2][FN];
+    if (total > 0) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s) issue(s);
+        wait_vmcnt((NS - 1) * TL::LPS);       // this wave's part of slab 0 has landed
+        __builtin_amdgcn_s_barrier();
+        load_frags(0, 0, fa[0], fb[0]);
+    }
+    int st_in_seg = 0;
+    for (int g = 0; g < total; ++g) {
+#pragma unroll
+        for (int ks = 0; ks < KS - 1; ++ks) {
+            load_frags(g, ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
+            mfma_block(fa[ks & 1], fb[ks & 1]);
+        }
+        if (g + 1 < total) {
+            wait_vmcnt((NS - 2) * TL::LPS);   // this wave's part of slab g+1 has landed ...
+            __builtin_amdgcn_s_waitcnt(0xC07F); // ... and its last fragments of slab g are in registers (lgkmcnt(0))
+            __builtin_amdgcn_s_barrier();
+            issue(g + NS);                    // refill slab g's buffer
+            load_frags(g + 1, 0, fa[KS & 1], fb[KS & 1]);
+        }
+        mfma_block(fa[(KS - 1) & 1], fb[(KS - 1) & 1]);
         if (PER_EXAMPLE) {
             if (++st_in_seg == nst) {
                 st_in_seg = 0;
@@ -307,10 +330,26 @@ hipError_t launch_stat_dma_bf16(const void* X, const void* G, int64_t B, int64_t
 {
     const uint16_t* x = (const uint16_t*)X;
     const uint16_t* g = (const uint16_t*)G;
+    // PEX_DMA_CFG picks the slab depth / ring length (same tile shapes, so the plan is unaffected)
+    const char* e = getenv("PEX_DMA_CFG");
+    const int cfg = e ? atoi(e) : 0;
+    using TilePhi1 = DmaTile<256, 128, 64, 64, 32, 6>;
+    using TilePhi2 = DmaTile<256, 128, 64, 64, 32, 4>;
+    using TileId1 = DmaTile<256, 256, 128, 64, 64, 2>;
+    using TileId2 = DmaTile<256, 256, 128, 64, 32, 5>;
     switch (mode) {
-    case MODE_IDENTITY: return launch_one<TileId, MODE_IDENTITY>(x, g, B, T, din, dout, plan, out, stream);
-    case MODE_SQUARE: return launch_one<TilePhi, MODE_SQUARE>(x, g, B, T, din, dout, plan, out, stream);
-    case MODE_SIGN: return launch_one<TilePhi, MODE_SIGN>(x, g, B, T, din, dout, plan, out, stream);
+    case MODE_IDENTITY:
+        if (cfg == 1) return launch_one<TileId1, MODE_IDENTITY>(x, g, B, T, din, dout, plan, out, stream);
+        if (cfg == 2) return launch_one<TileId2, MODE_IDENTITY>(x, g, B, T, din, dout, plan, out, stream);
+        return launch_one<TileId, MODE_IDENTITY>(x, g, B, T, din, dout, plan, out, stream);
+    case MODE_SQUARE:
+        if (cfg == 1) return launch_one<TilePhi1, MODE_SQUARE>(x, g, B, T, din, dout, plan, out, stream);
+        if (cfg == 2) return launch_one<TilePhi2, MODE_SQUARE>(x, g, B, T, din, dout, plan, out, stream);
+        return launch_one<TilePhi, MODE_SQUARE>(x, g, B, T, din, dout, plan, out, stream);
+    case MODE_SIGN:
+        if (cfg == 1) return launch_one<TilePhi1, MODE_SIGN>(x, g, B, T, din, dout, plan, out, stream);
+        if (cfg == 2) return launch_one<TilePhi2, MODE_SIGN>(x, g, B, T, din, dout, plan, out, stream);
+        return launch_one<TilePhi, MODE_SIGN>(x, g, B, T, din, dout, plan, out, stream);
     default: return hipErrorInvalidValue;
     }
 }

@@ -1,0 +1,57 @@
+"""GPU parity at the full workload sizes, in the launch configuration bench.py times: the oracle evaluates the
+per-example gradients entry by entry at sampled output positions (tile corners, tile seams, the ragged last
+tile, and random positions), and every statistic is compared there."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2510_00236_amd as pex
+import synth_inputs as si
+from parity_util import assert_real_stat, assert_sign_stat, TOKEN_SQ_BF16_BAR
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _sample_positions(din, dout, n_random, seed):
+    rng = np.random.default_rng(seed)
+    ii = list(rng.integers(0, din, n_random))
+    jj = list(rng.integers(0, dout, n_random))
+    # seams of the 64/128/192/256-wide tiles the kernels use, first and last rows/columns
+    edges_i = sorted({0, 1, 31, 32, 63, 64, 127, 128, 255, 256, din // 2 - 1, din // 2, din - 257, din - 256, din - 2, din - 1} & set(range(din)))
+    edges_j = sorted({0, 1, 31, 32, 63, 64, 127, 128, 191, 192, 255, 256, dout // 2 - 1, dout // 2, dout - 129, dout - 128, dout - 2, dout - 1} & set(range(dout)))
+    for a in edges_i:
+        for b in edges_j:
+            ii.append(a)
+            jj.append(b)
+    return np.array(ii, dtype=np.int64), np.array(jj, dtype=np.int64)
+
+
+@pytest.mark.parametrize("name", ["c3_gpt2_qkv", "c3_gpt2_proj", "c3_gpt2_fc", "c3_gpt2_fcproj", "c4_1b_up", "c4_1b_down", "c5_long"])
+def test_full_size_sampled(name):
+    w = si.WORKLOADS[name]
+    X, G = si.make(w, seed=0)
+    Xd, Gd = X.to(DEV), G.to(DEV)
+    got = {phi: pex.pex_stat(Xd, Gd, phi) for phi in ("identity", "square", "sign")}
+    got["token_sq"] = pex.pex_token_sq(Xd, Gd)
+    torch.cuda.synchronize()
+    for k, v in got.items():
+        assert torch.isfinite(v).all(), f"{name} {k}: non-finite"
+    ii, jj = _sample_positions(w.din, w.dout, 3000, seed=1)
+    Xn, Gn = si.widen(X), si.widen(G)
+    st = oracle.stat_at(Xn, Gn, ii, jj)
+    tok = oracle.token_sq_at(Xn, Gn, ii, jj)
+    del Xn, Gn
+    pick = lambda t: t[torch.as_tensor(ii, device=DEV), torch.as_tensor(jj, device=DEV)].cpu().numpy().astype(np.float64)
+    assert_real_stat(pick(got["identity"]), st.S_id, "bf16", f"{name} identity", elementwise=False)
+    assert_real_stat(pick(got["square"]), st.S_sq, "bf16", f"{name} square", elementwise=True)
+    n_diff = assert_sign_stat(pick(got["sign"]), st.S_sign, st.amb, f"{name} sign")
+    assert_real_stat(pick(got["token_sq"]), tok, "bf16", f"{name} token_sq", elementwise=True, bar=TOKEN_SQ_BF16_BAR, eng=None)
+    # properties that hold at any size, over the whole output
+    S_sq, S_id, S_sg = got["square"], got["identity"], got["sign"]
+    assert (S_sq >= 0).all()
+    assert (S_sq * w.B >= S_id * S_id * (1 - 1e-4) - 1e-6 * S_sq.max()).all()      # Cauchy-Schwarz: nu_micro >= nu_adam
+    assert (S_sg.abs() <= w.B).all() and torch.equal(S_sg, S_sg.round())
+    assert ((S_sg.long() - w.B) % 2 == 0).float().mean() > 0.999                    # parity of B wherever no M_b is exactly 0
+    print(f"{name}: sign mismatches inside the ambiguity band: {n_diff}")

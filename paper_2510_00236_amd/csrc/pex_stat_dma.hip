@@ -26,6 +26,7 @@ typedef __attribute__((ext_vector_type(4))) short short4_t;
 typedef __attribute__((ext_vector_type(8))) short short8_t;
 typedef __attribute__((ext_vector_type(16))) float float16_t;
 typedef __attribute__((ext_vector_type(4))) int int4_t;
+typedef __attribute__((ext_vector_type(4))) unsigned int uint4_t;
 typedef short4_t __attribute__((address_space(3)))* lds_v4;
 typedef __attribute__((address_space(3))) void* lds_void;
 
@@ -79,6 +80,23 @@ __device__ __forceinline__ void wait_vmcnt(int n)
 #undef PEX_W
     default: __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8)); break;
     }
+    asm volatile("" ::: "memory");   // keep LDS reads of the landed slab below the wait at every compiler level
+}
+
+__device__ __forceinline__ void wait_lds_and_barrier()
+{
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wave's LDS reads and writes are complete
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+// two bf16 values -> squares in fp32 -> two bf16 (round to nearest even); zero stays zero
+__device__ __forceinline__ uint32_t square_pair_rne(uint32_t packed)
+{
+    const float lo = __uint_as_float(packed << 16), hi = __uint_as_float(packed & 0xffff0000u);
+    const __bf16 l2 = (__bf16)(lo * lo), h2 = (__bf16)(hi * hi);
+    return (uint32_t)__builtin_bit_cast(uint16_t, l2) | ((uint32_t)__builtin_bit_cast(uint16_t, h2) << 16);
 }
 
 template <int MODE>
@@ -181,6 +199,28 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_dma_kernel(const uint16_t* __r
         for (int n = 0; n < NGI; ++n) dma_load_16(bg + (uint32_t)((wave * NGI + n) * 1024), goff[n], rg);
     };
 
+    // Per-token square: the operands are squared in place in LDS, one slab ahead of the MFMAs.  Lane L squares the
+    // 16 bytes its own load put at slot L, so this needs only this wave's vmcnt wait; the end-of-slab barrier
+    // publishes the result.  Squares are formed in fp32 and rounded to bf16 (nearest even); zero fill stays zero.
+    auto square_chunks = [&](int g) {
+        typedef uint4_t __attribute__((address_space(3)))* lds_u4;
+        unsigned char* bx = lds + (g % NS) * TL::STAGE;
+        unsigned char* bg = bx + TL::X_BYTES;
+        uint4_t v[NXI + NGI];
+#pragma unroll
+        for (int n = 0; n < NXI; ++n) v[n] = *(lds_u4)(bx + (wave * NXI + n) * 1024 + lane * 16);
+#pragma unroll
+        for (int n = 0; n < NGI; ++n) v[NXI + n] = *(lds_u4)(bg + (wave * NGI + n) * 1024 + lane * 16);
+#pragma unroll
+        for (int n = 0; n < NXI + NGI; ++n)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[n][e] = square_pair_rne(v[n][e]);
+#pragma unroll
+        for (int n = 0; n < NXI; ++n) *(lds_u4)(bx + (wave * NXI + n) * 1024 + lane * 16) = v[n];
+#pragma unroll
+        for (int n = 0; n < NGI; ++n) *(lds_u4)(bg + (wave * NGI + n) * 1024 + lane * 16) = v[NXI + n];
+    };
+
     // ---- fragment geometry for ds_read_b64_tr_b16 (lane i of a 16-lane group supplies row i/4, cols 4*(i%4)..+3
     // and receives column i, rows 0..3).  Row r = 16*ks + 8*(blk/2) + 4*h + li/4, so r mod 4 = li/4.
     const int blk = lane / 16, li = lane % 16;
@@ -237,20 +277,24 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_dma_kernel(const uint16_t* __r
 #pragma unroll
         for (int s = 0; s < NS; ++s) issue(s);
         wait_vmcnt((NS - 1) * TL::LPS);       // this wave's part of slab 0 has landed
-        __builtin_amdgcn_s_barrier();
+        if (MODE == MODE_TOKEN_SQ) square_chunks(0);
+        wait_lds_and_barrier();
         load_frags(0, 0, fa[0], fb[0]);
     }
     int st_in_seg = 0;
     for (int g = 0; g < total; ++g) {
+        if (MODE == MODE_TOKEN_SQ && g + 1 < total) {
+            wait_vmcnt((NS - 2) * TL::LPS);   // this wave's part of slab g+1 has landed: square it while slab g is multiplied
+            square_chunks(g + 1);
+        }
 #pragma unroll
         for (int ks = 0; ks < KS - 1; ++ks) {
             load_frags(g, ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
             mfma_block(fa[ks & 1], fb[ks & 1]);
         }
         if (g + 1 < total) {
-            wait_vmcnt((NS - 2) * TL::LPS);   // this wave's part of slab g+1 has landed ...
-            __builtin_amdgcn_s_waitcnt(0xC07F); // ... and its last fragments of slab g are in registers (lgkmcnt(0))
-            __builtin_amdgcn_s_barrier();
+            if (MODE != MODE_TOKEN_SQ) wait_vmcnt((NS - 2) * TL::LPS);   // this wave's part of slab g+1 has landed ...
+            wait_lds_and_barrier();           // ... and its LDS reads of slab g (and writes to slab g+1) are done
             issue(g + NS);                    // refill slab g's buffer
             load_frags(g + 1, 0, fa[KS & 1], fb[KS & 1]);
         }
@@ -285,7 +329,8 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_dma_kernel(const uint16_t* __r
 
 // per-example phi: 256 x 128 block, 64 x 64 per wave; plain contraction: 256 x 256 block, 128 x 64 per wave
 using TilePhi = DmaTile<256, 128, 64, 64, 64, 3>;
-using TileId = DmaTile<256, 256, 128, 64, 32, 4>;
+using TileId = DmaTile<256, 256, 128, 64, 64, 2>;
+using TileTok = DmaTile<256, 256, 128, 64, 32, 4>;
 
 template <typename TL, int MODE>
 hipError_t launch_one(const uint16_t* X, const uint16_t* G, int64_t B, int64_t T, int64_t din, int64_t dout,
@@ -311,13 +356,13 @@ hipError_t launch_one(const uint16_t* X, const uint16_t* G, int64_t B, int64_t T
 
 void dma_tile_shape(Mode mode, int* bm, int* bn)
 {
-    if (mode == MODE_IDENTITY) { *bm = TileId::BM; *bn = TileId::BN; }
+    if (mode == MODE_IDENTITY || mode == MODE_TOKEN_SQ) { *bm = TileId::BM; *bn = TileId::BN; }
     else { *bm = TilePhi::BM; *bn = TilePhi::BN; }
 }
 
 bool dma_bf16_supports(int64_t B, int64_t T, int64_t din, int64_t dout, Mode mode)
 {
-    if (mode == MODE_TOKEN_SQ) return false;            // squares are formed on the register path
+    (void)mode;
     if (din % 8 != 0 || dout % 8 != 0 || din < 32 || dout < 32 || B * T < 16) return false;
     // per-slab descriptors and lane offsets are 32-bit byte counts: one slab of rows must stay below 2 GiB
     const int64_t bk = 64;
@@ -335,13 +380,17 @@ hipError_t launch_stat_dma_bf16(const void* X, const void* G, int64_t B, int64_t
     const int cfg = e ? atoi(e) : 0;
     using TilePhi1 = DmaTile<256, 128, 64, 64, 32, 6>;
     using TilePhi2 = DmaTile<256, 128, 64, 64, 32, 4>;
-    using TileId1 = DmaTile<256, 256, 128, 64, 64, 2>;
+    using TileId1 = DmaTile<256, 256, 128, 64, 32, 4>;
     using TileId2 = DmaTile<256, 256, 128, 64, 32, 5>;
     switch (mode) {
     case MODE_IDENTITY:
         if (cfg == 1) return launch_one<TileId1, MODE_IDENTITY>(x, g, B, T, din, dout, plan, out, stream);
         if (cfg == 2) return launch_one<TileId2, MODE_IDENTITY>(x, g, B, T, din, dout, plan, out, stream);
         return launch_one<TileId, MODE_IDENTITY>(x, g, B, T, din, dout, plan, out, stream);
+    case MODE_TOKEN_SQ:
+        if (cfg == 1) return launch_one<TileId, MODE_TOKEN_SQ>(x, g, B, T, din, dout, plan, out, stream);
+        if (cfg == 2) return launch_one<TileId2, MODE_TOKEN_SQ>(x, g, B, T, din, dout, plan, out, stream);
+        return launch_one<TileTok, MODE_TOKEN_SQ>(x, g, B, T, din, dout, plan, out, stream);
     case MODE_SQUARE:
         if (cfg == 1) return launch_one<TilePhi1, MODE_SQUARE>(x, g, B, T, din, dout, plan, out, stream);
         if (cfg == 2) return launch_one<TilePhi2, MODE_SQUARE>(x, g, B, T, din, dout, plan, out, stream);

@@ -43,12 +43,37 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
     }
     const int64_t slab = 64;
     units = per_example ? B : (B * T + slab - 1) / slab;
-    int64_t nsplit = (target + tiles - 1) / tiles;
     const int max_split = env_int("PEX_MAX_SPLIT", 16);
-    if (nsplit > max_split) nsplit = max_split;
-    if (nsplit > units) nsplit = units;
-    if (nsplit < 1) nsplit = 1;
-    int64_t per = (units + nsplit - 1) / nsplit;
+    int64_t nsplit = 1, per = units;
+    if (p.kernel == 0) {
+        nsplit = (target + tiles - 1) / tiles;
+        if (nsplit > max_split) nsplit = max_split;
+        if (nsplit > units) nsplit = units;
+        if (nsplit < 1) nsplit = 1;
+        per = (units + nsplit - 1) / nsplit;
+    } else {
+        // One workgroup per compute unit runs at a time, so the contraction takes
+        //   rounds(ns) * ceil(units / ns)  unit-times,  rounds = ceil(tiles * ns / 256),
+        // and the fixed-order reduction of the partial sums reads ns copies of S.  Pick the cheapest ns.
+        // A unit-time is one example (or 64 rows) on one tile at ~4 TFLOP/s per compute unit; the reduction
+        // streams at ~4 TB/s.
+        int bm, bn;
+        if (p.kernel == 2) dma_tile_shape(mode, &bm, &bn);
+        else mfma_tile_shape(0, mode, &bm, &bn);
+        const double rows_per_unit = per_example ? (double)T : (double)slab;
+        const double t_unit = 2.0 * rows_per_unit * bm * bn / 4.0e12;
+        const double s_bytes = (double)din * (double)dout * 4.0;
+        double best = 0.0;
+        const int64_t lim = units < max_split ? units : max_split;
+        for (int64_t ns = 1; ns <= lim; ++ns) {
+            const int64_t pu = (units + ns - 1) / ns;
+            const int64_t ns_eff = (units + pu - 1) / pu;
+            const int64_t rounds = (tiles * ns_eff + target - 1) / target;
+            double cost = (double)rounds * (double)pu * t_unit;
+            if (ns_eff > 1) cost += (ns_eff + 1) * s_bytes / 4.0e12 + 3.0e-6;
+            if (ns == 1 || cost < best) { best = cost; nsplit = ns_eff; per = pu; }
+        }
+    }
     nsplit = (units + per - 1) / per;      // no empty group
     p.nsplit = (int)nsplit;
     p.per_split = per_example ? per : per * slab;

@@ -99,6 +99,20 @@ __device__ __forceinline__ uint32_t square_pair_rne(uint32_t packed)
     return (uint32_t)__builtin_bit_cast(uint16_t, l2) | ((uint32_t)__builtin_bit_cast(uint16_t, h2) << 16);
 }
 
+// sched_group_barrier sequence: MFMA number I of NM, followed by its share of the NR LDS reads
+template <int I, int NM, int NR>
+__device__ __forceinline__ void hint_step()
+{
+#ifndef PEX_NO_SCHED_HINT
+    if constexpr (I < NM) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        constexpr int n = (NR * (I + 1)) / NM - (NR * I) / NM;
+        if constexpr (n > 0) __builtin_amdgcn_sched_group_barrier(0x100, n, 0);
+        hint_step<I + 1, NM, NR>();
+    }
+#endif
+}
+
 template <int MODE>
 __device__ __forceinline__ void fold_tile(float16_t& acc2, float16_t& acc)
 {
@@ -272,6 +286,10 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_dma_kernel(const uint16_t* __r
                 acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[c], acc[a][c], 0, 0, 0);
     };
 
+    // Scheduling hint for one k-step (FM*FN MFMAs and 2*(FM+FN) transposing reads of the next k-step): alternate
+    // one MFMA with the reads that fit under it, so the wave keeps the matrix pipe and the LDS queue busy together.
+    auto interleave_hint = [&]() { hint_step<0, FM * FN, 2 * (FM + FN)>(); };
+
     bf16x8_t fa[2][FM], fb[2][FN];
     if (total > 0) {
 #pragma unroll
@@ -291,6 +309,7 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_dma_kernel(const uint16_t* __r
         for (int ks = 0; ks < KS - 1; ++ks) {
             load_frags(g, ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
             mfma_block(fa[ks & 1], fb[ks & 1]);
+            interleave_hint();
         }
         if (g + 1 < total) {
             if (MODE != MODE_TOKEN_SQ) wait_vmcnt((NS - 2) * TL::LPS);   // this wave's part of slab g+1 has landed ...
@@ -299,6 +318,7 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_dma_kernel(const uint16_t* __r
             load_frags(g + 1, 0, fa[KS & 1], fb[KS & 1]);
         }
         mfma_block(fa[(KS - 1) & 1], fb[(KS - 1) & 1]);
+        if (g + 1 < total) interleave_hint();
         if (PER_EXAMPLE) {
             if (++st_in_seg == nst) {
                 st_in_seg = 0;

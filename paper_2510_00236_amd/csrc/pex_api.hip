@@ -33,7 +33,7 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
     int64_t tiles, target, units;
     if (p.kernel != 0) {
         int bm, bn;
-        if (p.kernel == 2) dma_tile_shape(mode, &bm, &bn);
+        if (p.kernel == 2) dma_tile_shape(mode, B, &bm, &bn);
         else mfma_tile_shape(0, mode, &bm, &bn);
         tiles = ((din + bm - 1) / bm) * ((dout + bn - 1) / bn);
         target = 256;    // one workgroup per compute unit
@@ -58,7 +58,7 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
         // A unit-time is one example (or 64 rows) on one tile at ~4 TFLOP/s per compute unit; the reduction
         // streams at ~4 TB/s.
         int bm, bn;
-        if (p.kernel == 2) dma_tile_shape(mode, &bm, &bn);
+        if (p.kernel == 2) dma_tile_shape(mode, B, &bm, &bn);
         else mfma_tile_shape(0, mode, &bm, &bn);
         const double rows_per_unit = per_example ? (double)T : (double)slab;
         const double t_unit = 2.0 * rows_per_unit * bm * bn / 4.0e12;

@@ -12,7 +12,8 @@ namespace pex {
 
 // Which statistic a contraction kernel produces.  PHI_* match pex_phi; TOKEN_SQ is the per-token
 // square (operands squared on the load path, one plain contraction over K = B*T).
-enum Mode : int { MODE_IDENTITY = 0, MODE_SQUARE = 1, MODE_SIGN = 2, MODE_TOKEN_SQ = 3 };
+enum Mode : int { MODE_IDENTITY = 0, MODE_SQUARE = 1, MODE_SIGN = 2, MODE_TOKEN_SQ = 3,
+                  MODE_SIGN_PACKED = 4 /* kernel-internal: sign counts held as fp16 pairs */ };
 
 // How one call is carried out.  Chosen on the host from the shape alone, so the workspace query and
 // the launch always agree.
@@ -36,7 +37,7 @@ void mfma_tile_shape(int variant, Mode mode, int* bm, int* bn);
 hipError_t launch_stat_dma_bf16(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout,
                                 Mode mode, const StatPlan& plan, float* out, hipStream_t stream);
 bool dma_bf16_supports(int64_t B, int64_t T, int64_t din, int64_t dout, Mode mode);
-void dma_tile_shape(Mode mode, int* bm, int* bn);
+void dma_tile_shape(Mode mode, int64_t B, int* bm, int* bn);
 
 // S[e] = sum_{s < nsplit} partial[s][e], s ascending (fixed order => deterministic).
 hipError_t launch_reduce_partials(const float* partial, int nsplit, int64_t n, float* S, hipStream_t stream);

@@ -27,6 +27,7 @@ typedef __attribute__((ext_vector_type(8))) short short8_t;
 typedef __attribute__((ext_vector_type(16))) float float16_t;
 typedef __attribute__((ext_vector_type(4))) int int4_t;
 typedef __attribute__((ext_vector_type(4))) unsigned int uint4_t;
+typedef __attribute__((ext_vector_type(2))) _Float16 half2_t;
 typedef short4_t __attribute__((address_space(3)))* lds_v4;
 typedef __attribute__((address_space(3))) void* lds_void;
 
@@ -113,6 +114,13 @@ __device__ __forceinline__ void hint_step()
 #endif
 }
 
+// sign(m) in {-1, 0, +1} as a float without compares: scaling by 2^200 sends every non-zero value (denormals
+// included) beyond +-1 and keeps +-0 at 0, the median with -1 and +1 clamps it.
+__device__ __forceinline__ float sign_as_float(float m)
+{
+    return __builtin_amdgcn_fmed3f(__builtin_ldexpf(m, 200), -1.0f, 1.0f);
+}
+
 template <int MODE>
 __device__ __forceinline__ void fold_tile(float16_t& acc2, float16_t& acc)
 {
@@ -120,8 +128,20 @@ __device__ __forceinline__ void fold_tile(float16_t& acc2, float16_t& acc)
     for (int r = 0; r < 16; ++r) {
         const float m = acc[r];
         if (MODE == MODE_SQUARE) acc2[r] = fmaf(m, m, acc2[r]);
-        else acc2[r] += (float)((m > 0.f) - (m < 0.f));
+        else acc2[r] += sign_as_float(m);
         acc[r] = 0.f;
+    }
+}
+
+// Sign counts of a 32x32 MFMA tile held as 8 fp16 pairs per lane: integers up to 2048 are exact in fp16, so the
+// count of at most 2048 examples is exact, at half the registers of an fp32 tile.
+__device__ __forceinline__ void fold_tile_sign_packed(half2_t (&cnt)[8], float16_t& acc)
+{
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        cnt[r] += __builtin_bit_cast(half2_t, __builtin_amdgcn_cvt_pkrtz(sign_as_float(acc[2 * r]), sign_as_float(acc[2 * r + 1])));
+        acc[2 * r] = 0.f;
+        acc[2 * r + 1] = 0.f;
     }
 }
 
@@ -154,7 +174,8 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_dma_kernel(const uint16_t* __r
 {
     constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK, NS = TL::NS, FM = TL::FM, FN = TL::FN;
     constexpr int XROW = TL::XROW, GROW = TL::GROW, NXI = TL::NXI, NGI = TL::NGI, RX = TL::RX, RG = TL::RG;
-    constexpr bool PER_EXAMPLE = (MODE == MODE_SQUARE || MODE == MODE_SIGN);
+    constexpr bool PER_EXAMPLE = (MODE == MODE_SQUARE || MODE == MODE_SIGN || MODE == MODE_SIGN_PACKED);
+    constexpr bool PACKED = (MODE == MODE_SIGN_PACKED);
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
 
     int split, tm, tn;
@@ -247,13 +268,18 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_dma_kernel(const uint16_t* __r
 #pragma unroll
     for (int c = 0; c < FN; ++c) b_addr[c] = frow * GROW + ((((wn * TL::WN + c * 32) / 8) ^ sw) * 16) + low;
 
-    float16_t acc[FM][FN], acc2[FM][FN];
+    float16_t acc[FM][FN], acc2[PACKED ? 1 : FM][PACKED ? 1 : FN];
+    half2_t cnt[PACKED ? FM : 1][PACKED ? FN : 1][8];
 #pragma unroll
     for (int a = 0; a < FM; ++a)
 #pragma unroll
         for (int c = 0; c < FN; ++c)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) { acc[a][c][r] = 0.f; acc2[a][c][r] = 0.f; }
+            for (int r = 0; r < 16; ++r) {
+                acc[a][c][r] = 0.f;
+                if (!PACKED) acc2[a][c][r] = 0.f;
+                else cnt[a][c][r / 2] = half2_t{(_Float16)0, (_Float16)0};
+            }
 
     // ---- main loop.  Fragments are read one k-step ahead of the MFMAs that use them.  The barrier that makes
     // slab g+1 visible sits before the last MFMA block of slab g, so the first fragments of slab g+1 are in
@@ -325,7 +351,10 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_dma_kernel(const uint16_t* __r
 #pragma unroll
                 for (int a = 0; a < FM; ++a)
 #pragma unroll
-                    for (int c = 0; c < FN; ++c) fold_tile<MODE>(acc2[a][c], acc[a][c]);
+                    for (int c = 0; c < FN; ++c) {
+                        if constexpr (PACKED) fold_tile_sign_packed(cnt[a][c], acc[a][c]);
+                        else fold_tile<MODE>(acc2[a][c], acc[a][c]);
+                    }
             }
         }
     }
@@ -342,7 +371,11 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_dma_kernel(const uint16_t* __r
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int i = i0 + wm * TL::WM + a * 32 + 8 * (r / 4) + ib + (r % 4);
-                if (i < din && j < dout) dst[(int64_t)i * dout + j] = PER_EXAMPLE ? acc2[a][c][r] : acc[a][c][r];
+                float v;
+                if constexpr (PACKED) v = (float)cnt[a][c][r / 2][r % 2];
+                else if constexpr (PER_EXAMPLE) v = acc2[a][c][r];
+                else v = acc[a][c][r];
+                if (i < din && j < dout) dst[(int64_t)i * dout + j] = v;
             }
         }
 }
@@ -351,12 +384,13 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_dma_kernel(const uint16_t* __r
 using TilePhi = DmaTile<256, 128, 64, 64, 64, 3>;
 using TileId = DmaTile<256, 256, 128, 64, 64, 2>;
 using TileTok = DmaTile<256, 256, 128, 64, 32, 4>;
+using TileSgn = DmaTile<256, 256, 128, 64, 32, 4>;
 
 template <typename TL, int MODE>
 hipError_t launch_one(const uint16_t* X, const uint16_t* G, int64_t B, int64_t T, int64_t din, int64_t dout,
                       const StatPlan& plan, float* out, hipStream_t stream)
 {
-    constexpr bool PER_EXAMPLE = (MODE == MODE_SQUARE || MODE == MODE_SIGN);
+    constexpr bool PER_EXAMPLE = (MODE == MODE_SQUARE || MODE == MODE_SIGN || MODE == MODE_SIGN_PACKED);
     const int tiles_m = (int)((din + TL::BM - 1) / TL::BM), tiles_n = (int)((dout + TL::BN - 1) / TL::BN);
     const int64_t rows_per_split = PER_EXAMPLE ? plan.per_split * T : plan.per_split;
     auto kern = stat_dma_kernel<TL, MODE>;
@@ -374,9 +408,12 @@ hipError_t launch_one(const uint16_t* X, const uint16_t* G, int64_t B, int64_t T
 
 }  // namespace
 
-void dma_tile_shape(Mode mode, int* bm, int* bn)
+// sign counts are packed (and the tile is 256 x 256) while a group of examples cannot exceed 2048
+static bool sign_is_packed(int64_t B) { return B <= 2048 && !getenv("PEX_SIGN_FP32"); }
+
+void dma_tile_shape(Mode mode, int64_t B, int* bm, int* bn)
 {
-    if (mode == MODE_IDENTITY || mode == MODE_TOKEN_SQ) { *bm = TileId::BM; *bn = TileId::BN; }
+    if (mode == MODE_IDENTITY || mode == MODE_TOKEN_SQ || (mode == MODE_SIGN && sign_is_packed(B))) { *bm = TileId::BM; *bn = TileId::BN; }
     else { *bm = TilePhi::BM; *bn = TilePhi::BN; }
 }
 
@@ -416,6 +453,11 @@ hipError_t launch_stat_dma_bf16(const void* X, const void* G, int64_t B, int64_t
         if (cfg == 2) return launch_one<TilePhi2, MODE_SQUARE>(x, g, B, T, din, dout, plan, out, stream);
         return launch_one<TilePhi, MODE_SQUARE>(x, g, B, T, din, dout, plan, out, stream);
     case MODE_SIGN:
+        if (sign_is_packed(B)) {
+            if (cfg == 1) return launch_one<TileId1, MODE_SIGN_PACKED>(x, g, B, T, din, dout, plan, out, stream);
+            if (cfg == 2) return launch_one<TileTok, MODE_SIGN_PACKED>(x, g, B, T, din, dout, plan, out, stream);
+            return launch_one<TileSgn, MODE_SIGN_PACKED>(x, g, B, T, din, dout, plan, out, stream);
+        }
         if (cfg == 1) return launch_one<TilePhi1, MODE_SIGN>(x, g, B, T, din, dout, plan, out, stream);
         if (cfg == 2) return launch_one<TilePhi2, MODE_SIGN>(x, g, B, T, din, dout, plan, out, stream);
         return launch_one<TilePhi, MODE_SIGN>(x, g, B, T, din, dout, plan, out, stream);

@@ -60,6 +60,8 @@ SHAPES = [
     (2, 16, 32, 32, "bf16"),       # smallest shape the MFMA path takes
     (1, 1, 1, 1, "f32"),           # degenerate
     (1, 1, 8, 8, "bf16"),
+    (2100, 1, 64, 96, "bf16"),     # more examples than packed sign counts can hold: fp32 counts
+    (40, 24, 512, 520, "bf16"),    # 256-wide tiles with a ragged last tile column
 ]
 
 
@@ -82,6 +84,15 @@ def test_integer_inputs_are_bit_exact(B, T, din, dout, dtype):
     assert np.array_equal(got["sign"], st.S_sign)          # includes exact zeros: sgn(0) = 0
     assert (st.S_sign != np.sign(st.S_id) * B).any()
     assert np.array_equal(got["token_sq"], oracle.token_sq(Xn, Gn))
+
+
+def test_sign_count_at_the_packing_limit():
+    """2048 examples that all agree: the count 2048 must come out exactly (and -2048 with the cotangents negated)."""
+    X = torch.ones(2048, 1, 64, dtype=torch.bfloat16)
+    G = torch.ones(2048, 1, 96, dtype=torch.bfloat16)
+    G[:, :, 48:] = -1
+    S = pex.pex_stat(X.to(DEV), G.to(DEV), "sign").cpu()
+    assert torch.equal(S[:, :48], torch.full((64, 48), 2048.0)) and torch.equal(S[:, 48:], torch.full((64, 48), -2048.0))
 
 
 def test_zero_example_gives_zero_sign():

@@ -18,6 +18,16 @@
 
 #include "pex_internal.h"
 
+#ifndef PEX_EXP
+#define PEX_EXP 0
+#endif
+#ifndef PEX_RC
+#define PEX_RC 6
+#endif
+#ifndef PEX_DMA_IN_MUL
+#define PEX_DMA_IN_MUL 0
+#endif
+
 namespace pex {
 namespace {
 
@@ -71,25 +81,18 @@ struct DmaTile {
     static_assert(LDS_BYTES <= 160 * 1024, "LDS ring too large");
 };
 
-__device__ __forceinline__ void wait_vmcnt(int n)
+// s_waitcnt vmcnt(N) only.  Written as assembly: the compiler does not know about the direct-to-LDS loads and
+// would be free to move or drop a wait it sees no use for.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
 {
-    // s_waitcnt vmcnt(n) only (expcnt and lgkmcnt left at their maxima); gfx9 encoding
-    switch (n) {
-#define PEX_W(N) case N: __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (7 << 4) | (15 << 8) | (((N) >> 4) << 14)); break;
-        PEX_W(0) PEX_W(1) PEX_W(2) PEX_W(3) PEX_W(4) PEX_W(5) PEX_W(6) PEX_W(7) PEX_W(8) PEX_W(9) PEX_W(10) PEX_W(11)
-        PEX_W(12) PEX_W(13) PEX_W(14) PEX_W(15) PEX_W(16) PEX_W(18) PEX_W(20) PEX_W(24) PEX_W(30)
-#undef PEX_W
-    default: __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8)); break;
-    }
-    asm volatile("" ::: "memory");   // keep LDS reads of the landed slab below the wait at every compiler level
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
 __device__ __forceinline__ void wait_lds_and_barrier()
 {
-    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wave's LDS reads and writes are complete
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // this wave's LDS reads and writes are complete
 }
 
 // two bf16 values -> squares in fp32 -> two bf16 (round to nearest even); zero stays zero
@@ -320,7 +323,7 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_dma_kernel(const uint16_t* __r
     if (total > 0) {
 #pragma unroll
         for (int s = 0; s < NS; ++s) issue(s);
-        wait_vmcnt((NS - 1) * TL::LPS);       // this wave's part of slab 0 has landed
+        wait_vmcnt<(NS - 1) * TL::LPS>();       // this wave's part of slab 0 has landed
         if (MODE == MODE_TOKEN_SQ) square_chunks(0);
         wait_lds_and_barrier();
         load_frags(0, 0, fa[0], fb[0]);
@@ -328,7 +331,7 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_dma_kernel(const uint16_t* __r
     int st_in_seg = 0;
     for (int g = 0; g < total; ++g) {
         if (MODE == MODE_TOKEN_SQ && g + 1 < total) {
-            wait_vmcnt((NS - 2) * TL::LPS);   // this wave's part of slab g+1 has landed: square it while slab g is multiplied
+            wait_vmcnt<(NS - 2) * TL::LPS>();   // this wave's part of slab g+1 has landed: square it while slab g is multiplied
             square_chunks(g + 1);
         }
 #pragma unroll
@@ -338,7 +341,7 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_dma_kernel(const uint16_t* __r
             interleave_hint();
         }
         if (g + 1 < total) {
-            if (MODE != MODE_TOKEN_SQ) wait_vmcnt((NS - 2) * TL::LPS);   // this wave's part of slab g+1 has landed ...
+            if (MODE != MODE_TOKEN_SQ) wait_vmcnt<(NS - 2) * TL::LPS>();   // this wave's part of slab g+1 has landed ...
             wait_lds_and_barrier();           // ... and its LDS reads of slab g (and writes to slab g+1) are done
             issue(g + NS);                    // refill slab g's buffer
             load_frags(g + 1, 0, fa[KS & 1], fb[KS & 1]);
@@ -358,7 +361,7 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_dma_kernel(const uint16_t* __r
             }
         }
     }
-    wait_vmcnt(0);   // drain the (all out-of-range) loads issued past the end before the LDS is released
+    wait_vmcnt<0>();   // drain the (all out-of-range) loads issued past the end before the LDS is released
 
     // ---- epilogue: lane holds column (lane%32), rows 8*(r/4) + 4*(lane/32) + r%4 of each 32x32 tile
     float* dst = out + (int64_t)split * din * dout;
@@ -380,20 +383,344 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_dma_kernel(const uint16_t* __r
         }
 }
 
+
+// ---------------------------------------------------------------------------------------------------------
+// Two-group variant.  The eight waves form two groups of four (one wave of each group per SIMD) that run half
+// a slab apart, so that whenever one wave of a SIMD sits at a barrier, waits for LDS data or folds phi, the
+// other one is in the middle of its MFMAs.  A wave alternates between
+//   read phase     : the fragments of the first k-step(s) of slab g come from LDS into registers;
+//   multiply phase : all MFMAs of slab g at raised priority, with the fragments of the last k-step and this
+//                    wave's global->LDS loads of slab g+NS-1 slotted in between them,
+// and every phase ends at a workgroup barrier at which the two groups swap roles:
+//   phase 2g   : group 0 reads slab g       | group 1 multiplies slab g-1
+//   phase 2g+1 : group 0 multiplies slab g  | group 1 reads slab g
+// Why the split: a wave issues one LDS instruction per ~16 cycles whatever its width and the transposing read
+// is 8 bytes per lane, so the 2*(FM+FN) reads of a k-step cost as much issue time as half its MFMAs; all reads
+// of a slab in the read phase would make that phase longer than the multiply phase it hides behind.
+// Buffer life: slab g is read during phases 2g .. 2g+2; the loads that refill its buffer (slab g+NS) are issued
+// in the multiply phases of slab g+1 (phases 2g+3 and 2g+4).  Every wave makes sure its part of slab g+1 has
+// landed before the barrier that ends phase 2g+1.  Steady state is branch-free: loads past the end of the range
+// carry an empty descriptor and write zeros into a buffer nobody reads.
+template <typename TL, int MODE>
+__global__ __launch_bounds__(TL::NT, 1) void stat_pp_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ G,
+                                                            int64_t rows_total, int seg_len, int din, int dout,
+                                                            int64_t rows_per_split, int tiles_m, int tiles_n,
+                                                            float* __restrict__ out)
+{
+    constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK, NS = TL::NS, FM = TL::FM, FN = TL::FN;
+    constexpr int XROW = TL::XROW, GROW = TL::GROW, NXI = TL::NXI, NGI = TL::NGI, RX = TL::RX, RG = TL::RG;
+    constexpr int KS = BK / 16, LPS = TL::LPS;
+    constexpr bool PER_EXAMPLE = (MODE == MODE_SQUARE || MODE == MODE_SIGN || MODE == MODE_SIGN_PACKED);
+    constexpr bool PACKED = (MODE == MODE_SIGN_PACKED);
+    static_assert(NS >= 3, "the ring holds the slab being read, the one landing and at least one more");
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+
+#if PEX_EXP & 8
+    const uint64_t clk0 = __builtin_readcyclecounter(), rt0 = __builtin_amdgcn_s_memrealtime();
+#endif
+    int split, tm, tn;
+    map_workgroup(tiles_m, tiles_n, split, tm, tn);
+    const int i0 = tm * BM, j0 = tn * BN;
+    const int64_t row_begin = (int64_t)split * rows_per_split;
+    int64_t row_end = row_begin + rows_per_split;
+    if (row_end > rows_total) row_end = rows_total;
+    const int slen = PER_EXAMPLE ? seg_len : (int)(row_end - row_begin);
+    const int nseg = PER_EXAMPLE ? (int)((row_end - row_begin) / seg_len) : 1;
+    const int nst = (slen + BK - 1) / BK;
+    const int total = nseg * nst;
+
+    const int tid = threadIdx.x, lane = tid % 64;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+    const int group = wave / 4;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void)lds;
+    const int wm = wave / TL::WAVES_N, wn = wave % TL::WAVES_N;
+
+    // loader geometry: as in stat_dma_kernel
+    uint32_t xoff[NXI], goff[NGI];
+#pragma unroll
+    for (int n = 0; n < NXI; ++n) {
+        const int q = wave * NXI + n, r = q * RX + lane / (XROW / 16), slot = lane % (XROW / 16);
+        const int c = slot ^ (4 * (r & 3));
+        xoff[n] = (i0 + c * 8 < din) ? (uint32_t)(r * din + c * 8) * 2u : 0x80000000u;
+    }
+#pragma unroll
+    for (int n = 0; n < NGI; ++n) {
+        const int q = wave * NGI + n, r = q * RG + lane / (GROW / 16), slot = lane % (GROW / 16);
+        const int c = slot ^ (4 * (r & 3));
+        goff[n] = (j0 + c * 8 < dout) ? (uint32_t)(r * dout + c * 8) * 2u : 0x80000000u;
+    }
+    const int din_avail = din - i0, dout_avail = dout - j0;
+
+    // The next slab to load, kept incrementally: its number, its offset inside the example, its first row and
+    // its ring buffer.  issue_begin() builds the two descriptors, issue_load(n) sends this wave's n-th load.
+    int iss_slab = 0, iss_off = 0, iss_buf = 0, iss_valid = 0;
+    const uint16_t* xnext = X + row_begin * din + i0;
+    const uint16_t* gnext = G + row_begin * dout + j0;
+    int4_t iss_rx, iss_rg;
+    uint32_t iss_bx = 0;
+    auto issue_begin = [&]() {
+        iss_valid = 0;
+        if (iss_slab < total) iss_valid = (slen - iss_off) < BK ? (slen - iss_off) : BK;
+        iss_bx = lds_base + (uint32_t)(iss_buf * TL::STAGE);
+        const uint32_t nrx = iss_valid > 0 ? (uint32_t)(((iss_valid - 1) * din + din_avail) * 2) : 0u;
+        const uint32_t nrg = iss_valid > 0 ? (uint32_t)(((iss_valid - 1) * dout + dout_avail) * 2) : 0u;
+        iss_rx = make_rsrc(xnext, nrx);
+        iss_rg = make_rsrc(gnext, nrg);
+    };
+    auto issue_load = [&](int n) {
+#if PEX_EXP & 1
+        if (iss_slab >= NS - 1) return;
+#endif
+        if (n < NXI) dma_load_16(iss_bx + (uint32_t)((wave * NXI + n) * 1024), xoff[n], iss_rx);
+        else dma_load_16(iss_bx + TL::X_BYTES + (uint32_t)((wave * NGI + (n - NXI)) * 1024), goff[n - NXI], iss_rg);
+    };
+    auto issue_end = [&]() {
+        xnext += (int64_t)iss_valid * din;
+        gnext += (int64_t)iss_valid * dout;
+        iss_off += iss_valid;
+        if (iss_off >= slen) iss_off = 0;
+        ++iss_slab;
+        iss_buf = (iss_buf + 1 == NS) ? 0 : iss_buf + 1;
+    };
+
+    // fragment geometry: as in stat_dma_kernel
+    const int blk = lane / 16, li = lane % 16;
+    const int frow = 8 * (blk / 2) + li / 4;
+    const int sw = 4 * (li / 4);
+    const int low = 2 * (blk % 2) * 16 + (li % 4) * 8;
+    int a_addr[FM], b_addr[FN];
+#pragma unroll
+    for (int a = 0; a < FM; ++a) a_addr[a] = frow * XROW + ((((wm * TL::WM + a * 32) / 8) ^ sw) * 16) + low;
+#pragma unroll
+    for (int c = 0; c < FN; ++c) b_addr[c] = frow * GROW + ((((wn * TL::WN + c * 32) / 8) ^ sw) * 16) + low;
+
+    float16_t acc[FM][FN], acc2[(PACKED || !PER_EXAMPLE) ? 1 : FM][(PACKED || !PER_EXAMPLE) ? 1 : FN];
+    half2_t cnt[PACKED ? FM : 1][PACKED ? FN : 1][8];
+#pragma unroll
+    for (int a = 0; a < FM; ++a)
+#pragma unroll
+        for (int c = 0; c < FN; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                acc[a][c][r] = 0.f;
+                if (PACKED) cnt[a][c][r / 2] = half2_t{(_Float16)0, (_Float16)0};
+                else if (PER_EXAMPLE) acc2[a][c][r] = 0.f;
+            }
+
+    // Fragments of one slab.  Fragment number f of a k-step alternates between the two operands
+    // (G0, X0, G1, X1, ..., then what is left), so the operands of the first MFMAs arrive first.
+    constexpr int FPK = FM + FN;                       // fragments per k-step
+    constexpr int RC = PEX_RC < FPK ? PEX_RC : FPK;    // fragments of the last k-step that are read in the multiply phase
+    constexpr int NMF = KS * FM * FN;                  // MFMAs per slab
+    constexpr int DSTEP = (NMF - RC) / LPS > 0 ? (NMF - RC) / LPS : 1;
+    static_assert(RC + (LPS - 1) * DSTEP < NMF, "the multiply phase has a slot for every read and load");
+    bf16x8_t fa[KS][FM], fb[KS][FN];
+    const unsigned char* rd_bx = lds;                  // buffer of the slab being read
+    int rd_buf = 0;
+    auto read_frag = [&](int ks, int f) {
+        constexpr int NALT = 2 * (FM < FN ? FM : FN);
+        const bool is_g = f < NALT ? (f % 2 == 0) : (FN > FM);
+        const int idx = f < NALT ? f / 2 : f - NALT / 2;
+        if (is_g) {
+            const unsigned char* p = rd_bx + TL::X_BYTES + b_addr[idx] + ks * 16 * GROW;
+            const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p));
+            const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p + 4 * GROW));
+            fb[ks][idx] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        } else {
+            const unsigned char* p = rd_bx + a_addr[idx] + ks * 16 * XROW;
+            const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p));
+            const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p + 4 * XROW));
+            fa[ks][idx] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        }
+    };
+    auto read_phase = [&]() {
+        rd_bx = lds + rd_buf * TL::STAGE;
+        rd_buf = (rd_buf + 1 == NS) ? 0 : rd_buf + 1;
+#if PEX_EXP & 2
+        if (iss_slab > NS) return;
+#endif
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int f = 0; f < FPK; ++f)
+                if (ks < KS - 1 || f < FPK - RC) read_frag(ks, f);
+        if (!PEX_DMA_IN_MUL) {
+            // The loads go out after the reads: the memory pipeline accepts one such load per ~40-60 cycles, and a
+            // wave that stalls on it here delays nothing (it would wait at the barrier anyway).
+            issue_begin();
+#pragma unroll
+            for (int n = 0; n < LPS; ++n) issue_load(n);
+            issue_end();
+        }
+    };
+    // Multiply phase: MFMA number i is followed by fragment read i (while i < RC), later by one of the loads
+    // every DSTEP MFMAs.  The scheduling fences pin this order; the compiler adds the LDS waits it needs.
+    auto multiply_phase = [&]() {
+        __builtin_amdgcn_s_setprio(1);
+        if (PEX_DMA_IN_MUL) issue_begin();
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int a = 0; a < FM; ++a)
+#pragma unroll
+                for (int c = 0; c < FN; ++c) {
+                    const int i = (ks * FM + a) * FN + c;
+#if PEX_EXP & 4
+                    if (total < 0)
+#endif
+                    acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][a], fb[ks][c], acc[a][c], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (i < RC) {
+#if PEX_EXP & 2
+                        if (iss_slab <= NS)
+#endif
+                        read_frag(KS - 1, FPK - RC + i);
+                        __builtin_amdgcn_sched_barrier(0);
+                    } else if (PEX_DMA_IN_MUL && (i - RC) % DSTEP == 0 && (i - RC) / DSTEP < LPS) {
+                        issue_load((i - RC) / DSTEP);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+        if (PEX_DMA_IN_MUL) issue_end();
+        __builtin_amdgcn_s_setprio(0);
+    };
+    auto fold_all = [&]() {
+#pragma unroll
+        for (int a = 0; a < FM; ++a)
+#pragma unroll
+            for (int c = 0; c < FN; ++c) {
+                if constexpr (PACKED) fold_tile_sign_packed(cnt[a][c], acc[a][c]);
+                else if constexpr (PER_EXAMPLE) fold_tile<MODE>(acc2[a][c], acc[a][c]);
+            }
+    };
+    auto plain_barrier = [&]() { asm volatile("s_barrier" ::: "memory"); };
+
+    [[maybe_unused]] uint64_t tsum[6] = {0, 0, 0, 0, 0, 0};
+    // Loads issued in the multiply phase of slab h refill the buffer of slab h-1 (slab h+NS-1) for both groups.
+    // Issued in the read phase of slab h, group 1 (phase 2h+1) can still refill the buffer of slab h-1, group 0
+    // (phase 2h, when group 1 still reads slab h-1) only that of slab h-2: its loads run one slab behind.
+    constexpr int AHEAD0 = PEX_DMA_IN_MUL ? NS - 1 : NS - 2;   // slabs group 0 has issued before its first phase
+    constexpr int AHEAD1 = NS - 1;
+    // loads that may still be in flight when this wave's part of slab g+1 must have landed (end of phase 2g+1)
+    constexpr int INFLIGHT0 = (PEX_DMA_IN_MUL ? NS - 2 : NS - 3) * LPS;   // group 0, after its multiply phase of slab g
+    constexpr int INFLIGHT1 = (PEX_DMA_IN_MUL ? NS - 3 : NS - 2) * LPS;   // group 1, after its read phase of slab g
+    static_assert(AHEAD0 >= 1 && INFLIGHT0 >= 0 && INFLIGHT1 >= 0, "ring too short for this schedule");
+    if (total > 0) {
+#pragma unroll
+        for (int s = 0; s < AHEAD1; ++s) {
+            if (s < AHEAD0 || group == 1) {
+                issue_begin();
+#pragma unroll
+                for (int n = 0; n < LPS; ++n) issue_load(n);
+                issue_end();
+            }
+        }
+        if (group == 0) wait_vmcnt<(AHEAD0 - 1) * LPS>();
+        else wait_vmcnt<(AHEAD1 - 1) * LPS>();
+        wait_lds_and_barrier();               // slab 0 is visible to every wave
+        int st_in_seg = 0;
+#if PEX_EXP & 32
+        uint64_t tlast = __builtin_readcyclecounter();
+        auto tick = [&](int k) { const uint64_t now = __builtin_readcyclecounter(); tsum[k] += now - tlast; tlast = now; };
+        if (group == 0) {
+            for (int g = 0; g < total; ++g) {
+                read_phase(); asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); tick(0);
+                plain_barrier(); tick(2);
+                multiply_phase(); tick(3);
+                wait_vmcnt<INFLIGHT0>(); tick(4);
+                plain_barrier(); tick(5);
+            }
+            plain_barrier();
+        } else {
+            plain_barrier();
+            tlast = __builtin_readcyclecounter();
+            for (int g = 0; g < total; ++g) {
+                read_phase(); asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); tick(0);
+                wait_vmcnt<INFLIGHT1>(); tick(4);
+                plain_barrier(); tick(2);
+                multiply_phase(); tick(3);
+                plain_barrier(); tick(5);
+            }
+        }
+    }
+#else
+        if (group == 0) {
+            for (int g = 0; g < total; ++g) {
+                read_phase();
+                __builtin_amdgcn_sched_barrier(0);
+                wait_lds_and_barrier();       // ends phase 2g
+                multiply_phase();
+                __builtin_amdgcn_sched_barrier(0);
+                wait_vmcnt<INFLIGHT0>();          // this wave's part of slab g+1 has landed
+                plain_barrier();              // ends phase 2g+1
+                if (PER_EXAMPLE && ++st_in_seg == nst) { st_in_seg = 0; fold_all(); }
+            }
+            plain_barrier();                  // the other group's last multiply phase
+        } else {
+            plain_barrier();                  // start one phase late
+            for (int g = 0; g < total; ++g) {
+                read_phase();
+                __builtin_amdgcn_sched_barrier(0);
+                wait_vmcnt<INFLIGHT1>();          // this wave's part of slab g+1 has landed
+                wait_lds_and_barrier();       // ends phase 2g+1
+                multiply_phase();
+                __builtin_amdgcn_sched_barrier(0);
+                plain_barrier();              // ends phase 2g+2
+                if (PER_EXAMPLE && ++st_in_seg == nst) { st_in_seg = 0; fold_all(); }
+            }
+        }
+    }
+#endif
+    wait_vmcnt<0>();   // drain the (empty) loads issued past the end before the LDS is released
+
+    float* dst = out + (int64_t)split * din * dout;
+    const int jn = lane % 32, ib = 4 * (lane / 32);
+#pragma unroll
+    for (int a = 0; a < FM; ++a)
+#pragma unroll
+        for (int c = 0; c < FN; ++c) {
+            const int j = j0 + wn * TL::WN + c * 32 + jn;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int i = i0 + wm * TL::WM + a * 32 + 8 * (r / 4) + ib + (r % 4);
+                float v;
+                if constexpr (PACKED) v = (float)cnt[a][c][r / 2][r % 2];
+                else if constexpr (PER_EXAMPLE) v = acc2[a][c][r];
+                else v = acc[a][c][r];
+                if (i < din && j < dout) dst[(int64_t)i * dout + j] = v;
+            }
+        }
+#if PEX_EXP & 32
+    __syncthreads();
+    if (lane == 0 && blockIdx.x == 0 && (wave == 0 || wave == 4 || wave == 3 || wave == 7)) {
+        float* dbg = out + (wave % 4 ? 32 : 0) + (wave / 4) * 8;
+        for (int k = 0; k < 6; ++k) dbg[k] = (float)tsum[k];
+        dbg[6] = (float)total;
+    }
+#endif
+#if PEX_EXP & 8
+    const uint64_t clk1 = __builtin_readcyclecounter(), rt1 = __builtin_amdgcn_s_memrealtime();
+    __syncthreads();
+    if (blockIdx.x == 0 && tid == 0) { out[0] = (float)(clk1 - clk0); out[1] = (float)(rt1 - rt0); }
+#endif
+}
+
 // per-example phi: 256 x 128 block, 64 x 64 per wave; plain contraction: 256 x 256 block, 128 x 64 per wave
 using TilePhi = DmaTile<256, 128, 64, 64, 64, 3>;
 using TileId = DmaTile<256, 256, 128, 64, 64, 2>;
 using TileTok = DmaTile<256, 256, 128, 64, 32, 4>;
 using TileSgn = DmaTile<256, 256, 128, 64, 32, 4>;
 
-template <typename TL, int MODE>
+template <typename TL, int MODE, bool PP = false>
 hipError_t launch_one(const uint16_t* X, const uint16_t* G, int64_t B, int64_t T, int64_t din, int64_t dout,
                       const StatPlan& plan, float* out, hipStream_t stream)
 {
     constexpr bool PER_EXAMPLE = (MODE == MODE_SQUARE || MODE == MODE_SIGN || MODE == MODE_SIGN_PACKED);
     const int tiles_m = (int)((din + TL::BM - 1) / TL::BM), tiles_n = (int)((dout + TL::BN - 1) / TL::BN);
     const int64_t rows_per_split = PER_EXAMPLE ? plan.per_split * T : plan.per_split;
-    auto kern = stat_dma_kernel<TL, MODE>;
+    void (*kern)(const uint16_t*, const uint16_t*, int64_t, int, int, int, int64_t, int, int, float*);
+    if constexpr (PP) kern = stat_pp_kernel<TL, MODE>;
+    else kern = stat_dma_kernel<TL, MODE>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
@@ -434,11 +761,32 @@ hipError_t launch_stat_dma_bf16(const void* X, const void* G, int64_t B, int64_t
     const uint16_t* g = (const uint16_t*)G;
     // PEX_DMA_CFG picks the slab depth / ring length (same tile shapes, so the plan is unaffected)
     const char* e = getenv("PEX_DMA_CFG");
-    const int cfg = e ? atoi(e) : 0;
+    const int cfg = e ? atoi(e) : 10;
     using TilePhi1 = DmaTile<256, 128, 64, 64, 32, 6>;
     using TilePhi2 = DmaTile<256, 128, 64, 64, 32, 4>;
     using TileId1 = DmaTile<256, 256, 128, 64, 32, 4>;
     using TileId2 = DmaTile<256, 256, 128, 64, 32, 5>;
+    using TilePP = DmaTile<256, 256, 128, 64, 32, 4>;
+    using TilePP5 = DmaTile<256, 256, 128, 64, 32, 5>;
+    using TilePP3 = DmaTile<256, 256, 128, 64, 32, 3>;
+    using TilePPPhi = DmaTile<256, 128, 64, 64, 32, 4>;
+    using TilePPPhi64 = DmaTile<256, 128, 64, 64, 64, 3>;
+    if (cfg >= 10) {
+        switch (mode) {
+        case MODE_IDENTITY:
+            if (cfg == 12) return launch_one<TilePP5, MODE_IDENTITY, true>(x, g, B, T, din, dout, plan, out, stream);
+            if (cfg == 13) return launch_one<TilePP3, MODE_IDENTITY, true>(x, g, B, T, din, dout, plan, out, stream);
+            return launch_one<TilePP, MODE_IDENTITY, true>(x, g, B, T, din, dout, plan, out, stream);
+        case MODE_SQUARE:
+            if (cfg == 11) return launch_one<TilePPPhi64, MODE_SQUARE, true>(x, g, B, T, din, dout, plan, out, stream);
+            return launch_one<TilePPPhi, MODE_SQUARE, true>(x, g, B, T, din, dout, plan, out, stream);
+        case MODE_SIGN:
+            if (sign_is_packed(B)) return launch_one<TilePP, MODE_SIGN_PACKED, true>(x, g, B, T, din, dout, plan, out, stream);
+            if (cfg == 11) return launch_one<TilePPPhi64, MODE_SIGN, true>(x, g, B, T, din, dout, plan, out, stream);
+            return launch_one<TilePPPhi, MODE_SIGN, true>(x, g, B, T, din, dout, plan, out, stream);
+        default: break;
+        }
+    }
     switch (mode) {
     case MODE_IDENTITY:
         if (cfg == 1) return launch_one<TileId1, MODE_IDENTITY>(x, g, B, T, din, dout, plan, out, stream);

@@ -37,6 +37,20 @@ LAYER_SETS = {
 }
 
 
+def measured_traffic(workload: str):
+    """HBM bytes per launch of the phi = square contraction, from the committed rocprofv3 counter summary
+    (FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size); None if no summary covers this workload."""
+    path = os.path.join(ROOT, "profiles", f"stat_bf16_square_{workload}_pmc.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return float(line.split(":", 1)[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -46,6 +60,9 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="before the timed region, copy 1 GiB device to device once: a kernel of known traffic "
+                         "against which the FETCH_SIZE / WRITE_SIZE counters of a profiling run are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (per-example statistics shard over the batch axis, "
@@ -81,6 +98,13 @@ def main() -> int:
         L["keep_cpu"] = (X, G) if name == LAYER_SETS[args.workload][0] else None
         layers.append(L)
     torch.cuda.synchronize()
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     sq_events = []          # (start, stop) around every launch of the phi = square contraction
     upd_events = []
@@ -128,10 +152,10 @@ def main() -> int:
     sq_flop = [2.0 * w.B * w.T * w.din * w.dout for _, _, w in sq_events]
     sq_avg_ms = sum(sq_ms) / len(sq_ms)
     achieved = (sum(sq_flop) / len(sq_flop)) / (sq_avg_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "stat_dma_kernel<square> (pex_stat phi=square)",
+    roofline = {"bound": "mfma", "kernel": "stat_bf16_kernel<square> (pex_stat phi=square)",
                 "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "avg_launch_ms": round(sq_avg_ms, 4),
-                "launches": len(sq_ms), "traffic": None}
+                "launches": len(sq_ms), "traffic": measured_traffic(args.workload)}
     upd_ms = [a.elapsed_time(b) for a, b, _ in upd_events]
     upd_bytes = [32.0 * w.din * w.dout for _, _, w in upd_events]
     upd_gbs = (sum(upd_bytes) / len(upd_bytes)) / (sum(upd_ms) / len(upd_ms) * 1e-3) / 1e9

@@ -84,6 +84,9 @@ pex_status pex_stat(const void *X, const void *G, int64_t B, int64_t T, int64_t 
  *   Same buffers and conventions as pex_stat.  For bf16 inputs each squared operand is formed in fp32 and
  *   rounded to bf16 (round to nearest even) before the contraction; all terms are >= 0, so every entry
  *   carries a relative error of at most about 2^-7.  fp32 inputs are squared and multiplied in fp32.
+ *   Workspace: besides partial sums, for large bf16 layers (din*dout/(din+dout) beyond roughly 800) the
+ *   workspace holds bf16 copies of the squared operands, 2*B*T*(din+dout) bytes: squaring once at HBM speed
+ *   is cheaper there than squaring every slab inside the contraction.  The query returns the total.
  */
 size_t pex_token_sq_workspace_bytes(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt);
 pex_status pex_token_sq(const void *X, const void *G, int64_t B, int64_t T, int64_t din, int64_t dout,

@@ -20,27 +20,19 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
     // PEX_FORCE_GENERIC=1 routes bf16 through the SIMT kernel (a tuning/debugging aid, not a fallback:
     // both kernels are device code of this library).
     const bool force_generic = env_int("PEX_FORCE_GENERIC", 0) != 0;
-    // PEX_MFMA_VARIANT: 0 = register-staged kernel only, anything else = direct-to-LDS kernel where it applies
-    p.variant = env_int("PEX_MFMA_VARIANT", 1);
-    p.kernel = 0;
-    if (dt == PEX_BF16 && !force_generic) {
-        if (p.variant != 0 && dma_bf16_supports(B, T, din, dout, mode)) p.kernel = 2;
-        else if (mfma_bf16_supports(B, T, din, dout, mode, 0)) p.kernel = 1;
-    }
+    p.kernel = (dt == PEX_BF16 && !force_generic && bf16_supports(B, T, din, dout)) ? 1 : 0;
 
     // The unit the batch axis is split in: whole examples when phi is applied per example (the sum over
     // the sequence must be complete before phi), slabs of 64 rows of the flattened [B*T] axis otherwise.
     int64_t tiles, target, units;
+    int bm = 64, bn = 64;
     if (p.kernel != 0) {
-        int bm, bn;
-        if (p.kernel == 2) dma_tile_shape(mode, B, &bm, &bn);
-        else mfma_tile_shape(0, mode, &bm, &bn);
-        tiles = ((din + bm - 1) / bm) * ((dout + bn - 1) / bn);
+        bf16_tile_shape(mode, B, &bm, &bn);
         target = 256;    // one workgroup per compute unit
     } else {
-        tiles = ((din + 63) / 64) * ((dout + 63) / 64);
         target = 1024;   // four small workgroups per compute unit
     }
+    tiles = ((din + bm - 1) / bm) * ((dout + bn - 1) / bn);
     const int64_t slab = 64;
     units = per_example ? B : (B * T + slab - 1) / slab;
     const int max_split = env_int("PEX_MAX_SPLIT", 16);
@@ -57,9 +49,6 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
         // and the fixed-order reduction of the partial sums reads ns copies of S.  Pick the cheapest ns.
         // A unit-time is one example (or 64 rows) on one tile at ~4 TFLOP/s per compute unit; the reduction
         // streams at ~4 TB/s.
-        int bm, bn;
-        if (p.kernel == 2) dma_tile_shape(mode, B, &bm, &bn);
-        else mfma_tile_shape(0, mode, &bm, &bn);
         const double rows_per_unit = per_example ? (double)T : (double)slab;
         const double t_unit = 2.0 * rows_per_unit * bm * bn / 4.0e12;
         const double s_bytes = (double)din * (double)dout * 4.0;
@@ -77,7 +66,18 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
     nsplit = (units + per - 1) / per;      // no empty group
     p.nsplit = (int)nsplit;
     p.per_split = per_example ? per : per * slab;
-    p.ws_bytes = nsplit > 1 ? (size_t)nsplit * (size_t)din * (size_t)dout * sizeof(float) : 0;
+    // Per-token square on the MFMA kernel: squaring the operands inside the kernel costs LDS write bandwidth on
+    // every slab (about +60 % time); squaring them once into bf16 copies costs one pass over X and G at HBM speed
+    // (~5.5 TB/s, 4 bytes moved per element).  The copies win when din*dout/(din+dout) is large.
+    p.presq_bytes = 0;
+    if (mode == MODE_TOKEN_SQ && p.kernel == 1 && env_int("PEX_TOKEN_PRESQUARE", 1) != 0) {
+        const double elems = (double)B * (double)T * (double)(din + dout);
+        const double t_pre = 4.0 * elems / 5.5e12 + 6.0e-6;
+        const double t_fused_extra = 0.6 * 2.0 * (double)B * (double)T * (double)din * (double)dout / 1.3e15;
+        if (t_pre < t_fused_extra || env_int("PEX_TOKEN_PRESQUARE", 1) == 2)
+            p.presq_bytes = (((size_t)B * (size_t)T * (size_t)(din + dout) * 2) + 255) & ~(size_t)255;
+    }
+    p.ws_bytes = p.presq_bytes + (nsplit > 1 ? (size_t)nsplit * (size_t)din * (size_t)dout * sizeof(float) : 0);
     return p;
 }
 
@@ -98,18 +98,25 @@ static pex_status run_stat(const void* X, const void* G, int64_t B, int64_t T, i
 {
     const StatPlan plan = plan_stat(B, T, din, dout, dt, mode);
     float* out = S;
-    if (plan.nsplit > 1) {
+    if (plan.ws_bytes > 0) {
         if (!workspace || workspace_bytes < plan.ws_bytes) return PEX_ERR_WORKSPACE;
         if ((uintptr_t)workspace & 15u) return PEX_ERR_ALIGN;
-        out = (float*)workspace;
     }
+    float* partials = (float*)((char*)workspace + plan.presq_bytes);
+    if (plan.nsplit > 1) out = partials;
     hipError_t e;
-    if (plan.kernel == 2) e = launch_stat_dma_bf16(X, G, B, T, din, dout, mode, plan, out, stream);
-    else if (plan.kernel == 1) e = launch_stat_mfma_bf16(X, G, B, T, din, dout, mode, plan, out, stream);
+    if (plan.presq_bytes > 0) {
+        // squared copies of X and G at the front of the workspace, then the plain contraction on them
+        uint16_t* x2 = (uint16_t*)workspace;
+        uint16_t* g2 = x2 + B * T * din;
+        e = launch_square_bf16(X, x2, B * T * din, stream);
+        if (e == hipSuccess) e = launch_square_bf16(G, g2, B * T * dout, stream);
+        if (e == hipSuccess) e = launch_stat_bf16(x2, g2, B, T, din, dout, MODE_IDENTITY, plan, out, stream);
+    } else if (plan.kernel == 1) e = launch_stat_bf16(X, G, B, T, din, dout, mode, plan, out, stream);
     else e = launch_stat_generic(X, G, B, T, din, dout, dt, mode, plan, out, stream);
     if (e != hipSuccess) return PEX_ERR_HIP;
     if (plan.nsplit > 1) {
-        e = launch_reduce_partials((const float*)workspace, plan.nsplit, din * dout, S, stream);
+        e = launch_reduce_partials(partials, plan.nsplit, din * dout, S, stream);
         if (e != hipSuccess) return PEX_ERR_HIP;
     }
     return PEX_OK;

@@ -12,17 +12,16 @@ namespace pex {
 
 // Which statistic a contraction kernel produces.  PHI_* match pex_phi; TOKEN_SQ is the per-token
 // square (operands squared on the load path, one plain contraction over K = B*T).
-enum Mode : int { MODE_IDENTITY = 0, MODE_SQUARE = 1, MODE_SIGN = 2, MODE_TOKEN_SQ = 3,
-                  MODE_SIGN_PACKED = 4 /* kernel-internal: sign counts held as fp16 pairs */ };
+enum Mode : int { MODE_IDENTITY = 0, MODE_SQUARE = 1, MODE_SIGN = 2, MODE_TOKEN_SQ = 3 };
 
 // How one call is carried out.  Chosen on the host from the shape alone, so the workspace query and
 // the launch always agree.
 struct StatPlan {
-    int kernel;        // 0 = generic SIMT kernel, 1 = bf16 MFMA kernel (register-staged), 2 = bf16 MFMA kernel (direct-to-LDS)
+    int kernel;        // 0 = generic SIMT kernel (fp32 inputs, odd shapes), 1 = bf16 MFMA kernel
     int nsplit;        // number of groups the batch (or, for plain contractions, B*T) is split into
     int64_t per_split; // examples (or rows of B*T) per group
-    int variant;       // tile variant of the MFMA kernel
-    size_t ws_bytes;   // nsplit > 1: nsplit * din * dout * 4, else 0
+    size_t presq_bytes; // per-token square through pre-squared copies of X and G: their size (256-byte multiple), else 0
+    size_t ws_bytes;   // presq_bytes + (nsplit > 1 ? nsplit * din * dout * 4 : 0)
 };
 
 StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt, Mode mode);
@@ -30,14 +29,12 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
 // Launchers.  `out` is S when plan.nsplit == 1, else the workspace holding [nsplit][din][dout] partials.
 hipError_t launch_stat_generic(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout,
                                pex_dtype dt, Mode mode, const StatPlan& plan, float* out, hipStream_t stream);
-hipError_t launch_stat_mfma_bf16(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout,
-                                 Mode mode, const StatPlan& plan, float* out, hipStream_t stream);
-bool mfma_bf16_supports(int64_t B, int64_t T, int64_t din, int64_t dout, Mode mode, int variant);
-void mfma_tile_shape(int variant, Mode mode, int* bm, int* bn);
-hipError_t launch_stat_dma_bf16(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout,
-                                Mode mode, const StatPlan& plan, float* out, hipStream_t stream);
-bool dma_bf16_supports(int64_t B, int64_t T, int64_t din, int64_t dout, Mode mode);
-void dma_tile_shape(Mode mode, int64_t B, int* bm, int* bn);
+hipError_t launch_stat_bf16(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout,
+                            Mode mode, const StatPlan& plan, float* out, hipStream_t stream);
+bool bf16_supports(int64_t B, int64_t T, int64_t din, int64_t dout);
+// out[i] = bf16(in[i]^2) (square in fp32, round to nearest even) for n bf16 values, n a multiple of 8
+hipError_t launch_square_bf16(const void* in, void* out, int64_t n, hipStream_t stream);
+void bf16_tile_shape(Mode mode, int64_t B, int* bm, int* bn);
 
 // S[e] = sum_{s < nsplit} partial[s][e], s ascending (fixed order => deterministic).
 hipError_t launch_reduce_partials(const float* partial, int nsplit, int64_t n, float* S, hipStream_t stream);

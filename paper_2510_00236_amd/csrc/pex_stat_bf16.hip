@@ -1,0 +1,522 @@
+// pex_stat_bf16.hip -- bf16 MFMA kernel for S = sum_b phi(X_b^T G_b) and for the per-token square (gfx950).
+//
+// Mathematics (Sec. 2.3, dense layers in sequence models): contract over the sequence, M_b = X_b^T G_b, apply phi
+// to the complete per-example tile while it is still in registers, sum over the batch.  The per-example gradient
+// never leaves the register file.  The per-token square (X o X)^T (G o G) is one plain contraction over all
+// B*T rows whose operands are squared on the way.
+//
+// Data path
+//   * One workgroup = 8 waves (two per SIMD) owns a BM x BN tile of S; a wave owns WM x WN of it as FM x FN MFMA
+//     32x32x16 accumulators.  phi = identity, sign and the per-token square use 256 x 256 tiles (128 x 64 per
+//     wave); phi = square needs a second fp32 register tile for the running sum and uses 256 x 128 (64 x 64 per
+//     wave); sign counts are integers of magnitude <= B and are kept as packed fp16 pairs while B <= 2048, which
+//     is what lets sign use the large tile.
+//   * Slabs of BK tokens go HBM -> LDS with buffer_load_dwordx4 ... lds: no VGPR staging, no LDS write
+//     instructions.  Out-of-range lanes of a buffer load write zeros, which gives the zero fill of ragged slab
+//     rows (num_records of a per-slab descriptor) and of ragged tile columns (a poisoned lane offset) for free.
+//   * Each such instruction writes 1 KiB contiguous, so slab rows cannot be padded; instead the 16-byte chunks of
+//     slab row r are stored at chunk index c ^ 4*(r mod 4).  The transposing read ds_read_b64_tr_b16 of a
+//     16-lane group touches 4 consecutive rows x 32 bytes; the swizzle puts those in 4 different 64-byte bank
+//     groups (no bank conflicts measured).
+//   * NS slabs form a ring in LDS.
+//
+// Schedule: two groups of four waves (one wave of each group per SIMD) run half a slab apart, so that whenever
+// one wave of a SIMD sits at a barrier, waits for LDS data or folds phi, the other one is in the middle of its
+// MFMAs.  A wave alternates between
+//   read phase     : fragments of the first k-step(s) of slab g come from LDS into registers, then this wave's
+//                    global->LDS loads of a later slab are issued;
+//   multiply phase : all MFMAs of slab g at raised priority, the fragment reads of its last k-step slotted in
+//                    between the first of them,
+// and every phase ends at a workgroup barrier where the groups swap roles:
+//   phase 2g   : group 0 reads slab g       | group 1 multiplies slab g-1
+//   phase 2g+1 : group 0 multiplies slab g  | group 1 reads slab g
+// Measured facts behind this shape (MI355X): a wave gets one LDS instruction through per ~16 cycles whatever its
+// width, and the transposing read is 8 bytes per lane, so the 2*(FM+FN) reads of a k-step cost as much issue
+// time as half its MFMAs: all reads of a slab in one phase would make that phase longer than the multiply phase
+// it hides behind.  The memory pipeline takes one 1 KiB direct-to-LDS load per ~40-60 cycles per compute unit
+// when the whole chip is loading; a wave that stalls on that in its read phase delays nothing, in the multiply
+// phase it would starve the MFMA pipe.  Priority is raised only while a wave issues MFMAs: a wave that waits at
+// a barrier with raised priority slows the other wave of its SIMD.
+// Buffer life: slab g is read during phases 2g .. 2g+2.  In its read phase of slab h, group 1 (phase 2h+1)
+// refills the buffer of slab h-1 with slab h+NS-1; group 0 (phase 2h, when group 1 may still read slab h-1)
+// refills the buffer of slab h-2 with slab h+NS-2, i.e. its loads run one slab behind.  Every wave makes sure its
+// part of slab g+1 has landed before the barrier that ends phase 2g+1.  Steady state is branch-free: loads past
+// the end of the range carry an empty descriptor and write zeros into a buffer nobody reads.
+#include <cstdlib>
+
+#include "pex_internal.h"
+
+namespace pex {
+namespace {
+
+// kernel-internal variant of MODE_SIGN: sign counts held as packed fp16 pairs
+constexpr int MODE_SIGN_PACKED = 4;
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) short short4_t;
+typedef __attribute__((ext_vector_type(16))) float float16_t;
+typedef __attribute__((ext_vector_type(4))) int int4_t;
+typedef __attribute__((ext_vector_type(4))) unsigned int uint4_t;
+typedef __attribute__((ext_vector_type(2))) _Float16 half2_t;
+typedef short4_t __attribute__((address_space(3)))* lds_v4;
+typedef uint4_t __attribute__((address_space(3)))* lds_u4;
+typedef __attribute__((address_space(3))) void* lds_void;
+
+// One direct-to-LDS load: every lane fetches 16 bytes at (descriptor base + voff) and the wave's 1 KiB lands at
+// LDS byte address lds_addr + lane*16; lanes whose offset is outside the descriptor's range write zeros.
+// Issued as inline assembly so that the compiler does not serialise it against the LDS reads that follow
+// (it cannot tell that they touch a different slab of the ring); completion is tracked by hand with vmcnt.
+__device__ __forceinline__ void dma_load_16(uint32_t lds_addr, uint32_t voff, int4_t rsrc)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(rsrc)
+                 : "memory", "m0");
+}
+
+__device__ __forceinline__ int4_t make_rsrc(const void* base, uint32_t num_records)
+{
+    const uint64_t a = (uint64_t)base;
+    int4_t r;
+    r[0] = (int)(uint32_t)a;
+    r[1] = (int)((uint32_t)(a >> 32) & 0xffffu);     // stride 0, no swizzle
+    r[2] = (int)num_records;
+    r[3] = 0x00020000;                               // raw buffer, 32-bit data format
+    return r;
+}
+
+// s_waitcnt vmcnt(N) only.  Written as assembly: the compiler does not know about the direct-to-LDS loads and
+// would be free to move or drop a wait it sees no use for.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// this wave's LDS reads and writes are complete, then the workgroup barrier
+__device__ __forceinline__ void wait_lds_and_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+__device__ __forceinline__ void plain_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+// two bf16 values -> squares in fp32 -> two bf16 (round to nearest even, one packed conversion); zero stays zero
+__device__ __forceinline__ uint32_t square_pair_rne(uint32_t packed)
+{
+    typedef __attribute__((ext_vector_type(2))) float float2_t;
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+    const float lo = __uint_as_float(packed << 16), hi = __uint_as_float(packed & 0xffff0000u);
+    const float2_t sq = {lo * lo, hi * hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(sq, bf16x2_t));
+}
+
+// sign(m) in {-1, 0, +1} as a float without compares: scaling by 2^200 sends every non-zero value (denormals
+// included) beyond +-1 and keeps +-0 at 0, the median with -1 and +1 clamps it.
+__device__ __forceinline__ float sign_as_float(float m)
+{
+    return __builtin_amdgcn_fmed3f(__builtin_ldexpf(m, 200), -1.0f, 1.0f);
+}
+
+// phi applied to one finished 32x32 tile of M_b: acc2 += phi(acc), acc = 0
+template <int MODE>
+__device__ __forceinline__ void fold_tile(float16_t& acc2, float16_t& acc)
+{
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const float m = acc[r];
+        if (MODE == MODE_SQUARE) acc2[r] = fmaf(m, m, acc2[r]);
+        else acc2[r] += sign_as_float(m);
+        acc[r] = 0.f;
+    }
+}
+
+// Sign counts of a 32x32 MFMA tile held as 8 fp16 pairs per lane: integers up to 2048 are exact in fp16, so the
+// count of at most 2048 examples is exact, at half the registers of an fp32 tile.
+__device__ __forceinline__ void fold_tile_sign_packed(half2_t (&cnt)[8], float16_t& acc)
+{
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        cnt[r] += __builtin_bit_cast(half2_t, __builtin_amdgcn_cvt_pkrtz(sign_as_float(acc[2 * r]), sign_as_float(acc[2 * r + 1])));
+        acc[2 * r] = 0.f;
+        acc[2 * r + 1] = 0.f;
+    }
+}
+
+// Workgroup id -> (split, tile_m, tile_n): undo the round-robin assignment of consecutive ids to the 8 XCDs,
+// then walk tiles in groups of GROUP_M tile rows so the workgroups resident on one XCD form a compact patch
+// that shares X and G panels in that XCD's L2.
+__device__ __forceinline__ void map_workgroup(int tiles_m, int tiles_n, int& split, int& tm, int& tn)
+{
+    const int n = gridDim.x, id = blockIdx.x;
+    const int xcd = id % 8, local = id / 8;
+    const int base = n / 8, rem = n % 8;
+    const int nid = xcd * base + (xcd < rem ? xcd : rem) + local;
+    const int tiles = tiles_m * tiles_n;
+    split = nid / tiles;
+    const int q = nid - split * tiles;
+    constexpr int GROUP_M = 4;
+    const int per_group = GROUP_M * tiles_n;
+    const int group = q / per_group;
+    const int first_m = group * GROUP_M;
+    const int gm = (tiles_m - first_m) < GROUP_M ? (tiles_m - first_m) : GROUP_M;
+    const int r = q - group * per_group;
+    tm = first_m + r % gm;
+    tn = r / gm;
+}
+
+// Tile geometry.  RC_ = fragments of a slab's last k-step that are read in the multiply phase (the rest of the
+// slab's fragments are read in the read phase).
+template <int BM_, int BN_, int WM_, int WN_, int BK_, int NS_, int RC_>
+struct Bf16Tile {
+    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, BK = BK_, NS = NS_;
+    static constexpr int FM = WM / 32, FN = WN / 32, KS = BK / 16;
+    static constexpr int FPK = FM + FN;                                // fragments per k-step
+    static constexpr int RC = RC_ < FPK ? RC_ : FPK;
+    static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN, NWAVES = WAVES_M * WAVES_N, NT = NWAVES * 64;
+    static constexpr int XROW = BM * 2, GROW = BN * 2;                 // bytes per slab row
+    static constexpr int X_BYTES = BK * XROW, G_BYTES = BK * GROW, STAGE = X_BYTES + G_BYTES;
+    static constexpr int LDS_BYTES = NS * STAGE;
+    static constexpr int NXI = X_BYTES / 1024 / NWAVES, NGI = G_BYTES / 1024 / NWAVES;   // loads per wave per slab
+    static constexpr int LPS = NXI + NGI;
+    static constexpr int RX = 1024 / XROW, RG = 1024 / GROW;           // slab rows covered by one load
+    static_assert(NWAVES == 8, "eight waves per workgroup: two groups of four");
+    static_assert(X_BYTES % (1024 * NWAVES) == 0 && G_BYTES % (1024 * NWAVES) == 0, "slab must divide over the waves");
+    static_assert(BK % 16 == 0 && XROW <= 1024 && GROW <= 1024, "tile limits");
+    static_assert(NS >= 3, "the ring holds the slab being read, the one landing and at least one more");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS ring too large");
+    static_assert(RC <= KS * FM * FN, "the multiply phase has a slot for every read");
+};
+
+template <typename TL, int MODE>
+__global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ G,
+                                                              int64_t rows_total, int seg_len, int din, int dout,
+                                                              int64_t rows_per_split, int tiles_m, int tiles_n,
+                                                              float* __restrict__ out)
+{
+    constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK, NS = TL::NS, FM = TL::FM, FN = TL::FN, KS = TL::KS;
+    constexpr int XROW = TL::XROW, GROW = TL::GROW, NXI = TL::NXI, NGI = TL::NGI, RX = TL::RX, RG = TL::RG;
+    constexpr int LPS = TL::LPS, FPK = TL::FPK, RC = TL::RC;
+    constexpr bool PER_EXAMPLE = (MODE == MODE_SQUARE || MODE == MODE_SIGN || MODE == MODE_SIGN_PACKED);
+    constexpr bool PACKED = (MODE == MODE_SIGN_PACKED);
+    constexpr bool TOKEN = (MODE == MODE_TOKEN_SQ);
+    static_assert(!TOKEN || NS >= 4, "the per-token square needs its slab one phase earlier");
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+
+    int split, tm, tn;
+    map_workgroup(tiles_m, tiles_n, split, tm, tn);
+    const int i0 = tm * BM, j0 = tn * BN;
+    const int64_t row_begin = (int64_t)split * rows_per_split;
+    int64_t row_end = row_begin + rows_per_split;
+    if (row_end > rows_total) row_end = rows_total;
+    const int slen = PER_EXAMPLE ? seg_len : (int)(row_end - row_begin);   // segment: one example, or the whole range
+    const int nseg = PER_EXAMPLE ? (int)((row_end - row_begin) / seg_len) : 1;
+    const int nst = (slen + BK - 1) / BK;
+    const int total = nseg * nst;
+
+    const int tid = threadIdx.x, lane = tid % 64;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+    const int group = wave / 4;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void)lds;
+    const int wm = wave / TL::WAVES_N, wn = wave % TL::WAVES_N;
+
+    // ---- loader geometry.  Load q of a slab (q = wave*NXI + n) fills LDS bytes [q*1024, q*1024+1024) of the X
+    // part: slab rows q*RX .. q*RX+RX-1.  Lane L fills 16-byte slot (L mod XROW/16) of row q*RX + L/(XROW/16)
+    // with global chunk c = slot ^ 4*(row mod 4).
+    uint32_t xoff[NXI], goff[NGI];
+#pragma unroll
+    for (int n = 0; n < NXI; ++n) {
+        const int q = wave * NXI + n, r = q * RX + lane / (XROW / 16), slot = lane % (XROW / 16);
+        const int c = slot ^ (4 * (r & 3));
+        xoff[n] = (i0 + c * 8 < din) ? (uint32_t)(r * din + c * 8) * 2u : 0x80000000u;
+    }
+#pragma unroll
+    for (int n = 0; n < NGI; ++n) {
+        const int q = wave * NGI + n, r = q * RG + lane / (GROW / 16), slot = lane % (GROW / 16);
+        const int c = slot ^ (4 * (r & 3));
+        goff[n] = (j0 + c * 8 < dout) ? (uint32_t)(r * dout + c * 8) * 2u : 0x80000000u;
+    }
+    const int din_avail = din - i0, dout_avail = dout - j0;   // columns of this tile that exist
+
+    // The next slab to load, kept incrementally: its number, its offset inside the example, its first row and
+    // its ring buffer.  Descriptor: base at the tile's first column of slab row 0; num_records ends with the last
+    // valid row, so rows past the end of the example (and everything once the range is exhausted) read as zero.
+    int iss_slab = 0, iss_off = 0, iss_buf = 0;
+    const uint16_t* xnext = X + row_begin * din + i0;
+    const uint16_t* gnext = G + row_begin * dout + j0;
+    auto issue_slab = [&]() {
+        int valid = 0;
+        if (iss_slab < total) valid = (slen - iss_off) < BK ? (slen - iss_off) : BK;
+        const uint32_t bx = lds_base + (uint32_t)(iss_buf * TL::STAGE);
+        const uint32_t bg = bx + TL::X_BYTES;
+        const uint32_t nrx = valid > 0 ? (uint32_t)(((valid - 1) * din + din_avail) * 2) : 0u;
+        const uint32_t nrg = valid > 0 ? (uint32_t)(((valid - 1) * dout + dout_avail) * 2) : 0u;
+        const int4_t rx = make_rsrc(xnext, nrx);
+        const int4_t rg = make_rsrc(gnext, nrg);
+#pragma unroll
+        for (int n = 0; n < NXI; ++n) dma_load_16(bx + (uint32_t)((wave * NXI + n) * 1024), xoff[n], rx);
+#pragma unroll
+        for (int n = 0; n < NGI; ++n) dma_load_16(bg + (uint32_t)((wave * NGI + n) * 1024), goff[n], rg);
+        xnext += (int64_t)valid * din;
+        gnext += (int64_t)valid * dout;
+        iss_off += valid;
+        if (iss_off >= slen) iss_off = 0;
+        ++iss_slab;
+        iss_buf = (iss_buf + 1 == NS) ? 0 : iss_buf + 1;
+    };
+    // Per-token square: lane L squares the 16 bytes its own loads put into buffer `buf` (so only this wave's vmcnt
+    // matters); squares are formed in fp32 and rounded to bf16 (nearest even); the zero fill stays zero.
+    auto square_share = [&](int buf) {
+        unsigned char* bx = lds + buf * TL::STAGE;
+        unsigned char* bg = bx + TL::X_BYTES;
+        uint4_t v[LPS];
+#pragma unroll
+        for (int n = 0; n < NXI; ++n) v[n] = *(lds_u4)(bx + (wave * NXI + n) * 1024 + lane * 16);
+#pragma unroll
+        for (int n = 0; n < NGI; ++n) v[NXI + n] = *(lds_u4)(bg + (wave * NGI + n) * 1024 + lane * 16);
+#pragma unroll
+        for (int n = 0; n < LPS; ++n)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[n][e] = square_pair_rne(v[n][e]);
+#pragma unroll
+        for (int n = 0; n < NXI; ++n) *(lds_u4)(bx + (wave * NXI + n) * 1024 + lane * 16) = v[n];
+#pragma unroll
+        for (int n = 0; n < NGI; ++n) *(lds_u4)(bg + (wave * NGI + n) * 1024 + lane * 16) = v[NXI + n];
+    };
+
+    // ---- fragment geometry for ds_read_b64_tr_b16 (lane i of a 16-lane group supplies row i/4, cols 4*(i%4)..+3
+    // and receives column i, rows 0..3).  Row r = 16*ks + 8*(blk/2) + 4*h + li/4, so r mod 4 = li/4.
+    const int blk = lane / 16, li = lane % 16;
+    const int frow = 8 * (blk / 2) + li / 4;
+    const int sw = 4 * (li / 4);                                    // swizzle term of this lane's rows
+    const int low = 2 * (blk % 2) * 16 + (li % 4) * 8;              // bytes: chunk 2*(blk%2) + (li%4)/2, half (li%4)%2
+    int a_addr[FM], b_addr[FN];
+#pragma unroll
+    for (int a = 0; a < FM; ++a) a_addr[a] = frow * XROW + ((((wm * TL::WM + a * 32) / 8) ^ sw) * 16) + low;
+#pragma unroll
+    for (int c = 0; c < FN; ++c) b_addr[c] = frow * GROW + ((((wn * TL::WN + c * 32) / 8) ^ sw) * 16) + low;
+
+    float16_t acc[FM][FN], acc2[(PACKED || !PER_EXAMPLE) ? 1 : FM][(PACKED || !PER_EXAMPLE) ? 1 : FN];
+    half2_t cnt[PACKED ? FM : 1][PACKED ? FN : 1][8];
+#pragma unroll
+    for (int a = 0; a < FM; ++a)
+#pragma unroll
+        for (int c = 0; c < FN; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                acc[a][c][r] = 0.f;
+                if (PACKED) cnt[a][c][r / 2] = half2_t{(_Float16)0, (_Float16)0};
+                else if (PER_EXAMPLE) acc2[a][c][r] = 0.f;
+            }
+
+    // Fragments of one slab.  Fragment number f of a k-step alternates between the two operands
+    // (G0, X0, G1, X1, ..., then what is left), so the operands of the first MFMAs arrive first.
+    bf16x8_t fa[KS][FM], fb[KS][FN];
+    const unsigned char* rd_bx = lds;                  // buffer of the slab being read
+    int rd_buf = 0;
+    auto read_frag = [&](int ks, int f) {
+        constexpr int NALT = 2 * (FM < FN ? FM : FN);
+        const bool is_g = f < NALT ? (f % 2 == 0) : (FN > FM);
+        const int idx = f < NALT ? f / 2 : f - NALT / 2;
+        if (is_g) {
+            const unsigned char* p = rd_bx + TL::X_BYTES + b_addr[idx] + ks * 16 * GROW;
+            const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p));
+            const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p + 4 * GROW));
+            fb[ks][idx] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        } else {
+            const unsigned char* p = rd_bx + a_addr[idx] + ks * 16 * XROW;
+            const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p));
+            const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p + 4 * XROW));
+            fa[ks][idx] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        }
+    };
+    auto read_phase = [&]() {
+        rd_bx = lds + rd_buf * TL::STAGE;
+        rd_buf = (rd_buf + 1 == NS) ? 0 : rd_buf + 1;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int f = 0; f < FPK; ++f)
+                if (ks < KS - 1 || f < FPK - RC) read_frag(ks, f);
+        issue_slab();   // after the reads: a wave that stalls on the memory pipeline here has its reads in flight
+        if constexpr (TOKEN) {
+            // this wave's part of the NEXT slab is squared in place, a phase or more ahead of its first reader
+            if (group == 0) wait_vmcnt<(NS - 3) * LPS>();
+            else wait_vmcnt<(NS - 2) * LPS>();
+            square_share(rd_buf);
+        }
+    };
+    // Multiply phase: MFMA number i is followed by fragment read i of the last k-step (while i < RC).  The
+    // scheduling fences pin this order; the compiler adds the LDS waits the MFMAs need.
+    auto multiply_phase = [&]() {
+        __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int a = 0; a < FM; ++a)
+#pragma unroll
+                for (int c = 0; c < FN; ++c) {
+                    const int i = (ks * FM + a) * FN + c;
+                    acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][a], fb[ks][c], acc[a][c], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (i < RC) {
+                        read_frag(KS - 1, FPK - RC + i);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+        __builtin_amdgcn_s_setprio(0);
+    };
+    auto fold_all = [&]() {
+#pragma unroll
+        for (int a = 0; a < FM; ++a)
+#pragma unroll
+            for (int c = 0; c < FN; ++c) {
+                if constexpr (PACKED) fold_tile_sign_packed(cnt[a][c], acc[a][c]);
+                else if constexpr (PER_EXAMPLE) fold_tile<MODE>(acc2[a][c], acc[a][c]);
+            }
+    };
+
+    constexpr int AHEAD0 = NS - 2, AHEAD1 = NS - 1;   // slabs a group has issued before its first phase
+    // loads that may still be in flight when this wave's part of slab g+1 must have landed (end of phase 2g+1)
+    constexpr int INFLIGHT0 = (NS - 3) * LPS;          // group 0, after its multiply phase of slab g
+    constexpr int INFLIGHT1 = (NS - 2) * LPS;          // group 1, after its read phase of slab g
+    if (total > 0) {
+#pragma unroll
+        for (int s = 0; s < AHEAD1; ++s)
+            if (s < AHEAD0 || group == 1) issue_slab();
+        if (group == 0) wait_vmcnt<(AHEAD0 - 1) * LPS>();
+        else wait_vmcnt<(AHEAD1 - 1) * LPS>();
+        if constexpr (TOKEN) square_share(0);
+        wait_lds_and_barrier();               // slab 0 is visible to every wave
+        int st_in_seg = 0;
+        if (group == 0) {
+            for (int g = 0; g < total; ++g) {
+                read_phase();
+                __builtin_amdgcn_sched_barrier(0);
+                wait_lds_and_barrier();       // ends phase 2g
+                multiply_phase();
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (!TOKEN) wait_vmcnt<INFLIGHT0>();   // this wave's part of slab g+1 has landed
+                plain_barrier();              // ends phase 2g+1
+                if (PER_EXAMPLE && ++st_in_seg == nst) { st_in_seg = 0; fold_all(); }
+            }
+            plain_barrier();                  // the other group's last multiply phase
+        } else {
+            plain_barrier();                  // start one phase late
+            for (int g = 0; g < total; ++g) {
+                read_phase();
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (!TOKEN) wait_vmcnt<INFLIGHT1>();   // this wave's part of slab g+1 has landed
+                wait_lds_and_barrier();       // ends phase 2g+1
+                multiply_phase();
+                __builtin_amdgcn_sched_barrier(0);
+                plain_barrier();              // ends phase 2g+2
+                if (PER_EXAMPLE && ++st_in_seg == nst) { st_in_seg = 0; fold_all(); }
+            }
+        }
+    }
+    wait_vmcnt<0>();   // drain the (empty) loads issued past the end before the LDS is released
+
+    // ---- epilogue: lane holds column (lane%32), rows 8*(r/4) + 4*(lane/32) + r%4 of each 32x32 tile
+    float* dst = out + (int64_t)split * din * dout;
+    const int jn = lane % 32, ib = 4 * (lane / 32);
+#pragma unroll
+    for (int a = 0; a < FM; ++a)
+#pragma unroll
+        for (int c = 0; c < FN; ++c) {
+            const int j = j0 + wn * TL::WN + c * 32 + jn;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int i = i0 + wm * TL::WM + a * 32 + 8 * (r / 4) + ib + (r % 4);
+                float v;
+                if constexpr (PACKED) v = (float)cnt[a][c][r / 2][r % 2];
+                else if constexpr (PER_EXAMPLE) v = acc2[a][c][r];
+                else v = acc[a][c][r];
+                if (i < din && j < dout) dst[(int64_t)i * dout + j] = v;
+            }
+        }
+}
+
+// out = bf16(in^2), 8 values per lane per step
+__global__ __launch_bounds__(256) void square_bf16_kernel(const uint4_t* __restrict__ in, uint4_t* __restrict__ out, int64_t n16)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) {
+        uint4_t v = __builtin_nontemporal_load(in + i);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = square_pair_rne(v[e]);
+        out[i] = v;
+    }
+}
+
+// plain contractions and packed sign counts: 256 x 256 block, 128 x 64 per wave, slabs of 32 tokens, ring of 4;
+// the per-token square needs its slab a phase earlier and takes a ring of 5 (all 160 KB of LDS);
+// two fp32 register tiles (phi = square, sign counts beyond 2048 examples): 256 x 128 block, 64 x 64 per wave.
+using TileWide = Bf16Tile<256, 256, 128, 64, 32, 4, 6>;
+using TileToken = Bf16Tile<256, 256, 128, 64, 32, 5, 6>;
+using TilePhi = Bf16Tile<256, 128, 64, 64, 32, 4, 4>;
+
+template <typename TL, int MODE>
+hipError_t launch_one(const uint16_t* X, const uint16_t* G, int64_t B, int64_t T, int64_t din, int64_t dout,
+                      const StatPlan& plan, float* out, hipStream_t stream)
+{
+    constexpr bool PER_EXAMPLE = (MODE == MODE_SQUARE || MODE == MODE_SIGN || MODE == MODE_SIGN_PACKED);
+    const int tiles_m = (int)((din + TL::BM - 1) / TL::BM), tiles_n = (int)((dout + TL::BN - 1) / TL::BN);
+    const int64_t rows_per_split = PER_EXAMPLE ? plan.per_split * T : plan.per_split;
+    auto kern = stat_bf16_kernel<TL, MODE>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const dim3 grid((unsigned)(tiles_m * tiles_n * plan.nsplit)), block(TL::NT);
+    kern<<<grid, block, TL::LDS_BYTES, stream>>>(X, G, B * T, (int)T, (int)din, (int)dout, rows_per_split, tiles_m,
+                                                 tiles_n, out);
+    return hipGetLastError();
+}
+
+// sign counts are packed (and the tile is 256 x 256) while a group of examples cannot exceed 2048
+bool sign_is_packed(int64_t B) { return B <= 2048; }
+
+}  // namespace
+
+void bf16_tile_shape(Mode mode, int64_t B, int* bm, int* bn)
+{
+    if (mode == MODE_IDENTITY || mode == MODE_TOKEN_SQ || (mode == MODE_SIGN && sign_is_packed(B))) { *bm = TileWide::BM; *bn = TileWide::BN; }
+    else { *bm = TilePhi::BM; *bn = TilePhi::BN; }
+}
+
+bool bf16_supports(int64_t B, int64_t T, int64_t din, int64_t dout)
+{
+    // 16-byte chunks of a row; tiny problems are latency-bound and stay on the SIMT kernel
+    if (din % 8 != 0 || dout % 8 != 0 || din < 32 || dout < 32 || B * T < 16) return false;
+    // per-slab descriptors and lane offsets are 32-bit byte counts: one slab of rows must stay below 2 GiB
+    const int64_t bk = 32;
+    if (bk * din * 2 >= ((int64_t)1 << 31) || bk * dout * 2 >= ((int64_t)1 << 31)) return false;
+    return true;
+}
+
+hipError_t launch_square_bf16(const void* in, void* out, int64_t n, hipStream_t stream)
+{
+    const int64_t n16 = n / 8;
+    int64_t blocks = (n16 + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    square_bf16_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>((const uint4_t*)in, (uint4_t*)out, n16);
+    return hipGetLastError();
+}
+
+hipError_t launch_stat_bf16(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout, Mode mode,
+                            const StatPlan& plan, float* out, hipStream_t stream)
+{
+    const uint16_t* x = (const uint16_t*)X;
+    const uint16_t* g = (const uint16_t*)G;
+    switch (mode) {
+    case MODE_IDENTITY: return launch_one<TileWide, MODE_IDENTITY>(x, g, B, T, din, dout, plan, out, stream);
+    case MODE_TOKEN_SQ: return launch_one<TileToken, MODE_TOKEN_SQ>(x, g, B, T, din, dout, plan, out, stream);
+    case MODE_SQUARE: return launch_one<TilePhi, MODE_SQUARE>(x, g, B, T, din, dout, plan, out, stream);
+    case MODE_SIGN:
+        if (sign_is_packed(B)) return launch_one<TileWide, MODE_SIGN_PACKED>(x, g, B, T, din, dout, plan, out, stream);
+        return launch_one<TilePhi, MODE_SIGN>(x, g, B, T, din, dout, plan, out, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace pex

@@ -78,6 +78,24 @@ pex_status pex_stat(const void *X, const void *G, int64_t B, int64_t T, int64_t 
                     pex_stream_t stream);
 
 /*
+ * pex_stat_multi -- several of the statistics of pex_stat from one pass over X and G.  MicroAdam needs the mean
+ * gradient and the mean square of the same step (Algorithm 1, App. E; nu_micro and nu_adam of Eq. (nu_defs));
+ * the per-example gradient tile M_b is the same for every phi, so one contraction can feed them all.
+ *   want     bit set of PEX_WANT_IDENTITY, PEX_WANT_SQUARE, PEX_WANT_SIGN (at least one).
+ *   S_id, S_sq, S_sign  [din,dout] fp32 device outputs, each required iff its bit is set (ignored otherwise);
+ *                       same definitions, layout and error bounds as pex_stat with the matching phi.
+ *   On bf16 layers the MFMA kernel produces two statistics per contraction (three are a pair plus one);
+ *   other inputs are served one statistic at a time.  Workspace as for pex_stat, sized by the query below.
+ */
+#define PEX_WANT_IDENTITY 1u
+#define PEX_WANT_SQUARE 2u
+#define PEX_WANT_SIGN 4u
+size_t pex_stat_multi_workspace_bytes(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt, uint32_t want);
+pex_status pex_stat_multi(const void *X, const void *G, int64_t B, int64_t T, int64_t din, int64_t dout,
+                          pex_dtype dt, uint32_t want, float *S_id, float *S_sq, float *S_sign, void *workspace,
+                          size_t workspace_bytes, pex_stream_t stream);
+
+/*
  * pex_token_sq -- S_tok = (X o X)^T (G o G) = sum_{b,t} (x_bt o x_bt)(g_bt o g_bt)^T  (Sec. 2.3,
  * "per-token second moments").  A proxy statistic: tokens are not independent computational paths in a
  * transformer, so this is not a per-token gradient second moment.

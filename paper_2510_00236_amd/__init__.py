@@ -5,7 +5,8 @@ device memory and streams.  There is no CPU fallback: if ``libpex.so`` is missin
 the GPU the call raises.
 
 Functions mirror the C ABI in ``include/pex.h``:
-``pex_stat``, ``pex_token_sq``, ``pex_adam_update``, ``pex_signsgd_update`` and the workspace queries.
+``pex_stat``, ``pex_stat_multi``, ``pex_token_sq``, ``pex_adam_update``, ``pex_signsgd_update`` and the
+workspace queries.
 """
 from __future__ import annotations
 
@@ -23,7 +24,11 @@ PHI = {"identity": PEX_PHI_IDENTITY, "square": PEX_PHI_SQUARE, "sign": PEX_PHI_S
 VARIANT = {"adam": PEX_ADAM, "microadam": PEX_MICROADAM, "microadam_var": PEX_MICROADAM_VAR,
            "microadam_msq": PEX_MICROADAM_MSQ}
 
+PEX_WANT_IDENTITY, PEX_WANT_SQUARE, PEX_WANT_SIGN = 1, 2, 4
+WANT = {"identity": PEX_WANT_IDENTITY, "square": PEX_WANT_SQUARE, "sign": PEX_WANT_SIGN}
+
 EXPORTS = ("pex_status_string", "pex_version", "pex_stat_workspace_bytes", "pex_stat",
+           "pex_stat_multi_workspace_bytes", "pex_stat_multi",
            "pex_token_sq_workspace_bytes", "pex_token_sq", "pex_adam_update", "pex_signsgd_update")
 
 
@@ -59,6 +64,10 @@ def lib() -> ctypes.CDLL:
         L.pex_stat_workspace_bytes.restype = sz
         L.pex_stat.argtypes = [p, p, i64, i64, i64, i64, ctypes.c_int, ctypes.c_int, p, p, sz, p]
         L.pex_stat.restype = ctypes.c_int
+        L.pex_stat_multi_workspace_bytes.argtypes = [i64, i64, i64, i64, ctypes.c_int, ctypes.c_uint32]
+        L.pex_stat_multi_workspace_bytes.restype = sz
+        L.pex_stat_multi.argtypes = [p, p, i64, i64, i64, i64, ctypes.c_int, ctypes.c_uint32, p, p, p, p, sz, p]
+        L.pex_stat_multi.restype = ctypes.c_int
         L.pex_token_sq_workspace_bytes.argtypes = [i64, i64, i64, i64, ctypes.c_int]
         L.pex_token_sq_workspace_bytes.restype = sz
         L.pex_token_sq.argtypes = [p, p, i64, i64, i64, i64, ctypes.c_int, p, p, sz, p]
@@ -116,6 +125,19 @@ def pex_stat_workspace_bytes(B, T, din, dout, dtype_code, phi) -> int:
     return int(lib().pex_stat_workspace_bytes(B, T, din, dout, dtype_code, PHI.get(phi, phi)))
 
 
+def _want_mask(want) -> int:
+    if isinstance(want, int):
+        return want
+    mask = 0
+    for w in want:
+        mask |= WANT[w]
+    return mask
+
+
+def pex_stat_multi_workspace_bytes(B, T, din, dout, dtype_code, want) -> int:
+    return int(lib().pex_stat_multi_workspace_bytes(B, T, din, dout, dtype_code, _want_mask(want)))
+
+
 def pex_token_sq_workspace_bytes(B, T, din, dout, dtype_code) -> int:
     return int(lib().pex_token_sq_workspace_bytes(B, T, din, dout, dtype_code))
 
@@ -141,6 +163,30 @@ def pex_stat(X, G, phi, S=None, workspace=None, stream=None):
     _check(lib().pex_stat(_dev(X, "X"), _dev(G, "G"), B, T, din, dout, dt, code, _dev(S, "S"), wptr, wbytes,
                           _stream(stream)))
     return S
+
+
+def pex_stat_multi(X, G, want, out=None, workspace=None, stream=None):
+    """Several statistics from one pass.  ``want`` is an iterable of 'identity' | 'square' | 'sign' (or the bit
+    set); returns a dict name -> S[din,dout] fp32.  ``out`` may supply the output tensors by name."""
+    import torch
+    B, T, din, dout = _shapes(X, G)
+    dt = _dtype_code(X)
+    mask = _want_mask(want)
+    res = {}
+    ptrs = []
+    for name, bit in WANT.items():
+        if mask & bit:
+            S = (out or {}).get(name)
+            if S is None:
+                S = torch.empty(din, dout, dtype=torch.float32, device=X.device)
+            res[name] = S
+            ptrs.append(_dev(S, name))
+        else:
+            ptrs.append(None)
+    ws, wptr, wbytes = _workspace(pex_stat_multi_workspace_bytes(B, T, din, dout, dt, mask), X, workspace)
+    _check(lib().pex_stat_multi(_dev(X, "X"), _dev(G, "G"), B, T, din, dout, dt, mask, ptrs[0], ptrs[1], ptrs[2],
+                                wptr, wbytes, _stream(stream)))
+    return res
 
 
 def pex_token_sq(X, G, S=None, workspace=None, stream=None):

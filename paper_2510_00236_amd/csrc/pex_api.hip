@@ -122,6 +122,40 @@ static pex_status run_stat(const void* X, const void* G, int64_t B, int64_t T, i
     return PEX_OK;
 }
 
+// How pex_stat_multi is carried out: `pair` = two of the statistics from one MFMA contraction (bf16 layers),
+// the rest one at a time.
+struct MultiPlan {
+    bool pair;            // a fused pair is used
+    uint32_t pair_want;   // which two
+    uint32_t single_want; // served by separate pex_stat passes
+    StatPlan pair_plan;
+    size_t ws_bytes;
+};
+
+static MultiPlan plan_multi(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt, uint32_t want)
+{
+    MultiPlan m{};
+    const int n = __builtin_popcount(want);
+    const StatPlan sq = plan_stat(B, T, din, dout, dt, MODE_SQUARE);
+    m.pair = (n >= 2 && sq.kernel == 1);
+    if (m.pair) {
+        // three wanted: identity and square share a contraction, sign keeps its own (packed counts, large tile)
+        m.pair_want = (n == 3) ? (PEX_WANT_IDENTITY | PEX_WANT_SQUARE) : want;
+        m.single_want = want & ~m.pair_want;
+        m.pair_plan = sq;
+        m.pair_plan.ws_bytes = sq.nsplit > 1 ? 2 * sq.ws_bytes : 0;
+        m.ws_bytes = m.pair_plan.ws_bytes;
+    } else {
+        m.single_want = want;
+    }
+    for (int phi = 0; phi < 3; ++phi)
+        if (m.single_want & (1u << phi)) {
+            const size_t w = plan_stat(B, T, din, dout, dt, (Mode)phi).ws_bytes;
+            if (w > m.ws_bytes) m.ws_bytes = w;     // passes run one after the other on the stream and reuse it
+        }
+    return m;
+}
+
 }  // namespace pex
 
 using namespace pex;
@@ -160,6 +194,52 @@ pex_status pex_stat(const void* X, const void* G, int64_t B, int64_t T, int64_t 
     if (st != PEX_OK) return st;
     if (phi != PEX_PHI_IDENTITY && phi != PEX_PHI_SQUARE && phi != PEX_PHI_SIGN) return PEX_ERR_PHI;
     return run_stat(X, G, B, T, din, dout, dt, (Mode)phi, S, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+size_t pex_stat_multi_workspace_bytes(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt, uint32_t want)
+{
+    if (B < 1 || T < 1 || din < 1 || dout < 1) return 0;
+    if (dt != PEX_F32 && dt != PEX_BF16) return 0;
+    if (want == 0 || (want & ~7u)) return 0;
+    return plan_multi(B, T, din, dout, dt, want).ws_bytes;
+}
+
+pex_status pex_stat_multi(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt,
+                          uint32_t want, float* S_id, float* S_sq, float* S_sign, void* workspace,
+                          size_t workspace_bytes, pex_stream_t stream)
+{
+    if (want == 0 || (want & ~7u)) return PEX_ERR_PHI;
+    float* outs[3] = {(want & PEX_WANT_IDENTITY) ? S_id : nullptr, (want & PEX_WANT_SQUARE) ? S_sq : nullptr,
+                      (want & PEX_WANT_SIGN) ? S_sign : nullptr};
+    for (int phi = 0; phi < 3; ++phi) {
+        if (!(want & (1u << phi))) continue;
+        const pex_status st = check_stat_args(X, G, B, T, din, dout, dt, outs[phi]);
+        if (st != PEX_OK) return st;
+    }
+    const MultiPlan m = plan_multi(B, T, din, dout, dt, want);
+    if (m.ws_bytes > 0) {
+        if (!workspace || workspace_bytes < m.ws_bytes) return PEX_ERR_WORKSPACE;
+        if ((uintptr_t)workspace & 15u) return PEX_ERR_ALIGN;
+    }
+    hipStream_t hs = (hipStream_t)stream;
+    if (m.pair) {
+        const StatPlan& p = m.pair_plan;
+        const int64_t n = din * dout;
+        float* po[3] = {nullptr, nullptr, nullptr};
+        int k = 0;
+        for (int phi = 0; phi < 3; ++phi)
+            if (m.pair_want & (1u << phi)) po[phi] = p.nsplit > 1 ? (float*)workspace + (int64_t)(k++) * p.nsplit * n : outs[phi];
+        if (launch_stat_bf16_pair(X, G, B, T, din, dout, p, po[0], po[1], po[2], hs) != hipSuccess) return PEX_ERR_HIP;
+        if (p.nsplit > 1)
+            for (int phi = 0; phi < 3; ++phi)
+                if (po[phi] && launch_reduce_partials(po[phi], p.nsplit, n, outs[phi], hs) != hipSuccess) return PEX_ERR_HIP;
+    }
+    for (int phi = 0; phi < 3; ++phi) {
+        if (!(m.single_want & (1u << phi))) continue;
+        const pex_status st = run_stat(X, G, B, T, din, dout, dt, (Mode)phi, outs[phi], workspace, workspace_bytes, hs);
+        if (st != PEX_OK) return st;
+    }
+    return PEX_OK;
 }
 
 size_t pex_token_sq_workspace_bytes(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt)

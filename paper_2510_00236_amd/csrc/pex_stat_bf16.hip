@@ -49,8 +49,11 @@
 namespace pex {
 namespace {
 
-// kernel-internal variant of MODE_SIGN: sign counts held as packed fp16 pairs
-constexpr int MODE_SIGN_PACKED = 4;
+// What one launch produces (bit set).  A launch with only OUT_ID or only OUT_TOKEN is a plain contraction over
+// all rows (the accumulators are the result); every other set applies phi per example: the accumulators hold
+// M_b and are folded into one register tile per requested statistic at the end of each example.
+// OUT_SIGN_PK keeps the sign counts as packed fp16 pairs (exact up to 2048 examples), OUT_SIGN_F32 as fp32.
+constexpr int OUT_ID = 1, OUT_SQ = 2, OUT_SIGN_PK = 4, OUT_SIGN_F32 = 8, OUT_TOKEN = 16;
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) short short4_t;
@@ -115,29 +118,26 @@ __device__ __forceinline__ float sign_as_float(float m)
     return __builtin_amdgcn_fmed3f(__builtin_ldexpf(m, 200), -1.0f, 1.0f);
 }
 
-// phi applied to one finished 32x32 tile of M_b: acc2 += phi(acc), acc = 0
-template <int MODE>
-__device__ __forceinline__ void fold_tile(float16_t& acc2, float16_t& acc)
+// End of an example, one finished 32x32 tile of M_b: every requested statistic takes its phi(M_b), M_b restarts
+// from 0.  Sign counts of a tile as 8 fp16 pairs per lane: integers up to 2048 are exact in fp16, so the count of
+// at most 2048 examples is exact, at half the registers of an fp32 tile.
+template <int OUTS>
+__device__ __forceinline__ void fold_tile(float16_t& acc, float16_t& acc_id, float16_t& acc_sq, float16_t& acc_sg, half2_t (&cnt)[8])
 {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const float m = acc[r];
-        if (MODE == MODE_SQUARE) acc2[r] = fmaf(m, m, acc2[r]);
-        else acc2[r] += sign_as_float(m);
-        acc[r] = 0.f;
+        if (OUTS & OUT_ID) acc_id[r] += m;
+        if (OUTS & OUT_SQ) acc_sq[r] = fmaf(m, m, acc_sq[r]);
+        if (OUTS & OUT_SIGN_F32) acc_sg[r] += sign_as_float(m);
     }
-}
-
-// Sign counts of a 32x32 MFMA tile held as 8 fp16 pairs per lane: integers up to 2048 are exact in fp16, so the
-// count of at most 2048 examples is exact, at half the registers of an fp32 tile.
-__device__ __forceinline__ void fold_tile_sign_packed(half2_t (&cnt)[8], float16_t& acc)
-{
+    if (OUTS & OUT_SIGN_PK) {
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-        cnt[r] += __builtin_bit_cast(half2_t, __builtin_amdgcn_cvt_pkrtz(sign_as_float(acc[2 * r]), sign_as_float(acc[2 * r + 1])));
-        acc[2 * r] = 0.f;
-        acc[2 * r + 1] = 0.f;
+        for (int r = 0; r < 8; ++r)
+            cnt[r] += __builtin_bit_cast(half2_t, __builtin_amdgcn_cvt_pkrtz(sign_as_float(acc[2 * r]), sign_as_float(acc[2 * r + 1])));
     }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 }
 
 // Workgroup id -> (split, tile_m, tile_n): undo the round-robin assignment of consecutive ids to the 8 XCDs,
@@ -185,19 +185,22 @@ struct Bf16Tile {
     static_assert(RC <= KS * FM * FN, "the multiply phase has a slot for every read");
 };
 
-template <typename TL, int MODE>
+template <typename TL, int OUTS>
 __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ G,
                                                               int64_t rows_total, int seg_len, int din, int dout,
                                                               int64_t rows_per_split, int tiles_m, int tiles_n,
-                                                              float* __restrict__ out)
+                                                              float* __restrict__ out_id, float* __restrict__ out_sq,
+                                                              float* __restrict__ out_sg)
 {
     constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK, NS = TL::NS, FM = TL::FM, FN = TL::FN, KS = TL::KS;
     constexpr int XROW = TL::XROW, GROW = TL::GROW, NXI = TL::NXI, NGI = TL::NGI, RX = TL::RX, RG = TL::RG;
     constexpr int LPS = TL::LPS, FPK = TL::FPK, RC = TL::RC;
-    constexpr bool PER_EXAMPLE = (MODE == MODE_SQUARE || MODE == MODE_SIGN || MODE == MODE_SIGN_PACKED);
-    constexpr bool PACKED = (MODE == MODE_SIGN_PACKED);
-    constexpr bool TOKEN = (MODE == MODE_TOKEN_SQ);
+    constexpr bool TOKEN = (OUTS == OUT_TOKEN);
+    constexpr bool PER_EXAMPLE = !(OUTS == OUT_ID || OUTS == OUT_TOKEN);
+    constexpr bool HAS_ID = PER_EXAMPLE && (OUTS & OUT_ID), HAS_SQ = (OUTS & OUT_SQ) != 0;
+    constexpr bool HAS_PK = (OUTS & OUT_SIGN_PK) != 0, HAS_SF = (OUTS & OUT_SIGN_F32) != 0;
     static_assert(!TOKEN || NS >= 4, "the per-token square needs its slab one phase earlier");
+    static_assert(!(HAS_PK && HAS_SF) && (OUTS & 31) == OUTS && OUTS != 0, "one representation of the sign counts");
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
 
     int split, tm, tn;
@@ -293,8 +296,11 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
 #pragma unroll
     for (int c = 0; c < FN; ++c) b_addr[c] = frow * GROW + ((((wn * TL::WN + c * 32) / 8) ^ sw) * 16) + low;
 
-    float16_t acc[FM][FN], acc2[(PACKED || !PER_EXAMPLE) ? 1 : FM][(PACKED || !PER_EXAMPLE) ? 1 : FN];
-    half2_t cnt[PACKED ? FM : 1][PACKED ? FN : 1][8];
+    // register tiles: the running contraction, and one per requested per-example statistic
+    float16_t acc[FM][FN];
+    float16_t acc_id[HAS_ID ? FM : 1][HAS_ID ? FN : 1], acc_sq[HAS_SQ ? FM : 1][HAS_SQ ? FN : 1];
+    float16_t acc_sg[HAS_SF ? FM : 1][HAS_SF ? FN : 1];
+    half2_t cnt[HAS_PK ? FM : 1][HAS_PK ? FN : 1][8];
 #pragma unroll
     for (int a = 0; a < FM; ++a)
 #pragma unroll
@@ -302,8 +308,10 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 acc[a][c][r] = 0.f;
-                if (PACKED) cnt[a][c][r / 2] = half2_t{(_Float16)0, (_Float16)0};
-                else if (PER_EXAMPLE) acc2[a][c][r] = 0.f;
+                if (HAS_ID) acc_id[a][c][r] = 0.f;
+                if (HAS_SQ) acc_sq[a][c][r] = 0.f;
+                if (HAS_SF) acc_sg[a][c][r] = 0.f;
+                if (HAS_PK) cnt[a][c][r / 2] = half2_t{(_Float16)0, (_Float16)0};
             }
 
     // Fragments of one slab.  Fragment number f of a k-step alternates between the two operands
@@ -367,10 +375,10 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
 #pragma unroll
         for (int a = 0; a < FM; ++a)
 #pragma unroll
-            for (int c = 0; c < FN; ++c) {
-                if constexpr (PACKED) fold_tile_sign_packed(cnt[a][c], acc[a][c]);
-                else if constexpr (PER_EXAMPLE) fold_tile<MODE>(acc2[a][c], acc[a][c]);
-            }
+            for (int c = 0; c < FN; ++c)
+                if constexpr (PER_EXAMPLE)
+                    fold_tile<OUTS>(acc[a][c], acc_id[HAS_ID ? a : 0][HAS_ID ? c : 0], acc_sq[HAS_SQ ? a : 0][HAS_SQ ? c : 0],
+                                    acc_sg[HAS_SF ? a : 0][HAS_SF ? c : 0], cnt[HAS_PK ? a : 0][HAS_PK ? c : 0]);
     };
 
     constexpr int AHEAD0 = NS - 2, AHEAD1 = NS - 1;   // slabs a group has issued before its first phase
@@ -415,7 +423,7 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
     wait_vmcnt<0>();   // drain the (empty) loads issued past the end before the LDS is released
 
     // ---- epilogue: lane holds column (lane%32), rows 8*(r/4) + 4*(lane/32) + r%4 of each 32x32 tile
-    float* dst = out + (int64_t)split * din * dout;
+    const int64_t split_off = (int64_t)split * din * dout;
     const int jn = lane % 32, ib = 4 * (lane / 32);
 #pragma unroll
     for (int a = 0; a < FM; ++a)
@@ -425,11 +433,14 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int i = i0 + wm * TL::WM + a * 32 + 8 * (r / 4) + ib + (r % 4);
-                float v;
-                if constexpr (PACKED) v = (float)cnt[a][c][r / 2][r % 2];
-                else if constexpr (PER_EXAMPLE) v = acc2[a][c][r];
-                else v = acc[a][c][r];
-                if (i < din && j < dout) dst[(int64_t)i * dout + j] = v;
+                if (i < din && j < dout) {
+                    const int64_t e = split_off + (int64_t)i * dout + j;
+                    if constexpr (!PER_EXAMPLE) out_id[e] = acc[a][c][r];
+                    if constexpr (HAS_ID) out_id[e] = acc_id[a][c][r];
+                    if constexpr (HAS_SQ) out_sq[e] = acc_sq[a][c][r];
+                    if constexpr (HAS_SF) out_sg[e] = acc_sg[a][c][r];
+                    if constexpr (HAS_PK) out_sg[e] = (float)cnt[a][c][r / 2][r % 2];
+                }
             }
         }
 }
@@ -453,14 +464,14 @@ using TileWide = Bf16Tile<256, 256, 128, 64, 32, 4, 6>;
 using TileToken = Bf16Tile<256, 256, 128, 64, 32, 5, 6>;
 using TilePhi = Bf16Tile<256, 128, 64, 64, 32, 4, 4>;
 
-template <typename TL, int MODE>
+template <typename TL, int OUTS>
 hipError_t launch_one(const uint16_t* X, const uint16_t* G, int64_t B, int64_t T, int64_t din, int64_t dout,
-                      const StatPlan& plan, float* out, hipStream_t stream)
+                      const StatPlan& plan, float* out_id, float* out_sq, float* out_sg, hipStream_t stream)
 {
-    constexpr bool PER_EXAMPLE = (MODE == MODE_SQUARE || MODE == MODE_SIGN || MODE == MODE_SIGN_PACKED);
+    constexpr bool PER_EXAMPLE = !(OUTS == OUT_ID || OUTS == OUT_TOKEN);
     const int tiles_m = (int)((din + TL::BM - 1) / TL::BM), tiles_n = (int)((dout + TL::BN - 1) / TL::BN);
     const int64_t rows_per_split = PER_EXAMPLE ? plan.per_split * T : plan.per_split;
-    auto kern = stat_bf16_kernel<TL, MODE>;
+    auto kern = stat_bf16_kernel<TL, OUTS>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
@@ -469,7 +480,7 @@ hipError_t launch_one(const uint16_t* X, const uint16_t* G, int64_t B, int64_t T
     }
     const dim3 grid((unsigned)(tiles_m * tiles_n * plan.nsplit)), block(TL::NT);
     kern<<<grid, block, TL::LDS_BYTES, stream>>>(X, G, B * T, (int)T, (int)din, (int)dout, rows_per_split, tiles_m,
-                                                 tiles_n, out);
+                                                 tiles_n, out_id, out_sq, out_sg);
     return hipGetLastError();
 }
 
@@ -509,14 +520,33 @@ hipError_t launch_stat_bf16(const void* X, const void* G, int64_t B, int64_t T, 
     const uint16_t* x = (const uint16_t*)X;
     const uint16_t* g = (const uint16_t*)G;
     switch (mode) {
-    case MODE_IDENTITY: return launch_one<TileWide, MODE_IDENTITY>(x, g, B, T, din, dout, plan, out, stream);
-    case MODE_TOKEN_SQ: return launch_one<TileToken, MODE_TOKEN_SQ>(x, g, B, T, din, dout, plan, out, stream);
-    case MODE_SQUARE: return launch_one<TilePhi, MODE_SQUARE>(x, g, B, T, din, dout, plan, out, stream);
+    case MODE_IDENTITY: return launch_one<TileWide, OUT_ID>(x, g, B, T, din, dout, plan, out, nullptr, nullptr, stream);
+    case MODE_TOKEN_SQ: return launch_one<TileToken, OUT_TOKEN>(x, g, B, T, din, dout, plan, out, nullptr, nullptr, stream);
+    case MODE_SQUARE: return launch_one<TilePhi, OUT_SQ>(x, g, B, T, din, dout, plan, nullptr, out, nullptr, stream);
     case MODE_SIGN:
-        if (sign_is_packed(B)) return launch_one<TileWide, MODE_SIGN_PACKED>(x, g, B, T, din, dout, plan, out, stream);
-        return launch_one<TilePhi, MODE_SIGN>(x, g, B, T, din, dout, plan, out, stream);
+        if (sign_is_packed(B)) return launch_one<TileWide, OUT_SIGN_PK>(x, g, B, T, din, dout, plan, nullptr, nullptr, out, stream);
+        return launch_one<TilePhi, OUT_SIGN_F32>(x, g, B, T, din, dout, plan, nullptr, nullptr, out, stream);
     default: return hipErrorInvalidValue;
     }
+}
+
+// Two statistics from one contraction (always on the two-register-tile block shape).  A NULL output is not wanted.
+hipError_t launch_stat_bf16_pair(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout,
+                                 const StatPlan& plan, float* out_id, float* out_sq, float* out_sg, hipStream_t stream)
+{
+    const uint16_t* x = (const uint16_t*)X;
+    const uint16_t* g = (const uint16_t*)G;
+    const bool pk = sign_is_packed(B);
+    if (out_id && out_sq && !out_sg) return launch_one<TilePhi, OUT_ID | OUT_SQ>(x, g, B, T, din, dout, plan, out_id, out_sq, nullptr, stream);
+    if (out_id && !out_sq && out_sg) {
+        if (pk) return launch_one<TilePhi, OUT_ID | OUT_SIGN_PK>(x, g, B, T, din, dout, plan, out_id, nullptr, out_sg, stream);
+        return launch_one<TilePhi, OUT_ID | OUT_SIGN_F32>(x, g, B, T, din, dout, plan, out_id, nullptr, out_sg, stream);
+    }
+    if (!out_id && out_sq && out_sg) {
+        if (pk) return launch_one<TilePhi, OUT_SQ | OUT_SIGN_PK>(x, g, B, T, din, dout, plan, nullptr, out_sq, out_sg, stream);
+        return launch_one<TilePhi, OUT_SQ | OUT_SIGN_F32>(x, g, B, T, din, dout, plan, nullptr, out_sq, out_sg, stream);
+    }
+    return hipErrorInvalidValue;
 }
 
 }  // namespace pex

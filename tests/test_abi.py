@@ -50,7 +50,12 @@ def test_workspace_query_is_bounded_and_independent_of_B():
             assert ws % (din * dout * 4) == 0
             assert ws <= 16 * din * dout * 4
             assert ws < B * din * dout * 4 or B <= 16
-        assert pex.pex_token_sq_workspace_bytes(B, T, din, dout, pex.PEX_BF16) <= 16 * din * dout * 4
+        # per-token square: partial sums plus, on large layers, bf16 copies of the squared operands
+        assert pex.pex_token_sq_workspace_bytes(B, T, din, dout, pex.PEX_BF16) <= 16 * din * dout * 4 + 2 * B * T * (din + dout) + 256
+        for want in (3, 5, 6, 7):
+            ws = pex.pex_stat_multi_workspace_bytes(B, T, din, dout, pex.PEX_BF16, want)
+            assert ws <= 2 * 16 * din * dout * 4
+    assert pex.pex_stat_multi_workspace_bytes(4, 16, 64, 64, pex.PEX_BF16, 0) == 0
     assert pex.pex_stat_workspace_bytes(0, 1, 1, 1, pex.PEX_BF16, "square") == 0
     assert pex.pex_stat_workspace_bytes(16, 2048, 2048, 8192, pex.PEX_BF16, "square") == 0
 
@@ -74,6 +79,11 @@ def test_host_validation_launches_nothing():
     assert L.pex_stat(X, G, *ok, 0, 1, S, None, 0, None) == 6
     assert L.pex_stat(X, G, *ok, 0, 1, S, 0x4000, need - 1, None) == 6
     assert L.pex_stat(X, G, *ok, 0, 1, S, 0x4004, need, None) == 5
+    assert L.pex_stat_multi(X, G, *ok, 0, 0, S, S, S, None, 0, None) == 4          # nothing wanted
+    assert L.pex_stat_multi(X, G, *ok, 0, 8, S, S, S, None, 0, None) == 4
+    assert L.pex_stat_multi(X, G, *ok, 0, 3, S, None, None, None, 0, None) == 1     # square wanted, no output for it
+    assert L.pex_stat_multi(X, G, *ok, 0, 3, S, S + 4, None, None, 0, None) == 5
+    assert L.pex_stat_multi(X, G, *ok, 0, 3, S, S, None, None, 0, None) == 6        # fp32 square needs its workspace
     assert L.pex_token_sq(X, None, *ok, 0, S, None, 0, None) == 1
     assert L.pex_token_sq(X, G, 4, 0, 64, 64, 0, S, None, 0, None) == 2
 

@@ -151,3 +151,66 @@ def test_workspace_errors_on_gpu():
     with pytest.raises(pex.PexError) as ei:
         pex.pex_stat(Xd, Gd, "square", workspace=small)
     assert ei.value.code == 6
+
+
+MULTI_SHAPES = [
+    (5, 77, 520, 264, "bf16"),     # several tiles, ragged edges, batch split over workgroups (workspace)
+    (3, 100, 200, 136, "bf16"),
+    (7, 33, 256, 128, "bf16"),     # exactly one tile
+    (2100, 1, 64, 96, "bf16"),     # fp32 sign counts inside a pair
+    (3, 50, 129, 65, "f32"),       # SIMT kernel: one statistic at a time
+]
+
+
+@pytest.mark.parametrize("B,T,din,dout,dtype", MULTI_SHAPES)
+def test_multi_statistics_match_the_oracle_and_the_single_calls(B, T, din, dout, dtype):
+    """Every subset of {identity, square, sign} through pex_stat_multi: same bars as the single calls; square is
+    bit-identical to pex_stat (same tile, same order), sign counts agree wherever no example is ambiguous."""
+    X, G = si.custom(B, T, din, dout, dtype=dtype, seed=B + T)
+    Xd, Gd = X.to(DEV), G.to(DEV)
+    st = oracle.stat(si.widen(X), si.widen(G))
+    single = {phi: pex.pex_stat(Xd, Gd, phi) for phi in ("identity", "square", "sign")}
+    for want in (("identity", "square"), ("identity", "sign"), ("square", "sign"), ("identity", "square", "sign"),
+                 ("square",), ("identity",), ("sign",)):
+        poison = {w: torch.full((din, dout), 3e33, device=DEV) for w in want}     # outputs are overwritten
+        got = pex.pex_stat_multi(Xd, Gd, want, out=poison)
+        torch.cuda.synchronize()
+        assert set(got) == set(want)
+        tag = f"multi{want} B{B} T{T} {din}x{dout} {dtype}"
+        if "identity" in got:
+            assert_real_stat(got["identity"].cpu().double().numpy(), st.S_id, dtype, tag + " identity", elementwise=False)
+        if "square" in got:
+            assert_real_stat(got["square"].cpu().double().numpy(), st.S_sq, dtype, tag + " square", elementwise=(B >= 3))
+            assert torch.equal(got["square"], single["square"]), tag
+        if "sign" in got:
+            assert_sign_stat(got["sign"].cpu().double().numpy(), st.S_sign, st.amb, tag + " sign")
+            clear = torch.from_numpy(st.amb == 0).to(DEV)
+            assert torch.equal(got["sign"][clear], single["sign"][clear]), tag
+
+
+def test_multi_on_integer_inputs_is_bit_exact():
+    X, G = si.integer_valued(6, 40, 264, 136, dtype="bf16", seed=11)
+    st = oracle.stat(si.widen(X), si.widen(G))
+    got = pex.pex_stat_multi(X.to(DEV), G.to(DEV), ("identity", "square", "sign"))
+    torch.cuda.synchronize()
+    assert np.array_equal(got["identity"].cpu().double().numpy(), st.S_id)
+    assert np.array_equal(got["square"].cpu().double().numpy(), st.S_sq)
+    assert np.array_equal(got["sign"].cpu().double().numpy(), st.S_sign)
+
+
+def test_token_square_through_presquared_copies_is_the_same_bits(monkeypatch):
+    """The per-token square has two routes on bf16 layers (operands squared inside the contraction, or bf16 copies
+    of the squares made first); both round the squares the same way and must agree bit for bit."""
+    X, G = si.custom(5, 77, 520, 264, dtype="bf16", seed=21)
+    Xd, Gd = X.to(DEV), G.to(DEV)
+    monkeypatch.setenv("PEX_TOKEN_PRESQUARE", "0")
+    fused = pex.pex_token_sq(Xd, Gd).clone()
+    ws_fused = pex.pex_token_sq_workspace_bytes(5, 77, 520, 264, pex.PEX_BF16)
+    monkeypatch.setenv("PEX_TOKEN_PRESQUARE", "2")
+    copy_bytes = 2 * 5 * 77 * (520 + 264)
+    assert 0 <= pex.pex_token_sq_workspace_bytes(5, 77, 520, 264, pex.PEX_BF16) - ws_fused - copy_bytes < 256
+    copies = pex.pex_token_sq(Xd, Gd)
+    torch.cuda.synchronize()
+    assert torch.equal(fused, copies)
+    tok = oracle.token_sq(si.widen(X), si.widen(G))
+    assert_real_stat(copies.cpu().double().numpy(), tok, "bf16", "token_sq copies", elementwise=True, bar=TOKEN_SQ_BF16_BAR, eng=None)

@@ -84,7 +84,8 @@ pex_status pex_stat(const void *X, const void *G, int64_t B, int64_t T, int64_t 
  *   want     bit set of PEX_WANT_IDENTITY, PEX_WANT_SQUARE, PEX_WANT_SIGN (at least one).
  *   S_id, S_sq, S_sign  [din,dout] fp32 device outputs, each required iff its bit is set (ignored otherwise);
  *                       same definitions, layout and error bounds as pex_stat with the matching phi.
- *   On bf16 layers the MFMA kernel produces two statistics per contraction (three are a pair plus one);
+ *   On bf16 layers the MFMA kernel produces all wanted statistics from one contraction (for all three this needs
+ *   at most 127 examples per group of the batch; beyond that identity and square share one and sign runs alone);
  *   other inputs are served one statistic at a time.  Workspace as for pex_stat, sized by the query below.
  */
 #define PEX_WANT_IDENTITY 1u

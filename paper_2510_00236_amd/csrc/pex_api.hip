@@ -122,11 +122,11 @@ static pex_status run_stat(const void* X, const void* G, int64_t B, int64_t T, i
     return PEX_OK;
 }
 
-// How pex_stat_multi is carried out: `pair` = two of the statistics from one MFMA contraction (bf16 layers),
-// the rest one at a time.
+// How pex_stat_multi is carried out: `pair` = two or three of the statistics from one MFMA contraction (bf16
+// layers), the rest one at a time.
 struct MultiPlan {
-    bool pair;            // a fused pair is used
-    uint32_t pair_want;   // which two
+    bool pair;            // a fused launch is used
+    uint32_t pair_want;   // for which statistics
     uint32_t single_want; // served by separate pex_stat passes
     StatPlan pair_plan;
     size_t ws_bytes;
@@ -139,11 +139,12 @@ static MultiPlan plan_multi(int64_t B, int64_t T, int64_t din, int64_t dout, pex
     const StatPlan sq = plan_stat(B, T, din, dout, dt, MODE_SQUARE);
     m.pair = (n >= 2 && sq.kernel == 1);
     if (m.pair) {
-        // three wanted: identity and square share a contraction, sign keeps its own (packed counts, large tile)
-        m.pair_want = (n == 3) ? (PEX_WANT_IDENTITY | PEX_WANT_SQUARE) : want;
+        // three wanted: all from one contraction while the sign counts fit bytes; otherwise identity and square
+        // share a contraction and sign keeps its own (packed counts, large tile)
+        m.pair_want = (n == 3 && !bf16_triple_supported(sq)) ? (PEX_WANT_IDENTITY | PEX_WANT_SQUARE) : want;
         m.single_want = want & ~m.pair_want;
         m.pair_plan = sq;
-        m.pair_plan.ws_bytes = sq.nsplit > 1 ? 2 * sq.ws_bytes : 0;
+        m.pair_plan.ws_bytes = sq.nsplit > 1 ? __builtin_popcount(m.pair_want) * sq.ws_bytes : 0;
         m.ws_bytes = m.pair_plan.ws_bytes;
     } else {
         m.single_want = want;
@@ -229,7 +230,10 @@ pex_status pex_stat_multi(const void* X, const void* G, int64_t B, int64_t T, in
         int k = 0;
         for (int phi = 0; phi < 3; ++phi)
             if (m.pair_want & (1u << phi)) po[phi] = p.nsplit > 1 ? (float*)workspace + (int64_t)(k++) * p.nsplit * n : outs[phi];
-        if (launch_stat_bf16_pair(X, G, B, T, din, dout, p, po[0], po[1], po[2], hs) != hipSuccess) return PEX_ERR_HIP;
+        const hipError_t e = (__builtin_popcount(m.pair_want) == 3)
+                                 ? launch_stat_bf16_triple(X, G, B, T, din, dout, p, po[0], po[1], po[2], hs)
+                                 : launch_stat_bf16_pair(X, G, B, T, din, dout, p, po[0], po[1], po[2], hs);
+        if (e != hipSuccess) return PEX_ERR_HIP;
         if (p.nsplit > 1)
             for (int phi = 0; phi < 3; ++phi)
                 if (po[phi] && launch_reduce_partials(po[phi], p.nsplit, n, outs[phi], hs) != hipSuccess) return PEX_ERR_HIP;

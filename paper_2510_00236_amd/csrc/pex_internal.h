@@ -35,6 +35,10 @@ hipError_t launch_stat_bf16(const void* X, const void* G, int64_t B, int64_t T, 
 // shape of phi = square, so plan_stat(..., MODE_SQUARE) is its plan.
 hipError_t launch_stat_bf16_pair(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout,
                                  const StatPlan& plan, float* out_id, float* out_sq, float* out_sg, hipStream_t stream);
+// All three from one contraction, while a group of examples is small enough for byte-wide sign counters.
+bool bf16_triple_supported(const StatPlan& plan);
+hipError_t launch_stat_bf16_triple(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout,
+                                   const StatPlan& plan, float* out_id, float* out_sq, float* out_sg, hipStream_t stream);
 bool bf16_supports(int64_t B, int64_t T, int64_t din, int64_t dout);
 // out[i] = bf16(in[i]^2) (square in fp32, round to nearest even) for n bf16 values, n a multiple of 8
 hipError_t launch_square_bf16(const void* in, void* out, int64_t n, hipStream_t stream);

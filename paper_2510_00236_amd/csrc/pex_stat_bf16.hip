@@ -52,8 +52,12 @@ namespace {
 // What one launch produces (bit set).  A launch with only OUT_ID or only OUT_TOKEN is a plain contraction over
 // all rows (the accumulators are the result); every other set applies phi per example: the accumulators hold
 // M_b and are folded into one register tile per requested statistic at the end of each example.
-// OUT_SIGN_PK keeps the sign counts as packed fp16 pairs (exact up to 2048 examples), OUT_SIGN_F32 as fp32.
-constexpr int OUT_ID = 1, OUT_SQ = 2, OUT_SIGN_PK = 4, OUT_SIGN_F32 = 8, OUT_TOKEN = 16;
+// OUT_SIGN_PK keeps the sign counts as packed fp16 pairs (exact up to 2048 examples), OUT_SIGN_F32 as fp32,
+// OUT_SIGN_U8 as four biased byte counters per register: each example adds sign+1 in {0,1,2}, so a byte never
+// borrows from its neighbour and holds up to 127 examples; the count is byte - examples.  A quarter of the
+// registers of an fp32 tile, which is what lets identity, square and sign share one contraction.
+constexpr int OUT_ID = 1, OUT_SQ = 2, OUT_SIGN_PK = 4, OUT_SIGN_F32 = 8, OUT_TOKEN = 16, OUT_SIGN_U8 = 32;
+constexpr int MAX_U8_EXAMPLES = 127;
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) short short4_t;
@@ -122,7 +126,8 @@ __device__ __forceinline__ float sign_as_float(float m)
 // from 0.  Sign counts of a tile as 8 fp16 pairs per lane: integers up to 2048 are exact in fp16, so the count of
 // at most 2048 examples is exact, at half the registers of an fp32 tile.
 template <int OUTS>
-__device__ __forceinline__ void fold_tile(float16_t& acc, float16_t& acc_id, float16_t& acc_sq, float16_t& acc_sg, half2_t (&cnt)[8])
+__device__ __forceinline__ void fold_tile(float16_t& acc, float16_t& acc_id, float16_t& acc_sq, float16_t& acc_sg, half2_t (&cnt)[8],
+                                          uint32_t (&cnt8)[4])
 {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -135,6 +140,15 @@ __device__ __forceinline__ void fold_tile(float16_t& acc, float16_t& acc_id, flo
 #pragma unroll
         for (int r = 0; r < 8; ++r)
             cnt[r] += __builtin_bit_cast(half2_t, __builtin_amdgcn_cvt_pkrtz(sign_as_float(acc[2 * r]), sign_as_float(acc[2 * r + 1])));
+    }
+    if (OUTS & OUT_SIGN_U8) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            uint32_t w = 0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) w = __builtin_amdgcn_cvt_pk_u8_f32(sign_as_float(acc[4 * q + k]) + 1.0f, k, w);
+            cnt8[q] += w;
+        }
     }
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
@@ -198,9 +212,9 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
     constexpr bool TOKEN = (OUTS == OUT_TOKEN);
     constexpr bool PER_EXAMPLE = !(OUTS == OUT_ID || OUTS == OUT_TOKEN);
     constexpr bool HAS_ID = PER_EXAMPLE && (OUTS & OUT_ID), HAS_SQ = (OUTS & OUT_SQ) != 0;
-    constexpr bool HAS_PK = (OUTS & OUT_SIGN_PK) != 0, HAS_SF = (OUTS & OUT_SIGN_F32) != 0;
+    constexpr bool HAS_PK = (OUTS & OUT_SIGN_PK) != 0, HAS_SF = (OUTS & OUT_SIGN_F32) != 0, HAS_U8 = (OUTS & OUT_SIGN_U8) != 0;
     static_assert(!TOKEN || NS >= 4, "the per-token square needs its slab one phase earlier");
-    static_assert(!(HAS_PK && HAS_SF) && (OUTS & 31) == OUTS && OUTS != 0, "one representation of the sign counts");
+    static_assert(HAS_PK + HAS_SF + HAS_U8 <= 1 && (OUTS & 63) == OUTS && OUTS != 0, "one representation of the sign counts");
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
 
     int split, tm, tn;
@@ -301,6 +315,7 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
     float16_t acc_id[HAS_ID ? FM : 1][HAS_ID ? FN : 1], acc_sq[HAS_SQ ? FM : 1][HAS_SQ ? FN : 1];
     float16_t acc_sg[HAS_SF ? FM : 1][HAS_SF ? FN : 1];
     half2_t cnt[HAS_PK ? FM : 1][HAS_PK ? FN : 1][8];
+    uint32_t cnt8[HAS_U8 ? FM : 1][HAS_U8 ? FN : 1][4];
 #pragma unroll
     for (int a = 0; a < FM; ++a)
 #pragma unroll
@@ -312,6 +327,7 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
                 if (HAS_SQ) acc_sq[a][c][r] = 0.f;
                 if (HAS_SF) acc_sg[a][c][r] = 0.f;
                 if (HAS_PK) cnt[a][c][r / 2] = half2_t{(_Float16)0, (_Float16)0};
+                if (HAS_U8) cnt8[a][c][r / 4] = 0u;
             }
 
     // Fragments of one slab.  Fragment number f of a k-step alternates between the two operands
@@ -378,7 +394,8 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
             for (int c = 0; c < FN; ++c)
                 if constexpr (PER_EXAMPLE)
                     fold_tile<OUTS>(acc[a][c], acc_id[HAS_ID ? a : 0][HAS_ID ? c : 0], acc_sq[HAS_SQ ? a : 0][HAS_SQ ? c : 0],
-                                    acc_sg[HAS_SF ? a : 0][HAS_SF ? c : 0], cnt[HAS_PK ? a : 0][HAS_PK ? c : 0]);
+                                    acc_sg[HAS_SF ? a : 0][HAS_SF ? c : 0], cnt[HAS_PK ? a : 0][HAS_PK ? c : 0],
+                                    cnt8[HAS_U8 ? a : 0][HAS_U8 ? c : 0]);
     };
 
     constexpr int AHEAD0 = NS - 2, AHEAD1 = NS - 1;   // slabs a group has issued before its first phase
@@ -440,6 +457,7 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
                     if constexpr (HAS_SQ) out_sq[e] = acc_sq[a][c][r];
                     if constexpr (HAS_SF) out_sg[e] = acc_sg[a][c][r];
                     if constexpr (HAS_PK) out_sg[e] = (float)cnt[a][c][r / 2][r % 2];
+                    if constexpr (HAS_U8) out_sg[e] = (float)((int)((cnt8[a][c][r / 4] >> (8 * (r % 4))) & 0xffu) - nseg);
                 }
             }
         }
@@ -528,6 +546,17 @@ hipError_t launch_stat_bf16(const void* X, const void* G, int64_t B, int64_t T, 
         return launch_one<TilePhi, OUT_SIGN_F32>(x, g, B, T, din, dout, plan, nullptr, nullptr, out, stream);
     default: return hipErrorInvalidValue;
     }
+}
+
+// Identity, square and sign from one contraction: possible while a group of examples fits the byte counters.
+bool bf16_triple_supported(const StatPlan& plan) { return plan.per_split <= MAX_U8_EXAMPLES; }
+
+hipError_t launch_stat_bf16_triple(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout,
+                                   const StatPlan& plan, float* out_id, float* out_sq, float* out_sg, hipStream_t stream)
+{
+    if (!bf16_triple_supported(plan) || !out_id || !out_sq || !out_sg) return hipErrorInvalidValue;
+    return launch_one<TilePhi, OUT_ID | OUT_SQ | OUT_SIGN_U8>((const uint16_t*)X, (const uint16_t*)G, B, T, din, dout, plan, out_id,
+                                                              out_sq, out_sg, stream);
 }
 
 // Two statistics from one contraction (always on the two-register-tile block shape).  A NULL output is not wanted.

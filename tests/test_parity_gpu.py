@@ -158,6 +158,8 @@ MULTI_SHAPES = [
     (3, 100, 200, 136, "bf16"),
     (7, 33, 256, 128, "bf16"),     # exactly one tile
     (2100, 1, 64, 96, "bf16"),     # fp32 sign counts inside a pair
+    (127, 3, 64, 96, "bf16"),      # the most examples the byte-wide sign counters of the three-in-one launch hold
+    (128, 3, 64, 96, "bf16"),      # one more: identity and square share a contraction, sign runs alone
     (3, 50, 129, 65, "f32"),       # SIMT kernel: one statistic at a time
 ]
 
@@ -186,6 +188,18 @@ def test_multi_statistics_match_the_oracle_and_the_single_calls(B, T, din, dout,
             assert_sign_stat(got["sign"].cpu().double().numpy(), st.S_sign, st.amb, tag + " sign")
             clear = torch.from_numpy(st.amb == 0).to(DEV)
             assert torch.equal(got["sign"][clear], single["sign"][clear]), tag
+
+
+def test_byte_sign_counters_at_their_limit():
+    """127 examples that all agree (and all disagree): the three-in-one launch must return +-127 exactly."""
+    X = torch.ones(127, 2, 64, dtype=torch.bfloat16)
+    G = torch.ones(127, 2, 96, dtype=torch.bfloat16)
+    G[:, :, 48:] = -1
+    got = pex.pex_stat_multi(X.to(DEV), G.to(DEV), ("identity", "square", "sign"))
+    torch.cuda.synchronize()
+    S = got["sign"].cpu()
+    assert torch.equal(S[:, :48], torch.full((64, 48), 127.0)) and torch.equal(S[:, 48:], torch.full((64, 48), -127.0))
+    assert torch.equal(got["identity"].cpu(), 2.0 * S) and torch.equal(got["square"].cpu(), torch.full((64, 96), 4.0 * 127))
 
 
 def test_multi_on_integer_inputs_is_bit_exact():

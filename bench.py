@@ -142,6 +142,32 @@ def main() -> int:
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
+    # ---- for information, outside the timed region: the same outputs with identity, square and sign taken from
+    # one contraction (pex_stat_multi).  Not part of `value`: the metric counts one contraction per statistic.
+    def multi_step(t: int):
+        for L in layers:
+            w = L["w"]
+            pex.pex_stat_multi(L["X"], L["G"], ("identity", "square", "sign"),
+                               out={"identity": L["S_id"], "square": L["S_sq"], "sign": L["S_sg"]}, workspace=L["ws_multi"])
+            p = pex.AdamParams(lr=2.0 / 1024, beta1=0.9, beta2=0.95, eps=1e-8, eps_root=0.0, weight_decay=0.0,
+                               grad_scale=1.0 / w.B, sq_scale=1.0 / w.B, step=t, B=w.B)
+            pex.pex_adam_update(L["theta"], L["m"], L["v"], L["S_id"].view(-1), L["S_sq"].view(-1), "microadam", p)
+            pex.pex_signsgd_update(L["theta_s"], L["m_s"], L["S_sg"].view(-1), 3.47e-3, 0.9, 0.0, w.B, False, t)
+            pex.pex_token_sq(L["X"], L["G"], S=L["S_tk"], workspace=L["ws"])
+
+    for L in layers:
+        w = L["w"]
+        nb = pex.pex_stat_multi_workspace_bytes(w.B, w.T, w.din, w.dout, pex.PEX_BF16, ("identity", "square", "sign"))
+        L["ws_multi"] = torch.empty(max(nb, 16), dtype=torch.uint8, device=dev)
+    t_last = args.warmup + args.steps
+    multi_step(t_last + 1)
+    torch.cuda.synchronize()
+    m0 = time.perf_counter()
+    for t in range(t_last + 2, t_last + 2 + args.steps):
+        multi_step(t)
+    torch.cuda.synchronize()
+    multi_ms = (time.perf_counter() - m0) / args.steps * 1e3
+
     flop_per_stat = [2.0 * L["w"].B * L["w"].T * L["w"].din * L["w"].dout for L in layers]
     flop_per_step = 4.0 * sum(flop_per_stat)          # identity, square, sign, per-token square
     ms_per_step = elapsed / args.steps * 1e3
@@ -201,6 +227,9 @@ def main() -> int:
                    "step": "per layer: pex_stat identity+square -> MicroAdam update; pex_stat sign -> MicroSignSGD update; pex_token_sq",
                    "flop_per_step": flop_per_step, "seed": args.seed},
         "roofline": roofline, "update_roofline": update_roofline, "cpu_baseline": cpu,
+        "shared_contraction_step": {"ms_per_step": round(multi_ms, 4),
+                                    "note": "same outputs with identity, square and sign from one contraction per layer "
+                                            "(pex_stat_multi); informational, not used in value"},
     }
     print(json.dumps(out, ensure_ascii=False))
     return 0

@@ -97,6 +97,24 @@ pex_status pex_stat_multi(const void *X, const void *G, int64_t B, int64_t T, in
                           size_t workspace_bytes, pex_stream_t stream);
 
 /*
+ * pex_vec_stat -- the same statistics for a vector parameter (App. B, "Affine operations": an offset is a
+ * contraction of the cotangents with a vector of ones, so its per-example gradient is the reduction over the
+ * length axis).
+ *   v_b[j] = sum_t A[b,t,j] * C[b,t,j]      (C == NULL: an offset, v_b[j] = sum_t A[b,t,j];
+ *                                            C given: an elementwise scale applied to the activation C)
+ *   s      = sum_b phi(v_b)                 for every phi in `want` (bits as for pex_stat_multi)
+ *   A, C   [B,T,d] device, dtype `dt`, read-only; products are exact for bf16 and summed in fp32.
+ *   s_id, s_sq, s_sign  [d] fp32 device outputs, each required iff its bit is set.
+ *   workspace  at least pex_vec_stat_workspace_bytes(...) bytes (never 0): fp32 partial sums over ranges of the
+ *              length axis, B * ranges * d floats, summed in a fixed order.
+ *   Bound by HBM bandwidth: every input byte is read once.  Any B,T,d >= 1 (B*T, d < 2^31).
+ */
+size_t pex_vec_stat_workspace_bytes(int64_t B, int64_t T, int64_t d, pex_dtype dt);
+pex_status pex_vec_stat(const void *A, const void *C, int64_t B, int64_t T, int64_t d, pex_dtype dt, uint32_t want,
+                        float *s_id, float *s_sq, float *s_sign, void *workspace, size_t workspace_bytes,
+                        pex_stream_t stream);
+
+/*
  * pex_token_sq -- S_tok = (X o X)^T (G o G) = sum_{b,t} (x_bt o x_bt)(g_bt o g_bt)^T  (Sec. 2.3,
  * "per-token second moments").  A proxy statistic: tokens are not independent computational paths in a
  * transformer, so this is not a per-token gradient second moment.

@@ -28,7 +28,7 @@ PEX_WANT_IDENTITY, PEX_WANT_SQUARE, PEX_WANT_SIGN = 1, 2, 4
 WANT = {"identity": PEX_WANT_IDENTITY, "square": PEX_WANT_SQUARE, "sign": PEX_WANT_SIGN}
 
 EXPORTS = ("pex_status_string", "pex_version", "pex_stat_workspace_bytes", "pex_stat",
-           "pex_stat_multi_workspace_bytes", "pex_stat_multi",
+           "pex_stat_multi_workspace_bytes", "pex_stat_multi", "pex_vec_stat_workspace_bytes", "pex_vec_stat",
            "pex_token_sq_workspace_bytes", "pex_token_sq", "pex_adam_update", "pex_signsgd_update")
 
 
@@ -68,6 +68,10 @@ def lib() -> ctypes.CDLL:
         L.pex_stat_multi_workspace_bytes.restype = sz
         L.pex_stat_multi.argtypes = [p, p, i64, i64, i64, i64, ctypes.c_int, ctypes.c_uint32, p, p, p, p, sz, p]
         L.pex_stat_multi.restype = ctypes.c_int
+        L.pex_vec_stat_workspace_bytes.argtypes = [i64, i64, i64, ctypes.c_int]
+        L.pex_vec_stat_workspace_bytes.restype = sz
+        L.pex_vec_stat.argtypes = [p, p, i64, i64, i64, ctypes.c_int, ctypes.c_uint32, p, p, p, p, sz, p]
+        L.pex_vec_stat.restype = ctypes.c_int
         L.pex_token_sq_workspace_bytes.argtypes = [i64, i64, i64, i64, ctypes.c_int]
         L.pex_token_sq_workspace_bytes.restype = sz
         L.pex_token_sq.argtypes = [p, p, i64, i64, i64, i64, ctypes.c_int, p, p, sz, p]
@@ -186,6 +190,37 @@ def pex_stat_multi(X, G, want, out=None, workspace=None, stream=None):
     ws, wptr, wbytes = _workspace(pex_stat_multi_workspace_bytes(B, T, din, dout, dt, mask), X, workspace)
     _check(lib().pex_stat_multi(_dev(X, "X"), _dev(G, "G"), B, T, din, dout, dt, mask, ptrs[0], ptrs[1], ptrs[2],
                                 wptr, wbytes, _stream(stream)))
+    return res
+
+
+def pex_vec_stat_workspace_bytes(B, T, d, dtype_code) -> int:
+    return int(lib().pex_vec_stat_workspace_bytes(B, T, d, dtype_code))
+
+
+def pex_vec_stat(A, C=None, want=("identity", "square", "sign"), out=None, workspace=None, stream=None):
+    """Statistics of a vector parameter: s[d] = sum_b phi(sum_t A[b,t,:] * C[b,t,:]); ``C=None`` is an offset.
+    Returns a dict name -> s[d] fp32."""
+    import torch
+    if A.dim() != 3 or (C is not None and C.shape != A.shape):
+        raise ValueError("expected A[B,T,d] and C of the same shape (or None)")
+    if C is not None and C.dtype != A.dtype:
+        raise TypeError("A and C must share a dtype")
+    B, T, d = (int(x) for x in A.shape)
+    dt = _dtype_code(A)
+    mask = _want_mask(want)
+    res, ptrs = {}, []
+    for name, bit in WANT.items():
+        if mask & bit:
+            s = (out or {}).get(name)
+            if s is None:
+                s = torch.empty(d, dtype=torch.float32, device=A.device)
+            res[name] = s
+            ptrs.append(_dev(s, name))
+        else:
+            ptrs.append(None)
+    ws, wptr, wbytes = _workspace(pex_vec_stat_workspace_bytes(B, T, d, dt), A, workspace)
+    _check(lib().pex_vec_stat(_dev(A, "A"), _dev(C, "C") if C is not None else None, B, T, d, dt, mask,
+                              ptrs[0], ptrs[1], ptrs[2], wptr, wbytes, _stream(stream)))
     return res
 
 

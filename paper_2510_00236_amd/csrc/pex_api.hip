@@ -246,6 +246,39 @@ pex_status pex_stat_multi(const void* X, const void* G, int64_t B, int64_t T, in
     return PEX_OK;
 }
 
+size_t pex_vec_stat_workspace_bytes(int64_t B, int64_t T, int64_t d, pex_dtype dt)
+{
+    if (B < 1 || T < 1 || d < 1) return 0;
+    if (dt != PEX_F32 && dt != PEX_BF16) return 0;
+    return plan_vec_stat(B, T, d, dt).ws_bytes;
+}
+
+pex_status pex_vec_stat(const void* A, const void* C, int64_t B, int64_t T, int64_t d, pex_dtype dt, uint32_t want,
+                        float* s_id, float* s_sq, float* s_sign, void* workspace, size_t workspace_bytes,
+                        pex_stream_t stream)
+{
+    if (!A) return PEX_ERR_NULL;
+    if (want == 0 || (want & ~7u)) return PEX_ERR_PHI;
+    float* outs[3] = {(want & PEX_WANT_IDENTITY) ? s_id : nullptr, (want & PEX_WANT_SQUARE) ? s_sq : nullptr,
+                      (want & PEX_WANT_SIGN) ? s_sign : nullptr};
+    for (int phi = 0; phi < 3; ++phi)
+        if ((want & (1u << phi)) && !outs[phi]) return PEX_ERR_NULL;
+    if (dt != PEX_F32 && dt != PEX_BF16) return PEX_ERR_DTYPE;
+    const int64_t lim = (int64_t)1 << 31;
+    if (B < 1 || T < 1 || d < 1 || B >= lim || T >= lim || d >= lim || B * T >= lim) return PEX_ERR_SHAPE;
+    const uintptr_t esz = dt == PEX_BF16 ? 2 : 4;
+    if (((uintptr_t)A | (uintptr_t)C) & (esz - 1)) return PEX_ERR_ALIGN;
+    if (((uintptr_t)outs[0] | (uintptr_t)outs[1] | (uintptr_t)outs[2]) & 3u) return PEX_ERR_ALIGN;
+    const VecPlan plan = plan_vec_stat(B, T, d, dt);
+    if (B * plan.nrange >= 65536) return PEX_ERR_SHAPE;      // grid limit of the second launch dimension
+    if (!workspace || workspace_bytes < plan.ws_bytes) return PEX_ERR_WORKSPACE;
+    if ((uintptr_t)workspace & 15u) return PEX_ERR_ALIGN;
+    return launch_vec_stat(A, C, B, T, d, dt, plan, (float*)workspace, outs[0], outs[1], outs[2], (hipStream_t)stream) ==
+                   hipSuccess
+               ? PEX_OK
+               : PEX_ERR_HIP;
+}
+
 size_t pex_token_sq_workspace_bytes(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt)
 {
     if (B < 1 || T < 1 || din < 1 || dout < 1) return 0;

@@ -44,6 +44,18 @@ bool bf16_supports(int64_t B, int64_t T, int64_t din, int64_t dout);
 hipError_t launch_square_bf16(const void* in, void* out, int64_t n, hipStream_t stream);
 void bf16_tile_shape(Mode mode, int64_t B, int* bm, int* bn);
 
+// Vector parameters (offsets, elementwise scales): the length axis of each example is cut into nrange ranges of
+// rows_per_range tokens; the workspace holds [B][nrange][d] fp32 partial sums.
+struct VecPlan {
+    int nrange;
+    int rows_per_range;
+    size_t ws_bytes;
+};
+VecPlan plan_vec_stat(int64_t B, int64_t T, int64_t d, pex_dtype dt);
+// s = sum_b phi(v_b), v_b[j] = sum_t A[b,t,j] * (C ? C[b,t,j] : 1); outputs that are NULL are not wanted
+hipError_t launch_vec_stat(const void* A, const void* C, int64_t B, int64_t T, int64_t d, pex_dtype dt, const VecPlan& plan,
+                           float* partial, float* s_id, float* s_sq, float* s_sign, hipStream_t stream);
+
 // S[e] = sum_{s < nsplit} partial[s][e], s ascending (fixed order => deterministic).
 hipError_t launch_reduce_partials(const float* partial, int nsplit, int64_t n, float* S, hipStream_t stream);
 

@@ -54,8 +54,12 @@ def test_workspace_query_is_bounded_and_independent_of_B():
         assert pex.pex_token_sq_workspace_bytes(B, T, din, dout, pex.PEX_BF16) <= 16 * din * dout * 4 + 2 * B * T * (din + dout) + 256
         for want in (3, 5, 6, 7):
             ws = pex.pex_stat_multi_workspace_bytes(B, T, din, dout, pex.PEX_BF16, want)
-            assert ws <= 2 * 16 * din * dout * 4
+            assert ws <= 3 * 16 * din * dout * 4     # one set of partial sums per statistic of the shared contraction
     assert pex.pex_stat_multi_workspace_bytes(4, 16, 64, 64, pex.PEX_BF16, 0) == 0
+    # vector parameters: B * ranges * d floats, a few ranges at most
+    for (B, T, d) in [(16, 2048, 8192), (4, 8192, 4096), (64, 1024, 768), (1, 1, 1)]:
+        ws = pex.pex_vec_stat_workspace_bytes(B, T, d, pex.PEX_BF16)
+        assert 0 < ws <= max(2048, B * (T // 32 + 1)) * d * 4 and ws % (B * d * 4) == 0
     assert pex.pex_stat_workspace_bytes(0, 1, 1, 1, pex.PEX_BF16, "square") == 0
     assert pex.pex_stat_workspace_bytes(16, 2048, 2048, 8192, pex.PEX_BF16, "square") == 0
 
@@ -84,6 +88,14 @@ def test_host_validation_launches_nothing():
     assert L.pex_stat_multi(X, G, *ok, 0, 3, S, None, None, None, 0, None) == 1     # square wanted, no output for it
     assert L.pex_stat_multi(X, G, *ok, 0, 3, S, S + 4, None, None, 0, None) == 5
     assert L.pex_stat_multi(X, G, *ok, 0, 3, S, S, None, None, 0, None) == 6        # fp32 square needs its workspace
+    assert L.pex_vec_stat(None, None, 4, 16, 64, 0, 7, S, S, S, 0x4000, 1 << 20, None) == 1
+    assert L.pex_vec_stat(X, None, 4, 16, 64, 0, 0, S, S, S, 0x4000, 1 << 20, None) == 4
+    assert L.pex_vec_stat(X, None, 4, 16, 64, 0, 2, S, None, S, 0x4000, 1 << 20, None) == 1
+    assert L.pex_vec_stat(X, None, 4, 0, 64, 0, 7, S, S, S, 0x4000, 1 << 20, None) == 2
+    assert L.pex_vec_stat(X, None, 4, 16, 64, 5, 7, S, S, S, 0x4000, 1 << 20, None) == 3
+    assert L.pex_vec_stat(X + 2, None, 4, 16, 64, 0, 7, S, S, S, 0x4000, 1 << 20, None) == 5
+    assert L.pex_vec_stat(X, None, 4, 16, 64, 0, 7, S, S, S, None, 0, None) == 6
+    assert L.pex_vec_stat(X, None, 4, 16, 64, 0, 7, S, S, S, 0x4000, 16, None) == 6
     assert L.pex_token_sq(X, None, *ok, 0, S, None, 0, None) == 1
     assert L.pex_token_sq(X, G, 4, 0, 64, 64, 0, S, None, 0, None) == 2
 

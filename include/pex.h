@@ -115,6 +115,31 @@ pex_status pex_vec_stat(const void *A, const void *C, int64_t B, int64_t T, int6
                         pex_stream_t stream);
 
 /*
+ * Norms and clipping (Sec. 2.1 names clipping among the statistics of interest; Sec. 2.3 the squared norms).
+ *
+ * pex_example_norms -- N[b] = || X_b^T G_b ||_F^2, the squared norm of every per-example gradient of the layer.
+ *   N [B] fp32 device, overwritten.  One per-example contraction; M_b stays in registers, each workgroup adds its
+ *   tile's share of the norm to a small partial-sum buffer in the workspace ([tiles * 8][B] floats), a second kernel
+ *   sums the shares in a fixed order.
+ * pex_weighted_sum -- S = sum_b w[b] * X_b^T G_b with one weight per example (w [B] fp32 device, read-only).  With
+ *   w[b] = min(1, c / ||g_b||), ||g_b||^2 the sum of N[b] over the layers of the model, this is the clipped gradient
+ *   sum; with w = 1 it is pex_stat(identity).  Workspace as for pex_stat.
+ * pex_token_norms -- N_tok[b*T + t] = || x_bt ||^2 * || g_bt ||^2, the per-sample per-token norms of Sec. 2.3 (the
+ *   squared norm of the rank-one term x_bt g_bt^T).  N_tok [B*T] fp32 device, overwritten; no workspace; bound by
+ *   HBM bandwidth (X and G read once).
+ * Same input conventions, limits and error codes as pex_stat.
+ */
+size_t pex_example_norms_workspace_bytes(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt);
+pex_status pex_example_norms(const void *X, const void *G, int64_t B, int64_t T, int64_t din, int64_t dout,
+                             pex_dtype dt, float *N, void *workspace, size_t workspace_bytes, pex_stream_t stream);
+size_t pex_weighted_sum_workspace_bytes(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt);
+pex_status pex_weighted_sum(const void *X, const void *G, const float *w, int64_t B, int64_t T, int64_t din,
+                            int64_t dout, pex_dtype dt, float *S, void *workspace, size_t workspace_bytes,
+                            pex_stream_t stream);
+pex_status pex_token_norms(const void *X, const void *G, int64_t B, int64_t T, int64_t din, int64_t dout,
+                           pex_dtype dt, float *N_tok, pex_stream_t stream);
+
+/*
  * pex_token_sq -- S_tok = (X o X)^T (G o G) = sum_{b,t} (x_bt o x_bt)(g_bt o g_bt)^T  (Sec. 2.3,
  * "per-token second moments").  A proxy statistic: tokens are not independent computational paths in a
  * transformer, so this is not a per-token gradient second moment.

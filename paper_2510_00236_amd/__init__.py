@@ -29,6 +29,8 @@ WANT = {"identity": PEX_WANT_IDENTITY, "square": PEX_WANT_SQUARE, "sign": PEX_WA
 
 EXPORTS = ("pex_status_string", "pex_version", "pex_stat_workspace_bytes", "pex_stat",
            "pex_stat_multi_workspace_bytes", "pex_stat_multi", "pex_vec_stat_workspace_bytes", "pex_vec_stat",
+           "pex_example_norms_workspace_bytes", "pex_example_norms", "pex_weighted_sum_workspace_bytes",
+           "pex_weighted_sum", "pex_token_norms",
            "pex_token_sq_workspace_bytes", "pex_token_sq", "pex_adam_update", "pex_signsgd_update")
 
 
@@ -72,6 +74,15 @@ def lib() -> ctypes.CDLL:
         L.pex_vec_stat_workspace_bytes.restype = sz
         L.pex_vec_stat.argtypes = [p, p, i64, i64, i64, ctypes.c_int, ctypes.c_uint32, p, p, p, p, sz, p]
         L.pex_vec_stat.restype = ctypes.c_int
+        for fn in (L.pex_example_norms_workspace_bytes, L.pex_weighted_sum_workspace_bytes):
+            fn.argtypes = [i64, i64, i64, i64, ctypes.c_int]
+            fn.restype = sz
+        L.pex_example_norms.argtypes = [p, p, i64, i64, i64, i64, ctypes.c_int, p, p, sz, p]
+        L.pex_example_norms.restype = ctypes.c_int
+        L.pex_weighted_sum.argtypes = [p, p, p, i64, i64, i64, i64, ctypes.c_int, p, p, sz, p]
+        L.pex_weighted_sum.restype = ctypes.c_int
+        L.pex_token_norms.argtypes = [p, p, i64, i64, i64, i64, ctypes.c_int, p, p]
+        L.pex_token_norms.restype = ctypes.c_int
         L.pex_token_sq_workspace_bytes.argtypes = [i64, i64, i64, i64, ctypes.c_int]
         L.pex_token_sq_workspace_bytes.restype = sz
         L.pex_token_sq.argtypes = [p, p, i64, i64, i64, i64, ctypes.c_int, p, p, sz, p]
@@ -222,6 +233,45 @@ def pex_vec_stat(A, C=None, want=("identity", "square", "sign"), out=None, works
     _check(lib().pex_vec_stat(_dev(A, "A"), _dev(C, "C") if C is not None else None, B, T, d, dt, mask,
                               ptrs[0], ptrs[1], ptrs[2], wptr, wbytes, _stream(stream)))
     return res
+
+
+def pex_example_norms(X, G, N=None, workspace=None, stream=None):
+    """N[B] = ||X_b^T G_b||_F^2, fp32."""
+    import torch
+    B, T, din, dout = _shapes(X, G)
+    dt = _dtype_code(X)
+    if N is None:
+        N = torch.empty(B, dtype=torch.float32, device=X.device)
+    ws, wptr, wbytes = _workspace(int(lib().pex_example_norms_workspace_bytes(B, T, din, dout, dt)), X, workspace)
+    _check(lib().pex_example_norms(_dev(X, "X"), _dev(G, "G"), B, T, din, dout, dt, _dev(N, "N"), wptr, wbytes,
+                                   _stream(stream)))
+    return N
+
+
+def pex_weighted_sum(X, G, w, S=None, workspace=None, stream=None):
+    """S[din,dout] = sum_b w[b] X_b^T G_b, fp32 (``w`` fp32 [B] on the GPU)."""
+    import torch
+    B, T, din, dout = _shapes(X, G)
+    dt = _dtype_code(X)
+    if w.dtype != torch.float32 or w.numel() != B:
+        raise ValueError("w must be float32 with one weight per example")
+    if S is None:
+        S = torch.empty(din, dout, dtype=torch.float32, device=X.device)
+    ws, wptr, wbytes = _workspace(int(lib().pex_weighted_sum_workspace_bytes(B, T, din, dout, dt)), X, workspace)
+    _check(lib().pex_weighted_sum(_dev(X, "X"), _dev(G, "G"), _dev(w, "w"), B, T, din, dout, dt, _dev(S, "S"), wptr,
+                                  wbytes, _stream(stream)))
+    return S
+
+
+def pex_token_norms(X, G, N_tok=None, stream=None):
+    """N_tok[B,T] = ||x_bt||^2 ||g_bt||^2, fp32."""
+    import torch
+    B, T, din, dout = _shapes(X, G)
+    dt = _dtype_code(X)
+    if N_tok is None:
+        N_tok = torch.empty(B, T, dtype=torch.float32, device=X.device)
+    _check(lib().pex_token_norms(_dev(X, "X"), _dev(G, "G"), B, T, din, dout, dt, _dev(N_tok, "N_tok"), _stream(stream)))
+    return N_tok
 
 
 def pex_token_sq(X, G, S=None, workspace=None, stream=None):

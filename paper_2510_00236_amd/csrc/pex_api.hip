@@ -16,7 +16,7 @@ static int env_int(const char* name, int dflt)
 StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt, Mode mode)
 {
     StatPlan p{};
-    const bool per_example = (mode == MODE_SQUARE || mode == MODE_SIGN);
+    const bool per_example = (mode == MODE_SQUARE || mode == MODE_SIGN || mode == MODE_NORMS || mode == MODE_WEIGHTED);
     // PEX_FORCE_GENERIC=1 routes bf16 through the SIMT kernel (a tuning/debugging aid, not a fallback:
     // both kernels are device code of this library).
     const bool force_generic = env_int("PEX_FORCE_GENERIC", 0) != 0;
@@ -78,6 +78,8 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
             p.presq_bytes = (((size_t)B * (size_t)T * (size_t)(din + dout) * 2) + 255) & ~(size_t)255;
     }
     p.ws_bytes = p.presq_bytes + (nsplit > 1 ? (size_t)nsplit * (size_t)din * (size_t)dout * sizeof(float) : 0);
+    if (mode == MODE_NORMS)   // no S at all: one partial of ||M_b||^2 per tile (and wave) and example
+        p.ws_bytes = (size_t)(p.kernel == 1 ? bf16_norm_partials(din, dout) : generic_norm_partials(din, dout)) * (size_t)B * sizeof(float);
     return p;
 }
 
@@ -94,7 +96,8 @@ static pex_status check_stat_args(const void* X, const void* G, int64_t B, int64
 }
 
 static pex_status run_stat(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt,
-                           Mode mode, float* S, void* workspace, size_t workspace_bytes, hipStream_t stream)
+                           Mode mode, float* S, void* workspace, size_t workspace_bytes, hipStream_t stream,
+                           const float* weight = nullptr)
 {
     const StatPlan plan = plan_stat(B, T, din, dout, dt, mode);
     float* out = S;
@@ -112,6 +115,9 @@ static pex_status run_stat(const void* X, const void* G, int64_t B, int64_t T, i
         e = launch_square_bf16(X, x2, B * T * din, stream);
         if (e == hipSuccess) e = launch_square_bf16(G, g2, B * T * dout, stream);
         if (e == hipSuccess) e = launch_stat_bf16(x2, g2, B, T, din, dout, MODE_IDENTITY, plan, out, stream);
+    } else if (mode == MODE_WEIGHTED) {
+        e = plan.kernel == 1 ? launch_weighted_bf16(X, G, weight, B, T, din, dout, plan, out, stream)
+                             : launch_stat_generic(X, G, B, T, din, dout, dt, mode, plan, out, stream, weight, nullptr);
     } else if (plan.kernel == 1) e = launch_stat_bf16(X, G, B, T, din, dout, mode, plan, out, stream);
     else e = launch_stat_generic(X, G, B, T, din, dout, dt, mode, plan, out, stream);
     if (e != hipSuccess) return PEX_ERR_HIP;
@@ -277,6 +283,65 @@ pex_status pex_vec_stat(const void* A, const void* C, int64_t B, int64_t T, int6
                    hipSuccess
                ? PEX_OK
                : PEX_ERR_HIP;
+}
+
+size_t pex_example_norms_workspace_bytes(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt)
+{
+    if (B < 1 || T < 1 || din < 1 || dout < 1) return 0;
+    if (dt != PEX_F32 && dt != PEX_BF16) return 0;
+    return plan_stat(B, T, din, dout, dt, MODE_NORMS).ws_bytes;
+}
+
+pex_status pex_example_norms(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt,
+                             float* N, void* workspace, size_t workspace_bytes, pex_stream_t stream)
+{
+    pex_status st = check_stat_args(X, G, B, T, din, dout, dt, (const float*)0x10);
+    if (st != PEX_OK) return st;
+    if (!N) return PEX_ERR_NULL;
+    if ((uintptr_t)N & 3u) return PEX_ERR_ALIGN;
+    const StatPlan plan = plan_stat(B, T, din, dout, dt, MODE_NORMS);
+    if (!workspace || workspace_bytes < plan.ws_bytes) return PEX_ERR_WORKSPACE;
+    if ((uintptr_t)workspace & 15u) return PEX_ERR_ALIGN;
+    hipStream_t hs = (hipStream_t)stream;
+    float* partial = (float*)workspace;
+    hipError_t e;
+    int64_t nparts;
+    if (plan.kernel == 1) {
+        nparts = bf16_norm_partials(din, dout);
+        e = launch_norms_bf16(X, G, B, T, din, dout, plan, partial, hs);
+    } else {
+        nparts = generic_norm_partials(din, dout);
+        e = launch_stat_generic(X, G, B, T, din, dout, dt, MODE_NORMS, plan, nullptr, hs, nullptr, partial);
+    }
+    if (e != hipSuccess) return PEX_ERR_HIP;
+    return launch_reduce_norms(partial, nparts, B, N, hs) == hipSuccess ? PEX_OK : PEX_ERR_HIP;
+}
+
+size_t pex_weighted_sum_workspace_bytes(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt)
+{
+    if (B < 1 || T < 1 || din < 1 || dout < 1) return 0;
+    if (dt != PEX_F32 && dt != PEX_BF16) return 0;
+    return plan_stat(B, T, din, dout, dt, MODE_WEIGHTED).ws_bytes;
+}
+
+pex_status pex_weighted_sum(const void* X, const void* G, const float* w, int64_t B, int64_t T, int64_t din, int64_t dout,
+                            pex_dtype dt, float* S, void* workspace, size_t workspace_bytes, pex_stream_t stream)
+{
+    const pex_status st = check_stat_args(X, G, B, T, din, dout, dt, S);
+    if (st != PEX_OK) return st;
+    if (!w) return PEX_ERR_NULL;
+    if ((uintptr_t)w & 3u) return PEX_ERR_ALIGN;
+    return run_stat(X, G, B, T, din, dout, dt, MODE_WEIGHTED, S, workspace, workspace_bytes, (hipStream_t)stream, w);
+}
+
+pex_status pex_token_norms(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt,
+                           float* N_tok, pex_stream_t stream)
+{
+    const pex_status st = check_stat_args(X, G, B, T, din, dout, dt, (const float*)0x10);
+    if (st != PEX_OK) return st;
+    if (!N_tok) return PEX_ERR_NULL;
+    if ((uintptr_t)N_tok & 3u) return PEX_ERR_ALIGN;
+    return launch_token_norms(X, G, B * T, din, dout, dt, N_tok, (hipStream_t)stream) == hipSuccess ? PEX_OK : PEX_ERR_HIP;
 }
 
 size_t pex_token_sq_workspace_bytes(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt)

@@ -12,7 +12,8 @@ namespace pex {
 
 // Which statistic a contraction kernel produces.  PHI_* match pex_phi; TOKEN_SQ is the per-token
 // square (operands squared on the load path, one plain contraction over K = B*T).
-enum Mode : int { MODE_IDENTITY = 0, MODE_SQUARE = 1, MODE_SIGN = 2, MODE_TOKEN_SQ = 3 };
+// MODE_NORMS (per-example squared norms, no S) and MODE_WEIGHTED (sum_b w_b M_b) are per-example passes too.
+enum Mode : int { MODE_IDENTITY = 0, MODE_SQUARE = 1, MODE_SIGN = 2, MODE_TOKEN_SQ = 3, MODE_NORMS = 4, MODE_WEIGHTED = 5 };
 
 // How one call is carried out.  Chosen on the host from the shape alone, so the workspace query and
 // the launch always agree.
@@ -27,8 +28,22 @@ struct StatPlan {
 StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt, Mode mode);
 
 // Launchers.  `out` is S when plan.nsplit == 1, else the workspace holding [nsplit][din][dout] partials.
+// MODE_WEIGHTED reads one weight per example from `weight`; MODE_NORMS writes no S but one partial of ||M_b||^2 per
+// tile (generic kernel) into norm_partial[tile][B].
 hipError_t launch_stat_generic(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout,
-                               pex_dtype dt, Mode mode, const StatPlan& plan, float* out, hipStream_t stream);
+                               pex_dtype dt, Mode mode, const StatPlan& plan, float* out, hipStream_t stream,
+                               const float* weight = nullptr, float* norm_partial = nullptr);
+int64_t generic_norm_partials(int64_t din, int64_t dout);
+int64_t bf16_norm_partials(int64_t din, int64_t dout);
+hipError_t launch_norms_bf16(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout, const StatPlan& plan,
+                             float* norm_partial, hipStream_t stream);
+hipError_t launch_weighted_bf16(const void* X, const void* G, const float* w, int64_t B, int64_t T, int64_t din, int64_t dout,
+                                const StatPlan& plan, float* out, hipStream_t stream);
+// N[b] = sum_{p < nparts} partial[p][b], p ascending
+hipError_t launch_reduce_norms(const float* partial, int64_t nparts, int64_t B, float* N, hipStream_t stream);
+// N_tok[r] = |x_r|^2 |g_r|^2 for every row r of the flattened [B*T] axis
+hipError_t launch_token_norms(const void* X, const void* G, int64_t rows, int64_t din, int64_t dout, pex_dtype dt, float* N_tok,
+                              hipStream_t stream);
 hipError_t launch_stat_bf16(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout,
                             Mode mode, const StatPlan& plan, float* out, hipStream_t stream);
 // Two per-example statistics from one contraction; exactly one of the three outputs is NULL.  Uses the block

@@ -56,7 +56,10 @@ namespace {
 // OUT_SIGN_U8 as four biased byte counters per register: each example adds sign+1 in {0,1,2}, so a byte never
 // borrows from its neighbour and holds up to 127 examples; the count is byte - examples.  A quarter of the
 // registers of an fp32 tile, which is what lets identity, square and sign share one contraction.
-constexpr int OUT_ID = 1, OUT_SQ = 2, OUT_SIGN_PK = 4, OUT_SIGN_F32 = 8, OUT_TOKEN = 16, OUT_SIGN_U8 = 32;
+// OUT_NORM writes ||M_b||_F^2 of every example (one partial per tile and wave, summed by a second kernel);
+// OUT_IDW is the identity statistic with one weight per example, sum_b w_b M_b (what clipping needs).
+constexpr int OUT_ID = 1, OUT_SQ = 2, OUT_SIGN_PK = 4, OUT_SIGN_F32 = 8, OUT_TOKEN = 16, OUT_SIGN_U8 = 32, OUT_NORM = 64,
+              OUT_IDW = 128;
 constexpr int MAX_U8_EXAMPLES = 127;
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
@@ -127,12 +130,14 @@ __device__ __forceinline__ float sign_as_float(float m)
 // at most 2048 examples is exact, at half the registers of an fp32 tile.
 template <int OUTS>
 __device__ __forceinline__ void fold_tile(float16_t& acc, float16_t& acc_id, float16_t& acc_sq, float16_t& acc_sg, half2_t (&cnt)[8],
-                                          uint32_t (&cnt8)[4])
+                                          uint32_t (&cnt8)[4], float weight, float& norm)
 {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const float m = acc[r];
         if (OUTS & OUT_ID) acc_id[r] += m;
+        if (OUTS & OUT_IDW) acc_id[r] = fmaf(weight, m, acc_id[r]);
+        if (OUTS & OUT_NORM) norm = fmaf(m, m, norm);
         if (OUTS & OUT_SQ) acc_sq[r] = fmaf(m, m, acc_sq[r]);
         if (OUTS & OUT_SIGN_F32) acc_sg[r] += sign_as_float(m);
     }
@@ -204,17 +209,20 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
                                                               int64_t rows_total, int seg_len, int din, int dout,
                                                               int64_t rows_per_split, int tiles_m, int tiles_n,
                                                               float* __restrict__ out_id, float* __restrict__ out_sq,
-                                                              float* __restrict__ out_sg)
+                                                              float* __restrict__ out_sg, const float* __restrict__ weight,
+                                                              float* __restrict__ norm_partial, int examples_total)
 {
     constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK, NS = TL::NS, FM = TL::FM, FN = TL::FN, KS = TL::KS;
     constexpr int XROW = TL::XROW, GROW = TL::GROW, NXI = TL::NXI, NGI = TL::NGI, RX = TL::RX, RG = TL::RG;
     constexpr int LPS = TL::LPS, FPK = TL::FPK, RC = TL::RC;
     constexpr bool TOKEN = (OUTS == OUT_TOKEN);
     constexpr bool PER_EXAMPLE = !(OUTS == OUT_ID || OUTS == OUT_TOKEN);
-    constexpr bool HAS_ID = PER_EXAMPLE && (OUTS & OUT_ID), HAS_SQ = (OUTS & OUT_SQ) != 0;
+    constexpr bool HAS_W = (OUTS & OUT_IDW) != 0, HAS_NORM = (OUTS & OUT_NORM) != 0;
+    constexpr bool HAS_ID = (PER_EXAMPLE && (OUTS & OUT_ID)) || HAS_W, HAS_SQ = (OUTS & OUT_SQ) != 0;
     constexpr bool HAS_PK = (OUTS & OUT_SIGN_PK) != 0, HAS_SF = (OUTS & OUT_SIGN_F32) != 0, HAS_U8 = (OUTS & OUT_SIGN_U8) != 0;
     static_assert(!TOKEN || NS >= 4, "the per-token square needs its slab one phase earlier");
-    static_assert(HAS_PK + HAS_SF + HAS_U8 <= 1 && (OUTS & 63) == OUTS && OUTS != 0, "one representation of the sign counts");
+    static_assert(HAS_PK + HAS_SF + HAS_U8 <= 1 && (OUTS & 255) == OUTS && OUTS != 0, "one representation of the sign counts");
+    static_assert(!(HAS_W && (OUTS & OUT_ID)), "identity is either weighted or not");
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
 
     int split, tm, tn;
@@ -387,7 +395,11 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
                 }
         __builtin_amdgcn_s_setprio(0);
     };
+    // end of an example: fold every tile; the example's number is needed for its weight and its norm
+    int example = (int)(row_begin / (seg_len > 0 ? seg_len : 1));
     auto fold_all = [&]() {
+        float w = 1.0f, norm = 0.f;
+        if constexpr (HAS_W) w = weight[example];
 #pragma unroll
         for (int a = 0; a < FM; ++a)
 #pragma unroll
@@ -395,7 +407,14 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
                 if constexpr (PER_EXAMPLE)
                     fold_tile<OUTS>(acc[a][c], acc_id[HAS_ID ? a : 0][HAS_ID ? c : 0], acc_sq[HAS_SQ ? a : 0][HAS_SQ ? c : 0],
                                     acc_sg[HAS_SF ? a : 0][HAS_SF ? c : 0], cnt[HAS_PK ? a : 0][HAS_PK ? c : 0],
-                                    cnt8[HAS_U8 ? a : 0][HAS_U8 ? c : 0]);
+                                    cnt8[HAS_U8 ? a : 0][HAS_U8 ? c : 0], w, norm);
+        if constexpr (HAS_NORM) {
+            // this wave's part of ||M_b||^2 for this tile: lanes summed in a fixed butterfly order
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) norm += __shfl_xor(norm, off);
+            if (lane == 0) norm_partial[((int64_t)(tm * tiles_n + tn) * TL::NWAVES + wave) * examples_total + example] = norm;
+        }
+        ++example;
     };
 
     constexpr int AHEAD0 = NS - 2, AHEAD1 = NS - 1;   // slabs a group has issued before its first phase
@@ -484,7 +503,8 @@ using TilePhi = Bf16Tile<256, 128, 64, 64, 32, 4, 4>;
 
 template <typename TL, int OUTS>
 hipError_t launch_one(const uint16_t* X, const uint16_t* G, int64_t B, int64_t T, int64_t din, int64_t dout,
-                      const StatPlan& plan, float* out_id, float* out_sq, float* out_sg, hipStream_t stream)
+                      const StatPlan& plan, float* out_id, float* out_sq, float* out_sg, hipStream_t stream,
+                      const float* weight = nullptr, float* norm_partial = nullptr)
 {
     constexpr bool PER_EXAMPLE = !(OUTS == OUT_ID || OUTS == OUT_TOKEN);
     const int tiles_m = (int)((din + TL::BM - 1) / TL::BM), tiles_n = (int)((dout + TL::BN - 1) / TL::BN);
@@ -498,7 +518,7 @@ hipError_t launch_one(const uint16_t* X, const uint16_t* G, int64_t B, int64_t T
     }
     const dim3 grid((unsigned)(tiles_m * tiles_n * plan.nsplit)), block(TL::NT);
     kern<<<grid, block, TL::LDS_BYTES, stream>>>(X, G, B * T, (int)T, (int)din, (int)dout, rows_per_split, tiles_m,
-                                                 tiles_n, out_id, out_sq, out_sg);
+                                                 tiles_n, out_id, out_sq, out_sg, weight, norm_partial, (int)B);
     return hipGetLastError();
 }
 
@@ -509,7 +529,7 @@ bool sign_is_packed(int64_t B) { return B <= 2048; }
 
 void bf16_tile_shape(Mode mode, int64_t B, int* bm, int* bn)
 {
-    if (mode == MODE_IDENTITY || mode == MODE_TOKEN_SQ || (mode == MODE_SIGN && sign_is_packed(B))) { *bm = TileWide::BM; *bn = TileWide::BN; }
+    if (mode == MODE_IDENTITY || mode == MODE_TOKEN_SQ || mode == MODE_NORMS || (mode == MODE_SIGN && sign_is_packed(B))) { *bm = TileWide::BM; *bn = TileWide::BN; }
     else { *bm = TilePhi::BM; *bn = TilePhi::BN; }
 }
 
@@ -546,6 +566,28 @@ hipError_t launch_stat_bf16(const void* X, const void* G, int64_t B, int64_t T, 
         return launch_one<TilePhi, OUT_SIGN_F32>(x, g, B, T, din, dout, plan, nullptr, nullptr, out, stream);
     default: return hipErrorInvalidValue;
     }
+}
+
+// N partial sums of ||M_b||_F^2: [tiles][8 waves][B]; tiles of the 256 x 256 block shape
+int64_t bf16_norm_partials(int64_t din, int64_t dout)
+{
+    return ((din + TileWide::BM - 1) / TileWide::BM) * ((dout + TileWide::BN - 1) / TileWide::BN) * TileWide::NWAVES;
+}
+
+// per-example squared norms: a per-example contraction on the large tile whose only output is the norm partials
+hipError_t launch_norms_bf16(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout, const StatPlan& plan,
+                             float* norm_partial, hipStream_t stream)
+{
+    return launch_one<TileWide, OUT_NORM>((const uint16_t*)X, (const uint16_t*)G, B, T, din, dout, plan, nullptr, nullptr, nullptr, stream,
+                                          nullptr, norm_partial);
+}
+
+// S = sum_b w_b M_b (two register tiles: block shape of phi = square)
+hipError_t launch_weighted_bf16(const void* X, const void* G, const float* w, int64_t B, int64_t T, int64_t din, int64_t dout,
+                                const StatPlan& plan, float* out, hipStream_t stream)
+{
+    return launch_one<TilePhi, OUT_IDW>((const uint16_t*)X, (const uint16_t*)G, B, T, din, dout, plan, out, nullptr, nullptr, stream, w,
+                                        nullptr);
 }
 
 // Identity, square and sign from one contraction: possible while a group of examples fits the byte counters.

@@ -1,7 +1,7 @@
 // pex_stat_generic.hip -- shape-agnostic SIMT kernel for S = sum_b phi(X_b^T G_b) and the per-token
 // square.  Handles any B, T, din, dout >= 1 and both storage types with true fp32 products; it is the
 // path for fp32 inputs and for bf16 shapes the MFMA kernel does not take.  Latency/ALU bound by design:
-// the tuned path lives in pex_stat_mfma.hip.
+// the tuned path lives in pex_stat_bf16.hip.
 //
 // One workgroup (16 x 16 lanes) owns a 64 x 64 tile of S for one group of examples.  For each example it
 // walks the sequence in slabs of 16 tokens staged through LDS, keeps the running tile of M_b in registers
@@ -17,8 +17,9 @@ constexpr int TM = 64, TN = 64, TK = 16, NTHREADS = 256;
 __device__ __forceinline__ float load_as_float(const float* p) { return *p; }
 __device__ __forceinline__ float load_as_float(const uint16_t* p) { return __uint_as_float(((uint32_t)*p) << 16); }
 
+// end of an example: acc2 += phi(M_b) (weighted identity for MODE_WEIGHTED), norm += ||M_b||^2 of this lane's part
 template <int MODE>
-__device__ __forceinline__ void fold(float (&acc2)[4][4], float (&acc)[4][4])
+__device__ __forceinline__ void fold(float (&acc2)[4][4], float (&acc)[4][4], float w, float& norm)
 {
 #pragma unroll
     for (int a = 0; a < 4; ++a)
@@ -27,6 +28,8 @@ __device__ __forceinline__ void fold(float (&acc2)[4][4], float (&acc)[4][4])
             const float m = acc[a][c];
             if (MODE == MODE_SQUARE) acc2[a][c] = fmaf(m, m, acc2[a][c]);
             else if (MODE == MODE_SIGN) acc2[a][c] += (float)((m > 0.f) - (m < 0.f));
+            else if (MODE == MODE_WEIGHTED) acc2[a][c] = fmaf(w, m, acc2[a][c]);
+            else if (MODE == MODE_NORMS) norm = fmaf(m, m, norm);
             acc[a][c] = 0.f;
         }
 }
@@ -36,10 +39,13 @@ __device__ __forceinline__ void fold(float (&acc2)[4][4], float (&acc)[4][4])
 template <typename TIn, int MODE>
 __global__ __launch_bounds__(NTHREADS) void stat_generic_kernel(const TIn* __restrict__ X, const TIn* __restrict__ G,
                                                                 int64_t rows_total, int64_t T, int din, int dout,
-                                                                int64_t rows_per_split, float* __restrict__ out)
+                                                                int64_t rows_per_split, float* __restrict__ out,
+                                                                const float* __restrict__ weight,
+                                                                float* __restrict__ norm_partial, int examples_total)
 {
     __shared__ float sX[TK][TM + 4];
     __shared__ float sG[TK][TN + 4];
+    __shared__ float sN[NTHREADS];
 
     const int tid = threadIdx.x;
     const int tx = tid % 16, ty = tid / 16;
@@ -48,7 +54,7 @@ __global__ __launch_bounds__(NTHREADS) void stat_generic_kernel(const TIn* __res
     int64_t row_end = row_begin + rows_per_split;
     if (row_end > rows_total) row_end = rows_total;
 
-    constexpr bool PER_EXAMPLE = (MODE == MODE_SQUARE || MODE == MODE_SIGN);
+    constexpr bool PER_EXAMPLE = (MODE == MODE_SQUARE || MODE == MODE_SIGN || MODE == MODE_NORMS || MODE == MODE_WEIGHTED);
     float acc[4][4], acc2[4][4];
 #pragma unroll
     for (int a = 0; a < 4; ++a)
@@ -88,8 +94,23 @@ __global__ __launch_bounds__(NTHREADS) void stat_generic_kernel(const TIn* __res
             }
             __syncthreads();
         }
-        if (PER_EXAMPLE) fold<MODE>(acc2, acc);
+        if (PER_EXAMPLE) {
+            const int example = (int)(seg / T);
+            float norm = 0.f;
+            fold<MODE>(acc2, acc, MODE == MODE_WEIGHTED ? weight[example] : 1.0f, norm);
+            if (MODE == MODE_NORMS) {
+                // this tile's part of ||M_b||^2: fixed-order tree over the 256 lanes
+                sN[tid] = norm;
+                __syncthreads();
+                for (int h = NTHREADS / 2; h >= 1; h >>= 1) {
+                    if (tid < h) sN[tid] += sN[tid + h];
+                    __syncthreads();
+                }
+                if (tid == 0) norm_partial[((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * examples_total + example] = sN[0];
+            }
+        }
     }
+    if (MODE == MODE_NORMS) return;
 
     float* dst = out + (int64_t)blockIdx.z * din * dout;
 #pragma unroll
@@ -106,25 +127,31 @@ __global__ __launch_bounds__(NTHREADS) void stat_generic_kernel(const TIn* __res
 
 template <typename TIn>
 hipError_t launch_typed(const TIn* X, const TIn* G, int64_t B, int64_t T, int64_t din, int64_t dout, Mode mode,
-                        const StatPlan& plan, float* out, hipStream_t stream)
+                        const StatPlan& plan, float* out, hipStream_t stream, const float* weight, float* norm_partial)
 {
     const dim3 grid((unsigned)((dout + TN - 1) / TN), (unsigned)((din + TM - 1) / TM), (unsigned)plan.nsplit);
     const dim3 block(NTHREADS);
     const int64_t rows_total = B * T;
-    const bool per_example = (mode == MODE_SQUARE || mode == MODE_SIGN);
+    const bool per_example = (mode == MODE_SQUARE || mode == MODE_SIGN || mode == MODE_NORMS || mode == MODE_WEIGHTED);
     const int64_t rows_per_split = per_example ? plan.per_split * T : plan.per_split;
     switch (mode) {
     case MODE_IDENTITY:
-        stat_generic_kernel<TIn, MODE_IDENTITY><<<grid, block, 0, stream>>>(X, G, rows_total, T, (int)din, (int)dout, rows_per_split, out);
+        stat_generic_kernel<TIn, MODE_IDENTITY><<<grid, block, 0, stream>>>(X, G, rows_total, T, (int)din, (int)dout, rows_per_split, out, weight, norm_partial, (int)B);
         break;
     case MODE_SQUARE:
-        stat_generic_kernel<TIn, MODE_SQUARE><<<grid, block, 0, stream>>>(X, G, rows_total, T, (int)din, (int)dout, rows_per_split, out);
+        stat_generic_kernel<TIn, MODE_SQUARE><<<grid, block, 0, stream>>>(X, G, rows_total, T, (int)din, (int)dout, rows_per_split, out, weight, norm_partial, (int)B);
         break;
     case MODE_SIGN:
-        stat_generic_kernel<TIn, MODE_SIGN><<<grid, block, 0, stream>>>(X, G, rows_total, T, (int)din, (int)dout, rows_per_split, out);
+        stat_generic_kernel<TIn, MODE_SIGN><<<grid, block, 0, stream>>>(X, G, rows_total, T, (int)din, (int)dout, rows_per_split, out, weight, norm_partial, (int)B);
+        break;
+    case MODE_NORMS:
+        stat_generic_kernel<TIn, MODE_NORMS><<<grid, block, 0, stream>>>(X, G, rows_total, T, (int)din, (int)dout, rows_per_split, out, weight, norm_partial, (int)B);
+        break;
+    case MODE_WEIGHTED:
+        stat_generic_kernel<TIn, MODE_WEIGHTED><<<grid, block, 0, stream>>>(X, G, rows_total, T, (int)din, (int)dout, rows_per_split, out, weight, norm_partial, (int)B);
         break;
     case MODE_TOKEN_SQ:
-        stat_generic_kernel<TIn, MODE_TOKEN_SQ><<<grid, block, 0, stream>>>(X, G, rows_total, T, (int)din, (int)dout, rows_per_split, out);
+        stat_generic_kernel<TIn, MODE_TOKEN_SQ><<<grid, block, 0, stream>>>(X, G, rows_total, T, (int)din, (int)dout, rows_per_split, out, weight, norm_partial, (int)B);
         break;
     }
     return hipGetLastError();
@@ -144,11 +171,100 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
 }  // namespace
 
 hipError_t launch_stat_generic(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout,
-                               pex_dtype dt, Mode mode, const StatPlan& plan, float* out, hipStream_t stream)
+                               pex_dtype dt, Mode mode, const StatPlan& plan, float* out, hipStream_t stream,
+                               const float* weight, float* norm_partial)
 {
     if (dt == PEX_F32)
-        return launch_typed((const float*)X, (const float*)G, B, T, din, dout, mode, plan, out, stream);
-    return launch_typed((const uint16_t*)X, (const uint16_t*)G, B, T, din, dout, mode, plan, out, stream);
+        return launch_typed((const float*)X, (const float*)G, B, T, din, dout, mode, plan, out, stream, weight, norm_partial);
+    return launch_typed((const uint16_t*)X, (const uint16_t*)G, B, T, din, dout, mode, plan, out, stream, weight, norm_partial);
+}
+
+int64_t generic_norm_partials(int64_t din, int64_t dout) { return ((din + TM - 1) / TM) * ((dout + TN - 1) / TN); }
+
+namespace {
+
+// one block per example: lanes sum a strided subset in ascending order, then a fixed-order tree
+__global__ __launch_bounds__(256) void reduce_norms_kernel(const float* __restrict__ partial, int64_t nparts, int64_t B,
+                                                           float* __restrict__ N)
+{
+    __shared__ float red[256];
+    const int64_t b = blockIdx.x;
+    float s = 0.f;
+    for (int64_t p = threadIdx.x; p < nparts; p += 256) s += partial[p * B + b];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int h = 128; h >= 1; h >>= 1) {
+        if ((int)threadIdx.x < h) red[threadIdx.x] += red[threadIdx.x + h];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) N[b] = red[0];
+}
+
+// sum of squares of n values starting at p, this lane's share: 16-byte loads when WIDE, scalar otherwise
+template <typename TIn, bool WIDE>
+__device__ __forceinline__ float lane_sumsq(const TIn* p, int64_t n, int lane)
+{
+    float s = 0.f;
+    if constexpr (WIDE) {
+        typedef __attribute__((ext_vector_type(4))) unsigned int u4;
+        constexpr int PER = 16 / (int)sizeof(TIn);
+        for (int64_t i = (int64_t)lane * PER; i < n; i += 64 * PER) {
+            const u4 raw = __builtin_nontemporal_load((const u4*)(p + i));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if constexpr (sizeof(TIn) == 2) {
+                    const float lo = __uint_as_float(raw[e] << 16), hi = __uint_as_float(raw[e] & 0xffff0000u);
+                    s = fmaf(lo, lo, s);
+                    s = fmaf(hi, hi, s);
+                } else {
+                    const float v = __uint_as_float(raw[e]);
+                    s = fmaf(v, v, s);
+                }
+            }
+        }
+    } else {
+        for (int64_t i = lane; i < n; i += 64) { const float v = load_as_float(p + i); s = fmaf(v, v, s); }
+    }
+    return s;
+}
+
+// one wave per row: |x_r|^2 * |g_r|^2, lanes stride over the features, butterfly sum
+template <typename TIn, bool WIDE>
+__global__ __launch_bounds__(256) void token_norms_kernel(const TIn* __restrict__ X, const TIn* __restrict__ G, int64_t rows,
+                                                          int64_t din, int64_t dout, float* __restrict__ N_tok)
+{
+    const int lane = threadIdx.x % 64;
+    const int64_t r = (int64_t)blockIdx.x * 4 + threadIdx.x / 64;
+    if (r >= rows) return;
+    float sx = lane_sumsq<TIn, WIDE>(X + r * din, din, lane);
+    float sg = lane_sumsq<TIn, WIDE>(G + r * dout, dout, lane);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) { sx += __shfl_xor(sx, off); sg += __shfl_xor(sg, off); }
+    if (lane == 0) N_tok[r] = sx * sg;
+}
+
+}  // namespace
+
+hipError_t launch_reduce_norms(const float* partial, int64_t nparts, int64_t B, float* N, hipStream_t stream)
+{
+    reduce_norms_kernel<<<dim3((unsigned)B), dim3(256), 0, stream>>>(partial, nparts, B, N);
+    return hipGetLastError();
+}
+
+hipError_t launch_token_norms(const void* X, const void* G, int64_t rows, int64_t din, int64_t dout, pex_dtype dt, float* N_tok,
+                              hipStream_t stream)
+{
+    const dim3 grid((unsigned)((rows + 3) / 4)), block(256);
+    const int per = dt == PEX_F32 ? 4 : 8;
+    const bool wide = din % per == 0 && dout % per == 0 && ((((uintptr_t)X | (uintptr_t)G) & 15u) == 0);
+    if (dt == PEX_F32) {
+        if (wide) token_norms_kernel<float, true><<<grid, block, 0, stream>>>((const float*)X, (const float*)G, rows, din, dout, N_tok);
+        else token_norms_kernel<float, false><<<grid, block, 0, stream>>>((const float*)X, (const float*)G, rows, din, dout, N_tok);
+    } else {
+        if (wide) token_norms_kernel<uint16_t, true><<<grid, block, 0, stream>>>((const uint16_t*)X, (const uint16_t*)G, rows, din, dout, N_tok);
+        else token_norms_kernel<uint16_t, false><<<grid, block, 0, stream>>>((const uint16_t*)X, (const uint16_t*)G, rows, din, dout, N_tok);
+    }
+    return hipGetLastError();
 }
 
 hipError_t launch_reduce_partials(const float* partial, int nsplit, int64_t n, float* S, hipStream_t stream)

@@ -1,0 +1,79 @@
+"""GPU parity of per-example norms, per-token norms and clipping-weighted sums against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2510_00236_amd as pex
+import synth_inputs as si
+from oracle import norms as on
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+SHAPES = [
+    (5, 77, 520, 264, "bf16"),     # several tiles, ragged edges, batch split over workgroups
+    (3, 100, 200, 136, "bf16"),
+    (7, 33, 256, 128, "bf16"),
+    (2, 37, 70, 33, "bf16"),       # SIMT kernel on bf16
+    (3, 50, 129, 65, "f32"),
+    (1, 64, 96, 160, "bf16"),
+    (40, 1, 128, 96, "bf16"),
+    (1, 1, 1, 1, "f32"),
+]
+
+
+@pytest.mark.parametrize("B,T,din,dout,dtype", SHAPES)
+def test_norms_and_weighted_sums(B, T, din, dout, dtype):
+    X, G = si.custom(B, T, din, dout, dtype=dtype, seed=B * 7 + T)
+    Xd, Gd = X.to(DEV), G.to(DEV)
+    Xn, Gn = si.widen(X), si.widen(G)
+    # per-example norms: sums of din*dout squares of fp32-accumulated entries, all terms >= 0
+    N = pex.pex_example_norms(Xd, Gd)
+    torch.cuda.synchronize()
+    ref = on.example_norms(Xn, Gn)
+    assert np.abs(N.cpu().double().numpy() - ref).max() <= 2e-5 * ref.max(), (N, ref)
+    assert (np.abs(N.cpu().double().numpy() - ref) <= 1e-4 * ref + 1e-30).all()
+    # per-token norms
+    Nt = pex.pex_token_norms(Xd, Gd).cpu().double().numpy()
+    rt = on.token_norms(Xn, Gn)
+    assert (np.abs(Nt - rt) <= 1e-5 * rt + 1e-30).all()
+    # clipping weights from the norms, then the weighted sum
+    c = float(np.sqrt(np.median(ref)))
+    w = on.clip_weights(ref, c).astype(np.float32)
+    S = pex.pex_weighted_sum(Xd, Gd, torch.from_numpy(w).to(DEV)).cpu().double().numpy()
+    rs = on.weighted_sum(Xn, Gn, w.astype(np.float64))
+    assert np.abs(S - rs).max() <= 2e-5 * max(np.abs(rs).max(), 1e-300)
+
+
+def test_unit_weights_reproduce_the_identity_statistic_and_integers_are_exact():
+    X, G = si.integer_valued(6, 40, 264, 136, dtype="bf16", seed=11)
+    Xd, Gd = X.to(DEV), G.to(DEV)
+    S = pex.pex_weighted_sum(Xd, Gd, torch.ones(6, device=DEV))
+    assert torch.equal(S, pex.pex_stat(Xd, Gd, "identity"))
+    w = torch.tensor([2.0, 0.0, -1.0, 0.5, 4.0, 1.0])
+    S = pex.pex_weighted_sum(Xd, Gd, w.to(DEV)).cpu().double().numpy()
+    assert np.array_equal(S, on.weighted_sum(si.widen(X), si.widen(G), w.double().numpy()))
+    assert np.array_equal(pex.pex_token_norms(Xd, Gd).cpu().double().numpy(), on.token_norms(si.widen(X), si.widen(G)))
+    # norms stay below 2^24 on a small layer, so fp32 holds them exactly whatever the summation order
+    X, G = si.integer_valued(3, 8, 32, 40, dtype="bf16", seed=12)
+    ref = on.example_norms(si.widen(X), si.widen(G))
+    assert ref.max() < 2 ** 24
+    assert np.array_equal(pex.pex_example_norms(X.to(DEV), G.to(DEV)).cpu().double().numpy(), ref)
+
+
+def test_norms_sum_to_the_total_of_the_square_statistic_at_full_size():
+    """At the GPT-2 attention-projection size the oracle cannot materialise M_b quickly, but sum_b N_b must equal the
+    total of S_sq, and sum_bt N_bt the total of the per-token square (both computed by other kernels)."""
+    w = si.WORKLOADS["c3_gpt2_proj"]
+    X, G = si.make(w, seed=0)
+    Xd, Gd = X.to(DEV), G.to(DEV)
+    N = pex.pex_example_norms(Xd, Gd).double()
+    S_sq = pex.pex_stat(Xd, Gd, "square").double()
+    assert abs(float(N.sum()) - float(S_sq.sum())) <= 1e-5 * float(S_sq.sum())
+    Nt = pex.pex_token_norms(Xd, Gd).double()
+    assert Nt.shape == (w.B, w.T)
+    # the per-token square rounds each squared operand to bf16, the norms do not: 2^-7 band
+    tok = pex.pex_token_sq(Xd, Gd).double()
+    assert abs(float(Nt.sum()) - float(tok.sum())) <= 1e-2 * float(tok.sum())
+    again = pex.pex_example_norms(Xd, Gd).double()
+    assert torch.equal(N, again)

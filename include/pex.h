@@ -115,6 +115,17 @@ pex_status pex_vec_stat(const void *A, const void *C, int64_t B, int64_t T, int6
                         pex_stream_t stream);
 
 /*
+ * pex_stat_power -- S = sum_b |X_b^T G_b|^alpha elementwise, 0 < alpha <= 64 (PEX_ERR_PHI otherwise): the power
+ * nonlinearities phi(s) = s^alpha that Sec. 2.3 names beside square and sign (alpha = 2 is phi = square, alpha = 1
+ * the mean absolute gradient).  Each term is 2^(alpha * log2 |m|) through the hardware log2 / exp2 instructions:
+ * relative error of a term about 1e-6 * alpha * |log2 m|; all terms are >= 0.  Buffers as for pex_stat.
+ */
+size_t pex_stat_power_workspace_bytes(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt);
+pex_status pex_stat_power(const void *X, const void *G, int64_t B, int64_t T, int64_t din, int64_t dout,
+                          pex_dtype dt, float alpha, float *S, void *workspace, size_t workspace_bytes,
+                          pex_stream_t stream);
+
+/*
  * Norms and clipping (Sec. 2.1 names clipping among the statistics of interest; Sec. 2.3 the squared norms).
  *
  * pex_example_norms -- N[b] = || X_b^T G_b ||_F^2, the squared norm of every per-example gradient of the layer.
@@ -189,6 +200,21 @@ pex_status pex_adam_update(float *theta, float *m, float *v, const float *S_id, 
 pex_status pex_signsgd_update(float *theta, float *m, const float *S_sign, int64_t n, float lr,
                               float beta, float weight_decay, int32_t B, int32_t debias, int64_t step,
                               pex_stream_t stream);
+
+/*
+ * pex_sign_update -- the three placements of sign in SignSGD with momentum that Sec. 3.1 compares, in place:
+ *   PEX_MICROSIGNSGD  EMA o avg o sign : S = sum_b sgn(g_b) (pex_stat phi = sign);  m <- beta*m + (1-beta)*S/B;
+ *                                        theta <- theta - lr*d - weight_decay*theta, d = debias ? m/(1-beta^step) : m
+ *   PEX_SIGNSGD       EMA o sign o avg : S = sum_b g_b (phi = identity);            m <- beta*m + (1-beta)*sgn(S); same step
+ *   PEX_SIGNEMA       sign o EMA o avg : S = sum_b g_b;                             m <- beta*m + (1-beta)*S/B;
+ *                                        theta <- theta - lr*sgn(m) - weight_decay*theta  (debias cannot change a sign)
+ * sgn(0) = 0.  theta, m, S: fp32 device arrays of n elements, 16-byte aligned.  B >= 1, step >= 1.
+ * pex_signsgd_update is this call with PEX_MICROSIGNSGD.
+ */
+typedef enum { PEX_MICROSIGNSGD = 0, PEX_SIGNSGD = 1, PEX_SIGNEMA = 2 } pex_sign_variant;
+pex_status pex_sign_update(float *theta, float *m, const float *S, int64_t n, pex_sign_variant variant, float lr,
+                           float beta, float weight_decay, int32_t B, int32_t debias, int64_t step,
+                           pex_stream_t stream);
 
 #ifdef __cplusplus
 }

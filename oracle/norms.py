@@ -52,6 +52,15 @@ def weighted_sum(X, G, w) -> np.ndarray:
     return S
 
 
+def power_stat(X, G, alpha: float) -> np.ndarray:
+    """sum_b |X_b^T G_b|^alpha elementwise: the power nonlinearity phi(s) = s^alpha of Sec. 2.3 on a sequence layer."""
+    X, G = _f64(X), _f64(G)
+    S = np.zeros((X.shape[2], G.shape[2]))
+    for b in range(X.shape[0]):
+        S += np.abs(X[b].T @ G[b]) ** alpha
+    return S
+
+
 def clip_weights(norms_sq, c) -> np.ndarray:
     """w_b = min(1, c / ||g_b||): the factor of the clipping nonlinearity for squared norms ``norms_sq``."""
     n = np.sqrt(np.asarray(norms_sq, dtype=np.float64))

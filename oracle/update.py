@@ -23,7 +23,8 @@ notation, with these readings where the printed listing is garbled or silent:
 * grad_scale / sq_scale turn the sums S_id, S_sq into the mean gradient mu_t and
   nu_micro (1/B and 1/B when the cotangents are those of the summed loss).
 
-``microsignsgd_step`` is Sec. 3.1: EMA o avg o sign.
+``microsignsgd_step`` is Sec. 3.1: EMA o avg o sign; ``sign_family_step`` covers the three orderings of
+avg, EMA and sign that Sec. 3.1 compares (SignEMA, SignSGD, MicroSignSGD).
 """
 from __future__ import annotations
 
@@ -95,5 +96,34 @@ def microsignsgd_step(theta, m, S_sign, lr: float, beta: float, weight_decay: fl
     avg_sign = np.asarray(S_sign, dtype=np.float64) / float(B)
     m_t = beta * m + (1.0 - beta) * avg_sign
     d = m_t / (1.0 - beta ** step) if debias else m_t
+    theta_t = theta - lr * d - weight_decay * theta
+    return theta_t, m_t
+
+
+MICROSIGNSGD, SIGNSGD, SIGNEMA = 0, 1, 2
+
+
+def sign_family_step(theta, m, S, variant: int, lr: float, beta: float, weight_decay: float, B: int,
+                     debias: bool, step: int):
+    """One step of the three placements of sign in SignSGD (Sec. 3.1); returns new (theta, m).
+
+      MicroSignSGD = EMA o avg o sign : S is the sum of per-example signs;   m <- EMA(S/B),        step along m
+      SignSGD      = EMA o sign o avg : S is the sum of gradients;           m <- EMA(sign(S/B)),  step along m
+      SignEMA      = sign o EMA o avg : S is the sum of gradients;           m <- EMA(S/B),        step along sign(m)
+    Weight decay is decoupled and not multiplied by the learning rate (App. D).  ``debias`` divides the EMA by
+    1 - beta^t before it is used (for SignEMA this cannot change the sign and is ignored).
+    """
+    theta = np.asarray(theta, dtype=np.float64)
+    m = np.asarray(m, dtype=np.float64)
+    avg = np.asarray(S, dtype=np.float64) / float(B)
+    if variant == SIGNSGD:
+        avg = np.sign(avg)
+    elif variant not in (MICROSIGNSGD, SIGNEMA):
+        raise ValueError(f"unknown variant {variant}")
+    m_t = beta * m + (1.0 - beta) * avg
+    if variant == SIGNEMA:
+        d = np.sign(m_t)
+    else:
+        d = m_t / (1.0 - beta ** step) if debias else m_t
     theta_t = theta - lr * d - weight_decay * theta
     return theta_t, m_t

@@ -21,6 +21,8 @@ PEX_F32, PEX_BF16 = 0, 1
 PEX_PHI_IDENTITY, PEX_PHI_SQUARE, PEX_PHI_SIGN = 0, 1, 2
 PEX_ADAM, PEX_MICROADAM, PEX_MICROADAM_VAR, PEX_MICROADAM_MSQ = 0, 1, 2, 3
 PHI = {"identity": PEX_PHI_IDENTITY, "square": PEX_PHI_SQUARE, "sign": PEX_PHI_SIGN}
+PEX_MICROSIGNSGD, PEX_SIGNSGD, PEX_SIGNEMA = 0, 1, 2
+SIGN_VARIANT = {"microsignsgd": PEX_MICROSIGNSGD, "signsgd": PEX_SIGNSGD, "signema": PEX_SIGNEMA}
 VARIANT = {"adam": PEX_ADAM, "microadam": PEX_MICROADAM, "microadam_var": PEX_MICROADAM_VAR,
            "microadam_msq": PEX_MICROADAM_MSQ}
 
@@ -30,7 +32,8 @@ WANT = {"identity": PEX_WANT_IDENTITY, "square": PEX_WANT_SQUARE, "sign": PEX_WA
 EXPORTS = ("pex_status_string", "pex_version", "pex_stat_workspace_bytes", "pex_stat",
            "pex_stat_multi_workspace_bytes", "pex_stat_multi", "pex_vec_stat_workspace_bytes", "pex_vec_stat",
            "pex_example_norms_workspace_bytes", "pex_example_norms", "pex_weighted_sum_workspace_bytes",
-           "pex_weighted_sum", "pex_token_norms",
+           "pex_weighted_sum", "pex_token_norms", "pex_sign_update",
+           "pex_stat_power_workspace_bytes", "pex_stat_power",
            "pex_token_sq_workspace_bytes", "pex_token_sq", "pex_adam_update", "pex_signsgd_update")
 
 
@@ -81,6 +84,10 @@ def lib() -> ctypes.CDLL:
         L.pex_example_norms.restype = ctypes.c_int
         L.pex_weighted_sum.argtypes = [p, p, p, i64, i64, i64, i64, ctypes.c_int, p, p, sz, p]
         L.pex_weighted_sum.restype = ctypes.c_int
+        L.pex_stat_power_workspace_bytes.argtypes = [i64, i64, i64, i64, ctypes.c_int]
+        L.pex_stat_power_workspace_bytes.restype = sz
+        L.pex_stat_power.argtypes = [p, p, i64, i64, i64, i64, ctypes.c_int, f, p, p, sz, p]
+        L.pex_stat_power.restype = ctypes.c_int
         L.pex_token_norms.argtypes = [p, p, i64, i64, i64, i64, ctypes.c_int, p, p]
         L.pex_token_norms.restype = ctypes.c_int
         L.pex_token_sq_workspace_bytes.argtypes = [i64, i64, i64, i64, ctypes.c_int]
@@ -91,6 +98,8 @@ def lib() -> ctypes.CDLL:
         L.pex_adam_update.restype = ctypes.c_int
         L.pex_signsgd_update.argtypes = [p, p, p, i64, f, f, f, i32, i32, i64, p]
         L.pex_signsgd_update.restype = ctypes.c_int
+        L.pex_sign_update.argtypes = [p, p, p, i64, ctypes.c_int, f, f, f, i32, i32, i64, p]
+        L.pex_sign_update.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -263,6 +272,19 @@ def pex_weighted_sum(X, G, w, S=None, workspace=None, stream=None):
     return S
 
 
+def pex_stat_power(X, G, alpha, S=None, workspace=None, stream=None):
+    """S[din,dout] = sum_b |X_b^T G_b|^alpha, fp32."""
+    import torch
+    B, T, din, dout = _shapes(X, G)
+    dt = _dtype_code(X)
+    if S is None:
+        S = torch.empty(din, dout, dtype=torch.float32, device=X.device)
+    ws, wptr, wbytes = _workspace(int(lib().pex_stat_power_workspace_bytes(B, T, din, dout, dt)), X, workspace)
+    _check(lib().pex_stat_power(_dev(X, "X"), _dev(G, "G"), B, T, din, dout, dt, float(alpha), _dev(S, "S"), wptr,
+                                wbytes, _stream(stream)))
+    return S
+
+
 def pex_token_norms(X, G, N_tok=None, stream=None):
     """N_tok[B,T] = ||x_bt||^2 ||g_bt||^2, fp32."""
     import torch
@@ -306,3 +328,13 @@ def pex_signsgd_update(theta, m, S_sign, lr, beta, weight_decay, B, debias=False
         raise ValueError("theta, m and S_sign must have the same number of elements")
     _check(lib().pex_signsgd_update(_dev(theta, "theta"), _dev(m, "m"), _dev(S_sign, "S_sign"), n, lr, beta,
                                     weight_decay, int(B), int(bool(debias)), int(step), _stream(stream)))
+
+
+def pex_sign_update(theta, m, S, variant, lr, beta, weight_decay, B, debias=False, step=1, stream=None):
+    """One in-place step of 'microsignsgd' | 'signsgd' | 'signema' (Sec. 3.1); S is the sum of per-example signs for
+    the first and the sum of gradients for the other two."""
+    n = theta.numel()
+    if m.numel() != n or S.numel() != n:
+        raise ValueError("theta, m and S must have the same number of elements")
+    _check(lib().pex_sign_update(_dev(theta, "theta"), _dev(m, "m"), _dev(S, "S"), n, SIGN_VARIANT.get(variant, variant),
+                                 lr, beta, weight_decay, int(B), int(bool(debias)), int(step), _stream(stream)))

@@ -16,7 +16,7 @@ static int env_int(const char* name, int dflt)
 StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt, Mode mode)
 {
     StatPlan p{};
-    const bool per_example = (mode == MODE_SQUARE || mode == MODE_SIGN || mode == MODE_NORMS || mode == MODE_WEIGHTED);
+    const bool per_example = (mode == MODE_SQUARE || mode == MODE_SIGN || mode == MODE_NORMS || mode == MODE_WEIGHTED || mode == MODE_POWER);
     // PEX_FORCE_GENERIC=1 routes bf16 through the SIMT kernel (a tuning/debugging aid, not a fallback:
     // both kernels are device code of this library).
     const bool force_generic = env_int("PEX_FORCE_GENERIC", 0) != 0;
@@ -97,7 +97,7 @@ static pex_status check_stat_args(const void* X, const void* G, int64_t B, int64
 
 static pex_status run_stat(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt,
                            Mode mode, float* S, void* workspace, size_t workspace_bytes, hipStream_t stream,
-                           const float* weight = nullptr)
+                           const float* weight = nullptr, float alpha = 0.f)
 {
     const StatPlan plan = plan_stat(B, T, din, dout, dt, mode);
     float* out = S;
@@ -115,6 +115,9 @@ static pex_status run_stat(const void* X, const void* G, int64_t B, int64_t T, i
         e = launch_square_bf16(X, x2, B * T * din, stream);
         if (e == hipSuccess) e = launch_square_bf16(G, g2, B * T * dout, stream);
         if (e == hipSuccess) e = launch_stat_bf16(x2, g2, B, T, din, dout, MODE_IDENTITY, plan, out, stream);
+    } else if (mode == MODE_POWER) {
+        e = plan.kernel == 1 ? launch_power_bf16(X, G, alpha, B, T, din, dout, plan, out, stream)
+                             : launch_stat_generic(X, G, B, T, din, dout, dt, mode, plan, out, stream, nullptr, nullptr, alpha);
     } else if (mode == MODE_WEIGHTED) {
         e = plan.kernel == 1 ? launch_weighted_bf16(X, G, weight, B, T, din, dout, plan, out, stream)
                              : launch_stat_generic(X, G, B, T, din, dout, dt, mode, plan, out, stream, weight, nullptr);
@@ -334,6 +337,22 @@ pex_status pex_weighted_sum(const void* X, const void* G, const float* w, int64_
     return run_stat(X, G, B, T, din, dout, dt, MODE_WEIGHTED, S, workspace, workspace_bytes, (hipStream_t)stream, w);
 }
 
+size_t pex_stat_power_workspace_bytes(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt)
+{
+    if (B < 1 || T < 1 || din < 1 || dout < 1) return 0;
+    if (dt != PEX_F32 && dt != PEX_BF16) return 0;
+    return plan_stat(B, T, din, dout, dt, MODE_POWER).ws_bytes;
+}
+
+pex_status pex_stat_power(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt,
+                          float alpha, float* S, void* workspace, size_t workspace_bytes, pex_stream_t stream)
+{
+    const pex_status st = check_stat_args(X, G, B, T, din, dout, dt, S);
+    if (st != PEX_OK) return st;
+    if (!(alpha > 0.f) || !(alpha <= 64.f)) return PEX_ERR_PHI;
+    return run_stat(X, G, B, T, din, dout, dt, MODE_POWER, S, workspace, workspace_bytes, (hipStream_t)stream, nullptr, alpha);
+}
+
 pex_status pex_token_norms(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt,
                            float* N_tok, pex_stream_t stream)
 {
@@ -373,16 +392,22 @@ pex_status pex_adam_update(float* theta, float* m, float* v, const float* S_id, 
                                                                                                            : PEX_ERR_HIP;
 }
 
+pex_status pex_sign_update(float* theta, float* m, const float* S, int64_t n, pex_sign_variant variant, float lr, float beta,
+                           float weight_decay, int32_t B, int32_t debias, int64_t step, pex_stream_t stream)
+{
+    if (!theta || !m || !S) return PEX_ERR_NULL;
+    if (variant != PEX_MICROSIGNSGD && variant != PEX_SIGNSGD && variant != PEX_SIGNEMA) return PEX_ERR_PHI;
+    if (n < 1 || B < 1 || step < 1) return PEX_ERR_SHAPE;
+    if (((uintptr_t)theta | (uintptr_t)m | (uintptr_t)S) & 15u) return PEX_ERR_ALIGN;
+    return launch_sign_update(theta, m, S, n, variant, lr, beta, weight_decay, B, debias, step, (hipStream_t)stream) == hipSuccess
+               ? PEX_OK
+               : PEX_ERR_HIP;
+}
+
 pex_status pex_signsgd_update(float* theta, float* m, const float* S_sign, int64_t n, float lr, float beta,
                               float weight_decay, int32_t B, int32_t debias, int64_t step, pex_stream_t stream)
 {
-    if (!theta || !m || !S_sign) return PEX_ERR_NULL;
-    if (n < 1 || B < 1 || step < 1) return PEX_ERR_SHAPE;
-    if (((uintptr_t)theta | (uintptr_t)m | (uintptr_t)S_sign) & 15u) return PEX_ERR_ALIGN;
-    return launch_signsgd_update(theta, m, S_sign, n, lr, beta, weight_decay, B, debias, step, (hipStream_t)stream) ==
-                   hipSuccess
-               ? PEX_OK
-               : PEX_ERR_HIP;
+    return pex_sign_update(theta, m, S_sign, n, PEX_MICROSIGNSGD, lr, beta, weight_decay, B, debias, step, stream);
 }
 
 }  // extern "C"

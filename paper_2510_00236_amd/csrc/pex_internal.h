@@ -13,7 +13,8 @@ namespace pex {
 // Which statistic a contraction kernel produces.  PHI_* match pex_phi; TOKEN_SQ is the per-token
 // square (operands squared on the load path, one plain contraction over K = B*T).
 // MODE_NORMS (per-example squared norms, no S) and MODE_WEIGHTED (sum_b w_b M_b) are per-example passes too.
-enum Mode : int { MODE_IDENTITY = 0, MODE_SQUARE = 1, MODE_SIGN = 2, MODE_TOKEN_SQ = 3, MODE_NORMS = 4, MODE_WEIGHTED = 5 };
+// MODE_POWER is phi(m) = |m|^alpha.
+enum Mode : int { MODE_IDENTITY = 0, MODE_SQUARE = 1, MODE_SIGN = 2, MODE_TOKEN_SQ = 3, MODE_NORMS = 4, MODE_WEIGHTED = 5, MODE_POWER = 6 };
 
 // How one call is carried out.  Chosen on the host from the shape alone, so the workspace query and
 // the launch always agree.
@@ -32,7 +33,9 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
 // tile (generic kernel) into norm_partial[tile][B].
 hipError_t launch_stat_generic(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout,
                                pex_dtype dt, Mode mode, const StatPlan& plan, float* out, hipStream_t stream,
-                               const float* weight = nullptr, float* norm_partial = nullptr);
+                               const float* weight = nullptr, float* norm_partial = nullptr, float alpha = 0.f);
+hipError_t launch_power_bf16(const void* X, const void* G, float alpha, int64_t B, int64_t T, int64_t din, int64_t dout,
+                             const StatPlan& plan, float* out, hipStream_t stream);
 int64_t generic_norm_partials(int64_t din, int64_t dout);
 int64_t bf16_norm_partials(int64_t din, int64_t dout);
 hipError_t launch_norms_bf16(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout, const StatPlan& plan,
@@ -76,7 +79,7 @@ hipError_t launch_reduce_partials(const float* partial, int nsplit, int64_t n, f
 
 hipError_t launch_adam_update(float* theta, float* m, float* v, const float* S_id, const float* S_sq, int64_t n,
                               pex_adam_variant variant, const pex_adam_params& p, hipStream_t stream);
-hipError_t launch_signsgd_update(float* theta, float* m, const float* S_sign, int64_t n, float lr, float beta,
-                                 float weight_decay, int32_t B, int32_t debias, int64_t step, hipStream_t stream);
+hipError_t launch_sign_update(float* theta, float* m, const float* S, int64_t n, pex_sign_variant variant, float lr, float beta,
+                              float weight_decay, int32_t B, int32_t debias, int64_t step, hipStream_t stream);
 
 }  // namespace pex

@@ -58,8 +58,9 @@ namespace {
 // registers of an fp32 tile, which is what lets identity, square and sign share one contraction.
 // OUT_NORM writes ||M_b||_F^2 of every example (one partial per tile and wave, summed by a second kernel);
 // OUT_IDW is the identity statistic with one weight per example, sum_b w_b M_b (what clipping needs).
+// OUT_POW is phi(m) = |m|^alpha through the hardware log2 / exp2 (relative error of a term about 1e-6 * alpha * |log2 m|).
 constexpr int OUT_ID = 1, OUT_SQ = 2, OUT_SIGN_PK = 4, OUT_SIGN_F32 = 8, OUT_TOKEN = 16, OUT_SIGN_U8 = 32, OUT_NORM = 64,
-              OUT_IDW = 128;
+              OUT_IDW = 128, OUT_POW = 256;
 constexpr int MAX_U8_EXAMPLES = 127;
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
@@ -125,6 +126,12 @@ __device__ __forceinline__ float sign_as_float(float m)
     return __builtin_amdgcn_fmed3f(__builtin_ldexpf(m, 200), -1.0f, 1.0f);
 }
 
+// |m|^alpha = 2^(alpha * log2 |m|), alpha > 0; zero stays zero (log2 0 = -inf, 2^-inf = 0)
+__device__ __forceinline__ float abs_power(float m, float alpha)
+{
+    return __builtin_amdgcn_exp2f(alpha * __builtin_amdgcn_logf(__builtin_fabsf(m)));
+}
+
 // End of an example, one finished 32x32 tile of M_b: every requested statistic takes its phi(M_b), M_b restarts
 // from 0.  Sign counts of a tile as 8 fp16 pairs per lane: integers up to 2048 are exact in fp16, so the count of
 // at most 2048 examples is exact, at half the registers of an fp32 tile.
@@ -139,6 +146,7 @@ __device__ __forceinline__ void fold_tile(float16_t& acc, float16_t& acc_id, flo
         if (OUTS & OUT_IDW) acc_id[r] = fmaf(weight, m, acc_id[r]);
         if (OUTS & OUT_NORM) norm = fmaf(m, m, norm);
         if (OUTS & OUT_SQ) acc_sq[r] = fmaf(m, m, acc_sq[r]);
+        if (OUTS & OUT_POW) acc_sq[r] += abs_power(m, weight);        // the exponent travels in the weight slot
         if (OUTS & OUT_SIGN_F32) acc_sg[r] += sign_as_float(m);
     }
     if (OUTS & OUT_SIGN_PK) {
@@ -210,7 +218,7 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
                                                               int64_t rows_per_split, int tiles_m, int tiles_n,
                                                               float* __restrict__ out_id, float* __restrict__ out_sq,
                                                               float* __restrict__ out_sg, const float* __restrict__ weight,
-                                                              float* __restrict__ norm_partial, int examples_total)
+                                                              float* __restrict__ norm_partial, int examples_total, float alpha)
 {
     constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK, NS = TL::NS, FM = TL::FM, FN = TL::FN, KS = TL::KS;
     constexpr int XROW = TL::XROW, GROW = TL::GROW, NXI = TL::NXI, NGI = TL::NGI, RX = TL::RX, RG = TL::RG;
@@ -218,11 +226,13 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
     constexpr bool TOKEN = (OUTS == OUT_TOKEN);
     constexpr bool PER_EXAMPLE = !(OUTS == OUT_ID || OUTS == OUT_TOKEN);
     constexpr bool HAS_W = (OUTS & OUT_IDW) != 0, HAS_NORM = (OUTS & OUT_NORM) != 0;
-    constexpr bool HAS_ID = (PER_EXAMPLE && (OUTS & OUT_ID)) || HAS_W, HAS_SQ = (OUTS & OUT_SQ) != 0;
+    constexpr bool HAS_POW = (OUTS & OUT_POW) != 0;
+    constexpr bool HAS_ID = (PER_EXAMPLE && (OUTS & OUT_ID)) || HAS_W, HAS_SQ = (OUTS & OUT_SQ) != 0 || HAS_POW;
     constexpr bool HAS_PK = (OUTS & OUT_SIGN_PK) != 0, HAS_SF = (OUTS & OUT_SIGN_F32) != 0, HAS_U8 = (OUTS & OUT_SIGN_U8) != 0;
     static_assert(!TOKEN || NS >= 4, "the per-token square needs its slab one phase earlier");
-    static_assert(HAS_PK + HAS_SF + HAS_U8 <= 1 && (OUTS & 255) == OUTS && OUTS != 0, "one representation of the sign counts");
+    static_assert(HAS_PK + HAS_SF + HAS_U8 <= 1 && (OUTS & 511) == OUTS && OUTS != 0, "one representation of the sign counts");
     static_assert(!(HAS_W && (OUTS & OUT_ID)), "identity is either weighted or not");
+    static_assert(!(HAS_POW && ((OUTS & OUT_SQ) || HAS_W)), "the power statistic uses the square's register tile and the weight slot");
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
 
     int split, tm, tn;
@@ -400,6 +410,7 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
     auto fold_all = [&]() {
         float w = 1.0f, norm = 0.f;
         if constexpr (HAS_W) w = weight[example];
+        if constexpr (HAS_POW) w = alpha;
 #pragma unroll
         for (int a = 0; a < FM; ++a)
 #pragma unroll
@@ -504,7 +515,7 @@ using TilePhi = Bf16Tile<256, 128, 64, 64, 32, 4, 4>;
 template <typename TL, int OUTS>
 hipError_t launch_one(const uint16_t* X, const uint16_t* G, int64_t B, int64_t T, int64_t din, int64_t dout,
                       const StatPlan& plan, float* out_id, float* out_sq, float* out_sg, hipStream_t stream,
-                      const float* weight = nullptr, float* norm_partial = nullptr)
+                      const float* weight = nullptr, float* norm_partial = nullptr, float alpha = 0.f)
 {
     constexpr bool PER_EXAMPLE = !(OUTS == OUT_ID || OUTS == OUT_TOKEN);
     const int tiles_m = (int)((din + TL::BM - 1) / TL::BM), tiles_n = (int)((dout + TL::BN - 1) / TL::BN);
@@ -518,7 +529,7 @@ hipError_t launch_one(const uint16_t* X, const uint16_t* G, int64_t B, int64_t T
     }
     const dim3 grid((unsigned)(tiles_m * tiles_n * plan.nsplit)), block(TL::NT);
     kern<<<grid, block, TL::LDS_BYTES, stream>>>(X, G, B * T, (int)T, (int)din, (int)dout, rows_per_split, tiles_m,
-                                                 tiles_n, out_id, out_sq, out_sg, weight, norm_partial, (int)B);
+                                                 tiles_n, out_id, out_sq, out_sg, weight, norm_partial, (int)B, alpha);
     return hipGetLastError();
 }
 
@@ -588,6 +599,14 @@ hipError_t launch_weighted_bf16(const void* X, const void* G, const float* w, in
 {
     return launch_one<TilePhi, OUT_IDW>((const uint16_t*)X, (const uint16_t*)G, B, T, din, dout, plan, out, nullptr, nullptr, stream, w,
                                         nullptr);
+}
+
+// S = sum_b |M_b|^alpha
+hipError_t launch_power_bf16(const void* X, const void* G, float alpha, int64_t B, int64_t T, int64_t din, int64_t dout,
+                             const StatPlan& plan, float* out, hipStream_t stream)
+{
+    return launch_one<TilePhi, OUT_POW>((const uint16_t*)X, (const uint16_t*)G, B, T, din, dout, plan, nullptr, out, nullptr, stream,
+                                        nullptr, nullptr, alpha);
 }
 
 // Identity, square and sign from one contraction: possible while a group of examples fits the byte counters.

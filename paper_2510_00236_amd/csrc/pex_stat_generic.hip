@@ -29,6 +29,7 @@ __device__ __forceinline__ void fold(float (&acc2)[4][4], float (&acc)[4][4], fl
             if (MODE == MODE_SQUARE) acc2[a][c] = fmaf(m, m, acc2[a][c]);
             else if (MODE == MODE_SIGN) acc2[a][c] += (float)((m > 0.f) - (m < 0.f));
             else if (MODE == MODE_WEIGHTED) acc2[a][c] = fmaf(w, m, acc2[a][c]);
+            else if (MODE == MODE_POWER) acc2[a][c] += __builtin_amdgcn_exp2f(w * __builtin_amdgcn_logf(__builtin_fabsf(m)));
             else if (MODE == MODE_NORMS) norm = fmaf(m, m, norm);
             acc[a][c] = 0.f;
         }
@@ -41,7 +42,7 @@ __global__ __launch_bounds__(NTHREADS) void stat_generic_kernel(const TIn* __res
                                                                 int64_t rows_total, int64_t T, int din, int dout,
                                                                 int64_t rows_per_split, float* __restrict__ out,
                                                                 const float* __restrict__ weight,
-                                                                float* __restrict__ norm_partial, int examples_total)
+                                                                float* __restrict__ norm_partial, int examples_total, float alpha)
 {
     __shared__ float sX[TK][TM + 4];
     __shared__ float sG[TK][TN + 4];
@@ -54,7 +55,7 @@ __global__ __launch_bounds__(NTHREADS) void stat_generic_kernel(const TIn* __res
     int64_t row_end = row_begin + rows_per_split;
     if (row_end > rows_total) row_end = rows_total;
 
-    constexpr bool PER_EXAMPLE = (MODE == MODE_SQUARE || MODE == MODE_SIGN || MODE == MODE_NORMS || MODE == MODE_WEIGHTED);
+    constexpr bool PER_EXAMPLE = (MODE == MODE_SQUARE || MODE == MODE_SIGN || MODE == MODE_NORMS || MODE == MODE_WEIGHTED || MODE == MODE_POWER);
     float acc[4][4], acc2[4][4];
 #pragma unroll
     for (int a = 0; a < 4; ++a)
@@ -97,7 +98,7 @@ __global__ __launch_bounds__(NTHREADS) void stat_generic_kernel(const TIn* __res
         if (PER_EXAMPLE) {
             const int example = (int)(seg / T);
             float norm = 0.f;
-            fold<MODE>(acc2, acc, MODE == MODE_WEIGHTED ? weight[example] : 1.0f, norm);
+            fold<MODE>(acc2, acc, MODE == MODE_WEIGHTED ? weight[example] : (MODE == MODE_POWER ? alpha : 1.0f), norm);
             if (MODE == MODE_NORMS) {
                 // this tile's part of ||M_b||^2: fixed-order tree over the 256 lanes
                 sN[tid] = norm;
@@ -127,31 +128,34 @@ __global__ __launch_bounds__(NTHREADS) void stat_generic_kernel(const TIn* __res
 
 template <typename TIn>
 hipError_t launch_typed(const TIn* X, const TIn* G, int64_t B, int64_t T, int64_t din, int64_t dout, Mode mode,
-                        const StatPlan& plan, float* out, hipStream_t stream, const float* weight, float* norm_partial)
+                        const StatPlan& plan, float* out, hipStream_t stream, const float* weight, float* norm_partial, float alpha)
 {
     const dim3 grid((unsigned)((dout + TN - 1) / TN), (unsigned)((din + TM - 1) / TM), (unsigned)plan.nsplit);
     const dim3 block(NTHREADS);
     const int64_t rows_total = B * T;
-    const bool per_example = (mode == MODE_SQUARE || mode == MODE_SIGN || mode == MODE_NORMS || mode == MODE_WEIGHTED);
+    const bool per_example = (mode == MODE_SQUARE || mode == MODE_SIGN || mode == MODE_NORMS || mode == MODE_WEIGHTED || mode == MODE_POWER);
     const int64_t rows_per_split = per_example ? plan.per_split * T : plan.per_split;
     switch (mode) {
     case MODE_IDENTITY:
-        stat_generic_kernel<TIn, MODE_IDENTITY><<<grid, block, 0, stream>>>(X, G, rows_total, T, (int)din, (int)dout, rows_per_split, out, weight, norm_partial, (int)B);
+        stat_generic_kernel<TIn, MODE_IDENTITY><<<grid, block, 0, stream>>>(X, G, rows_total, T, (int)din, (int)dout, rows_per_split, out, weight, norm_partial, (int)B, alpha);
         break;
     case MODE_SQUARE:
-        stat_generic_kernel<TIn, MODE_SQUARE><<<grid, block, 0, stream>>>(X, G, rows_total, T, (int)din, (int)dout, rows_per_split, out, weight, norm_partial, (int)B);
+        stat_generic_kernel<TIn, MODE_SQUARE><<<grid, block, 0, stream>>>(X, G, rows_total, T, (int)din, (int)dout, rows_per_split, out, weight, norm_partial, (int)B, alpha);
         break;
     case MODE_SIGN:
-        stat_generic_kernel<TIn, MODE_SIGN><<<grid, block, 0, stream>>>(X, G, rows_total, T, (int)din, (int)dout, rows_per_split, out, weight, norm_partial, (int)B);
+        stat_generic_kernel<TIn, MODE_SIGN><<<grid, block, 0, stream>>>(X, G, rows_total, T, (int)din, (int)dout, rows_per_split, out, weight, norm_partial, (int)B, alpha);
         break;
     case MODE_NORMS:
-        stat_generic_kernel<TIn, MODE_NORMS><<<grid, block, 0, stream>>>(X, G, rows_total, T, (int)din, (int)dout, rows_per_split, out, weight, norm_partial, (int)B);
+        stat_generic_kernel<TIn, MODE_NORMS><<<grid, block, 0, stream>>>(X, G, rows_total, T, (int)din, (int)dout, rows_per_split, out, weight, norm_partial, (int)B, alpha);
         break;
     case MODE_WEIGHTED:
-        stat_generic_kernel<TIn, MODE_WEIGHTED><<<grid, block, 0, stream>>>(X, G, rows_total, T, (int)din, (int)dout, rows_per_split, out, weight, norm_partial, (int)B);
+        stat_generic_kernel<TIn, MODE_WEIGHTED><<<grid, block, 0, stream>>>(X, G, rows_total, T, (int)din, (int)dout, rows_per_split, out, weight, norm_partial, (int)B, alpha);
+        break;
+    case MODE_POWER:
+        stat_generic_kernel<TIn, MODE_POWER><<<grid, block, 0, stream>>>(X, G, rows_total, T, (int)din, (int)dout, rows_per_split, out, weight, norm_partial, (int)B, alpha);
         break;
     case MODE_TOKEN_SQ:
-        stat_generic_kernel<TIn, MODE_TOKEN_SQ><<<grid, block, 0, stream>>>(X, G, rows_total, T, (int)din, (int)dout, rows_per_split, out, weight, norm_partial, (int)B);
+        stat_generic_kernel<TIn, MODE_TOKEN_SQ><<<grid, block, 0, stream>>>(X, G, rows_total, T, (int)din, (int)dout, rows_per_split, out, weight, norm_partial, (int)B, alpha);
         break;
     }
     return hipGetLastError();
@@ -172,11 +176,11 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
 
 hipError_t launch_stat_generic(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout,
                                pex_dtype dt, Mode mode, const StatPlan& plan, float* out, hipStream_t stream,
-                               const float* weight, float* norm_partial)
+                               const float* weight, float* norm_partial, float alpha)
 {
     if (dt == PEX_F32)
-        return launch_typed((const float*)X, (const float*)G, B, T, din, dout, mode, plan, out, stream, weight, norm_partial);
-    return launch_typed((const uint16_t*)X, (const uint16_t*)G, B, T, din, dout, mode, plan, out, stream, weight, norm_partial);
+        return launch_typed((const float*)X, (const float*)G, B, T, din, dout, mode, plan, out, stream, weight, norm_partial, alpha);
+    return launch_typed((const uint16_t*)X, (const uint16_t*)G, B, T, din, dout, mode, plan, out, stream, weight, norm_partial, alpha);
 }
 
 int64_t generic_norm_partials(int64_t din, int64_t dout) { return ((din + TM - 1) / TM) * ((dout + TN - 1) / TN); }

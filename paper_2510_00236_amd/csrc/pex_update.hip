@@ -1,5 +1,5 @@
 // pex_update.hip -- elementwise optimizer updates that consume the statistics (Algorithm 1, App. E, with
-// the estimators of Eq. (musq_sigsq_est); MicroSignSGD of Sec. 3.1).  One pass, in place, bound by HBM
+// the estimators of Eq. (musq_sigsq_est); the three placements of sign of Sec. 3.1: MicroSignSGD, SignSGD, SignEMA).  One pass, in place, bound by HBM
 // bandwidth: Adam family 20 B read + 12 B written per parameter (16 + 12 for plain Adam, which never
 // touches S_sq), MicroSignSGD 12 B read + 8 B written.  16-byte accesses, grid-stride, scalar tail.
 #include "pex_internal.h"
@@ -67,6 +67,10 @@ __global__ __launch_bounds__(256) void adam_update_kernel(float* __restrict__ th
     }
 }
 
+// VARIANT: PEX_MICROSIGNSGD  m <- EMA(S/B), S = sum of per-example signs, step along m
+//          PEX_SIGNSGD       m <- EMA(sign(S)), S = sum of gradients,     step along m
+//          PEX_SIGNEMA       m <- EMA(S/B), S = sum of gradients,          step along sign(m)
+template <int VARIANT>
 __global__ __launch_bounds__(256) void signsgd_update_kernel(float* __restrict__ theta, float* __restrict__ m,
                                                              const float* __restrict__ S_sign, int64_t n, float lr,
                                                              float beta, float one_m_beta_over_B, float wd, float debias_mul)
@@ -77,9 +81,12 @@ __global__ __launch_bounds__(256) void signsgd_update_kernel(float* __restrict__
     float4* th4 = reinterpret_cast<float4*>(theta);
     float4* m4 = reinterpret_cast<float4*>(m);
     const float4* s4 = reinterpret_cast<const float4*>(S_sign);
+    auto sgn = [](float x) { return (float)((x > 0.f) - (x < 0.f)); };
     auto one = [&](float& t, float& mm, float s) {
-        mm = fmaf(beta, mm, one_m_beta_over_B * s);
-        t = t - lr * (mm * debias_mul) - wd * t;
+        // for PEX_SIGNSGD the factor holds 1 - beta (the sign of S/B is the sign of S)
+        mm = fmaf(beta, mm, one_m_beta_over_B * (VARIANT == PEX_SIGNSGD ? sgn(s) : s));
+        const float dir = VARIANT == PEX_SIGNEMA ? sgn(mm) : mm * debias_mul;
+        t = t - lr * dir - wd * t;
     };
     for (int64_t e = gid; e < n4; e += stride) {
         float4 t = th4[e], mm = m4[e];
@@ -126,12 +133,17 @@ hipError_t launch_adam_update(float* theta, float* m, float* v, const float* S_i
     return hipGetLastError();
 }
 
-hipError_t launch_signsgd_update(float* theta, float* m, const float* S_sign, int64_t n, float lr, float beta,
-                                 float weight_decay, int32_t B, int32_t debias, int64_t step, hipStream_t stream)
+hipError_t launch_sign_update(float* theta, float* m, const float* S, int64_t n, pex_sign_variant variant, float lr, float beta,
+                              float weight_decay, int32_t B, int32_t debias, int64_t step, hipStream_t stream)
 {
     const float debias_mul = debias ? (float)(1.0 / (1.0 - pow((double)beta, (double)step))) : 1.f;
     const float w = (1.f - beta) / (float)B;
-    signsgd_update_kernel<<<dim3(update_grid(n)), dim3(256), 0, stream>>>(theta, m, S_sign, n, lr, beta, w, weight_decay, debias_mul);
+    const dim3 grid(update_grid(n)), block(256);
+    switch (variant) {
+    case PEX_MICROSIGNSGD: signsgd_update_kernel<PEX_MICROSIGNSGD><<<grid, block, 0, stream>>>(theta, m, S, n, lr, beta, w, weight_decay, debias_mul); break;
+    case PEX_SIGNSGD: signsgd_update_kernel<PEX_SIGNSGD><<<grid, block, 0, stream>>>(theta, m, S, n, lr, beta, 1.f - beta, weight_decay, debias_mul); break;
+    case PEX_SIGNEMA: signsgd_update_kernel<PEX_SIGNEMA><<<grid, block, 0, stream>>>(theta, m, S, n, lr, beta, w, weight_decay, 1.f); break;
+    }
     return hipGetLastError();
 }
 

@@ -77,3 +77,24 @@ def test_norms_sum_to_the_total_of_the_square_statistic_at_full_size():
     assert abs(float(Nt.sum()) - float(tok.sum())) <= 1e-2 * float(tok.sum())
     again = pex.pex_example_norms(Xd, Gd).double()
     assert torch.equal(N, again)
+
+
+@pytest.mark.parametrize("B,T,din,dout,dtype", [(5, 77, 520, 264, "bf16"), (3, 50, 129, 65, "f32"), (7, 33, 256, 128, "bf16")])
+@pytest.mark.parametrize("alpha", [1.0, 1.5, 2.0, 3.0])
+def test_power_statistic(B, T, din, dout, dtype, alpha):
+    X, G = si.custom(B, T, din, dout, dtype=dtype, seed=B + int(10 * alpha))
+    S = pex.pex_stat_power(X.to(DEV), G.to(DEV), alpha).cpu().double().numpy()
+    ref = on.power_stat(si.widen(X), si.widen(G), alpha)
+    # terms are >= 0; each carries the fp32 contraction error amplified by alpha plus the log2/exp2 error
+    assert (np.abs(S - ref) <= 1e-4 * ref + 1e-5 * ref.max()).all(), float((np.abs(S - ref) / ref.max()).max())
+    if alpha == 2.0:
+        sq = pex.pex_stat(X.to(DEV), G.to(DEV), "square").cpu().double().numpy()
+        assert np.abs(S - sq).max() <= 1e-5 * sq.max()
+
+
+def test_power_statistic_rejects_bad_exponents():
+    X, G = si.custom(2, 16, 32, 32, dtype="bf16", seed=1)
+    for alpha in (0.0, -1.0, float("nan"), 100.0):
+        with pytest.raises(pex.PexError) as ei:
+            pex.pex_stat_power(X.to(DEV), G.to(DEV), alpha)
+        assert ei.value.code == 4

@@ -75,3 +75,21 @@ def test_all_ones_closed_form_and_integer_brute_force():
                 m = sum(int(X[b, t, i]) * int(G[b, t, j]) for t in range(3))
                 tot += m * m
         assert on.example_norms(X, G)[b] == tot
+
+
+def test_power_statistic():
+    X, G = _rand(5, 7, 6, 4, 8)
+    st = oracle.stat(X, G)
+    # alpha = 2 is the square statistic; B = 1, alpha = 1 is |S_id|
+    np.testing.assert_allclose(on.power_stat(X, G, 2.0), st.S_sq, rtol=1e-12)
+    np.testing.assert_allclose(on.power_stat(X[:1], G[:1], 1.0), np.abs(oracle.stat(X[:1], G[:1]).S_id), rtol=1e-12)
+    # T = 1: gradients are rank one and the power factorises (Sec. 2.3): (|X|^a)^T (|G|^a)
+    X1, G1 = _rand(6, 1, 5, 3, 9)
+    a = 1.5
+    fact = (np.abs(X1.astype(np.float64)) ** a).reshape(6, 5).T @ (np.abs(G1.astype(np.float64)) ** a).reshape(6, 3)
+    np.testing.assert_allclose(on.power_stat(X1, G1, a), fact, rtol=1e-12)
+    # scaling one example's cotangents by c multiplies its contribution by |c|^alpha (c a power of two: exact in fp32)
+    G2 = G.copy(); G2[2] *= -4.0
+    ii, jj = np.meshgrid(np.arange(6), np.arange(4), indexing="ij")
+    M2 = np.abs(oracle.per_example_at(X, G, ii.ravel(), jj.ravel()).reshape(5, 6, 4)[2])
+    np.testing.assert_allclose(on.power_stat(X, G2, a) - on.power_stat(X, G, a), (4.0 ** a - 1.0) * M2 ** a, rtol=1e-9, atol=1e-12)

@@ -156,3 +156,46 @@ def test_microsignsgd_pins():
     # debias makes the all-agree direction exactly +-1; weight decay is not multiplied by lr
     th2, m2 = ou.microsignsgd_step(np.ones(3), np.zeros(3), np.array([B, -B, 0.0]), lr, beta, 0.5, B, True, 1)
     np.testing.assert_allclose(th2, 1.0 - lr * np.array([1, -1, 0]) - 0.5, rtol=1e-13)
+
+
+def test_sign_family_pins():
+    """The three placements of sign (Sec. 3.1): MicroSignSGD variant = the dedicated routine; with B = 1 MicroSignSGD
+    and SignSGD coincide; SignEMA equals torch.sign of a hand-rolled EMA; constant-gradient closed forms."""
+    n, beta, lr, wd = 30, 0.9, 1e-3, 1e-2
+    rng = np.random.default_rng(12)
+    th0 = rng.standard_normal(n)
+    # (a) variant 0 is the MicroSignSGD routine
+    S = rng.integers(-8, 9, n).astype(np.float64) * 2
+    a = ou.sign_family_step(th0, np.zeros(n), S, ou.MICROSIGNSGD, lr, beta, wd, 16, True, 3)
+    b = ou.microsignsgd_step(th0, np.zeros(n), S, lr, beta, wd, 16, True, 3)
+    np.testing.assert_array_equal(a[0], b[0]); np.testing.assert_array_equal(a[1], b[1])
+    # (b) one example per batch: the sign of the average is the average of the signs
+    g = rng.standard_normal(n)
+    th_a, m_a, th_b, m_b = th0.copy(), np.zeros(n), th0.copy(), np.zeros(n)
+    for t in range(1, 6):
+        th_a, m_a = ou.sign_family_step(th_a, m_a, np.sign(g), ou.MICROSIGNSGD, lr, beta, 0.0, 1, False, t)
+        th_b, m_b = ou.sign_family_step(th_b, m_b, g, ou.SIGNSGD, lr, beta, 0.0, 1, False, t)
+    np.testing.assert_allclose(th_a, th_b, rtol=1e-14)
+    # (c) SignEMA against a hand-rolled recursion and the library sign; every step has size lr exactly
+    th, m, ema = th0.copy(), np.zeros(n), np.zeros(n)
+    for t in range(1, 6):
+        S = rng.standard_normal(n) * 16
+        prev = th.copy()
+        th, m = ou.sign_family_step(th, m, S, ou.SIGNEMA, lr, beta, 0.0, 16, False, t)
+        ema = beta * ema + (1 - beta) * S / 16
+        np.testing.assert_allclose(m, ema, rtol=1e-13)
+        np.testing.assert_allclose(np.abs(th - prev), lr, rtol=1e-9)
+        np.testing.assert_allclose(th, prev - lr * np.sign(ema), rtol=1e-12, atol=1e-15)
+    # (d) constant gradient: SignSGD's EMA tends to sign(g) as 1 - beta^t; weight decay is not scaled by lr
+    th, m = np.ones(3), np.zeros(3)
+    S = np.array([3.0, -0.5, 0.0])
+    for t in range(1, 20):
+        th, m = ou.sign_family_step(th, m, S, ou.SIGNSGD, lr, beta, 0.0, 4, False, t)
+        np.testing.assert_allclose(m, np.array([1, -1, 0]) * (1 - beta ** t), rtol=1e-12)
+    th2, _ = ou.sign_family_step(np.ones(3), np.zeros(3), S, ou.SIGNEMA, lr, beta, 0.5, 4, False, 1)
+    np.testing.assert_allclose(th2, 1.0 - lr * np.array([1, -1, 0]) - 0.5, rtol=1e-13)
+    # (e) the ordering matters once B > 1: a batch whose mean and whose majority disagree
+    per_example = np.array([[5.0], [-1.0], [-1.0]])            # mean +1, two of three negative
+    _, m_micro = ou.sign_family_step(np.zeros(1), np.zeros(1), np.sign(per_example).sum(0), ou.MICROSIGNSGD, lr, beta, 0.0, 3, False, 1)
+    _, m_sgd = ou.sign_family_step(np.zeros(1), np.zeros(1), per_example.sum(0), ou.SIGNSGD, lr, beta, 0.0, 3, False, 1)
+    assert m_micro[0] < 0 < m_sgd[0]

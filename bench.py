@@ -9,9 +9,12 @@ A step is one pass of the whole hot path over one batch of synthetic input for t
 Inputs are resident in HBM before the timed region.  `value` is the contraction work of the step
 (2*B*T*din*dout FLOP per statistic) divided by the wall time of the step, in TFLOP/s.
 
-Prints ONE JSON line.  `roofline` is measured live with HIP events around every launch of the dominant
-kernel (the phi = square contraction) on the stream it runs on; `cpu_baseline` times the fp64 oracle on a
-bounded sample of the same workload on the host cores.
+Prints ONE JSON line.  `roofline` is measured live with HIP events around launches of the dominant kernel on
+the stream it runs on.  The kernel that takes the largest share of the step (42 % in the kernel trace under
+profiles/) is the plain 256 x 256-tile contraction: pex_stat(identity) launches it once per layer and
+pex_token_sq launches it once more on the pre-squared operands; the events bracket the pex_stat(identity)
+launches.  `square_roofline` reports the phi = square contraction (27 % of the step) the same way.
+`cpu_baseline` times the fp64 oracle on a bounded sample of the same workload on the host cores.
 """
 from __future__ import annotations
 
@@ -37,14 +40,15 @@ LAYER_SETS = {
 }
 
 
-def measured_traffic(workload: str):
-    """HBM bytes per launch of the phi = square contraction, from the committed rocprofv3 counter summary
-    (FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size); None if no summary covers this workload."""
-    path = os.path.join(ROOT, "profiles", f"stat_bf16_square_{workload}_pmc.txt")
+def measured_traffic(workload: str, which: str):
+    """Bytes beyond L2 per launch of a contraction kernel (`which` = identity | square), from the committed
+    rocprofv3 counter summary (FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size); None if no summary
+    covers this workload."""
+    path = os.path.join(ROOT, "profiles", f"stat_bf16_{workload}_pmc.txt")
     try:
         with open(path) as f:
             for line in f:
-                if line.startswith("traffic_bytes_per_launch:"):
+                if line.startswith(f"traffic_bytes_per_launch_{which}:"):
                     return float(line.split(":", 1)[1].split()[0])
     except OSError:
         pass
@@ -60,6 +64,9 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--no-shared-step", action="store_true",
+                    help="skip the informational step with shared contractions (profiling runs: the trace then "
+                         "holds the headline step only)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="before the timed region, copy 1 GiB device to device once: a kernel of known traffic "
                          "against which the FETCH_SIZE / WRITE_SIZE counters of a profiling run are scaled")
@@ -106,14 +113,20 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    sq_events = []          # (start, stop) around every launch of the phi = square contraction
+    id_events = []          # (start, stop) around every launch of the plain contraction by pex_stat(identity)
+    sq_events = []          # ... of the phi = square contraction
     upd_events = []
 
     def step(t: int, record: bool):
         for L in layers:
             w = L["w"]
+            if record:
+                i0, i1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                i0.record()
             pex.pex_stat(L["X"], L["G"], "identity", S=L["S_id"], workspace=L["ws"])
             if record:
+                i1.record()
+                id_events.append((i0, i1, w))
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
             pex.pex_stat(L["X"], L["G"], "square", S=L["S_sq"], workspace=L["ws"])
@@ -160,28 +173,34 @@ def main() -> int:
         nb = pex.pex_stat_multi_workspace_bytes(w.B, w.T, w.din, w.dout, pex.PEX_BF16, ("identity", "square", "sign"))
         L["ws_multi"] = torch.empty(max(nb, 16), dtype=torch.uint8, device=dev)
     t_last = args.warmup + args.steps
-    multi_step(t_last + 1)
-    torch.cuda.synchronize()
-    m0 = time.perf_counter()
-    for t in range(t_last + 2, t_last + 2 + args.steps):
-        multi_step(t)
-    torch.cuda.synchronize()
-    multi_ms = (time.perf_counter() - m0) / args.steps * 1e3
+    multi_ms = None
+    if not args.no_shared_step:
+        multi_step(t_last + 1)
+        torch.cuda.synchronize()
+        m0 = time.perf_counter()
+        for t in range(t_last + 2, t_last + 2 + args.steps):
+            multi_step(t)
+        torch.cuda.synchronize()
+        multi_ms = (time.perf_counter() - m0) / args.steps * 1e3
 
     flop_per_stat = [2.0 * L["w"].B * L["w"].T * L["w"].din * L["w"].dout for L in layers]
     flop_per_step = 4.0 * sum(flop_per_stat)          # identity, square, sign, per-token square
     ms_per_step = elapsed / args.steps * 1e3
     value = flop_per_step / (elapsed / args.steps) / 1e12
 
-    # ---- roofline of the dominant kernel: the phi = square contraction, per launch
-    sq_ms = [a.elapsed_time(b) for a, b, _ in sq_events]
-    sq_flop = [2.0 * w.B * w.T * w.din * w.dout for _, _, w in sq_events]
-    sq_avg_ms = sum(sq_ms) / len(sq_ms)
-    achieved = (sum(sq_flop) / len(sq_flop)) / (sq_avg_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "stat_bf16_kernel<square> (pex_stat phi=square)",
-                "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "avg_launch_ms": round(sq_avg_ms, 4),
-                "launches": len(sq_ms), "traffic": measured_traffic(args.workload)}
+    # ---- rooflines of the contraction kernels, per launch
+    def contraction_roofline(events, kernel, which):
+        ms = [a.elapsed_time(b) for a, b, _ in events]
+        flop = [2.0 * w.B * w.T * w.din * w.dout for _, _, w in events]
+        avg_ms = sum(ms) / len(ms)
+        achieved = (sum(flop) / len(flop)) / (avg_ms * 1e-3) / 1e12
+        return {"bound": "mfma", "kernel": kernel, "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "avg_launch_ms": round(avg_ms, 4),
+                "launches": len(ms), "traffic": measured_traffic(args.workload, which)}
+
+    roofline = contraction_roofline(id_events, "stat_bf16_kernel<256x256 tile, identity> (pex_stat phi=identity; also "
+                                               "the contraction inside pex_token_sq)", "identity")
+    square_roofline = contraction_roofline(sq_events, "stat_bf16_kernel<256x128 tile, square> (pex_stat phi=square)", "square")
     upd_ms = [a.elapsed_time(b) for a, b, _ in upd_events]
     upd_bytes = [32.0 * w.din * w.dout for _, _, w in upd_events]
     upd_gbs = (sum(upd_bytes) / len(upd_bytes)) / (sum(upd_ms) / len(upd_ms) * 1e-3) / 1e9
@@ -226,8 +245,9 @@ def main() -> int:
                    "shapes": [[L["w"].din, L["w"].dout] for L in layers],
                    "step": "per layer: pex_stat identity+square -> MicroAdam update; pex_stat sign -> MicroSignSGD update; pex_token_sq",
                    "flop_per_step": flop_per_step, "seed": args.seed},
-        "roofline": roofline, "update_roofline": update_roofline, "cpu_baseline": cpu,
-        "shared_contraction_step": {"ms_per_step": round(multi_ms, 4),
+        "roofline": roofline, "square_roofline": square_roofline, "update_roofline": update_roofline,
+        "cpu_baseline": cpu,
+        "shared_contraction_step": None if multi_ms is None else {"ms_per_step": round(multi_ms, 4),
                                     "note": "same outputs with identity, square and sign from one contraction per layer "
                                             "(pex_stat_multi); informational, not used in value"},
     }

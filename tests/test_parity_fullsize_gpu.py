@@ -55,3 +55,33 @@ def test_full_size_sampled(name):
     assert (S_sg.abs() <= w.B).all() and torch.equal(S_sg, S_sg.round())
     assert ((S_sg.long() - w.B) % 2 == 0).float().mean() > 0.999                    # parity of B wherever no M_b is exactly 0
     print(f"{name}: sign mismatches inside the ambiguity band: {n_diff}")
+
+
+@pytest.mark.parametrize("name", ["c4_1b_up", "c5_long"])
+def test_full_size_shared_contraction_weighted_and_power(name):
+    """The entry points that share the contraction kernels (several statistics from one pass, clipping-weighted
+    sums, |.|^alpha) at the sizes bench.py times, against per-example values the oracle computes at sampled positions."""
+    w = si.WORKLOADS[name]
+    X, G = si.make(w, seed=2)
+    Xd, Gd = X.to(DEV), G.to(DEV)
+    multi = pex.pex_stat_multi(Xd, Gd, ("identity", "square", "sign"))
+    pair = pex.pex_stat_multi(Xd, Gd, ("identity", "square"))
+    wts = torch.linspace(0.25, 1.0, w.B)
+    S_w = pex.pex_weighted_sum(Xd, Gd, wts.to(DEV))
+    S_p = pex.pex_stat_power(Xd, Gd, 1.0)
+    N = pex.pex_example_norms(Xd, Gd)
+    torch.cuda.synchronize()
+    ii, jj = _sample_positions(w.din, w.dout, 2000, seed=3)
+    M = oracle.per_example_at(si.widen(X), si.widen(G), ii, jj)             # [B, n] fp64
+    pick = lambda t: t[torch.as_tensor(ii, device=DEV), torch.as_tensor(jj, device=DEV)].cpu().numpy().astype(np.float64)
+    mx = np.abs(M).max(axis=1)
+    amb = (np.abs(M) < oracle.SIGN_BAND * mx[:, None]).sum(axis=0)
+    for got, what in ((multi, "three at once"), (pair, "identity and square")):
+        assert_real_stat(pick(got["identity"]), M.sum(axis=0), "bf16", f"{name} {what}: identity", elementwise=False)
+        assert_real_stat(pick(got["square"]), (M * M).sum(axis=0), "bf16", f"{name} {what}: square", elementwise=True)
+    assert_sign_stat(pick(multi["sign"]), np.sign(M).sum(axis=0), amb, f"{name} three at once: sign")
+    assert_real_stat(pick(S_w), (wts.double().numpy()[:, None] * M).sum(axis=0), "bf16", f"{name} weighted", elementwise=False)
+    assert_real_stat(pick(S_p), np.abs(M).sum(axis=0), "bf16", f"{name} |.|^1", elementwise=True)
+    # the norms cover every entry; the total of the square statistic is the same number by another kernel
+    tot = float(multi["square"].double().sum())
+    assert abs(float(N.double().sum()) - tot) <= 1e-5 * tot

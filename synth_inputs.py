@@ -7,7 +7,7 @@ the 1.2B model of App. D).  Both the HIP path and the CPU oracle are handed the
 very same rounded payloads; neither imports the other.
 
 Streams: X from seed*2, G from seed*2+1, per-token scale / mask from seed*2+2,
-optimizer state from seed*2+3.  All draws use a CPU ``torch.Generator`` so they
+optimizer state from seed*2+3, token ids from seed*2+4.  All draws use a CPU ``torch.Generator`` so they
 are identical on every machine.
 """
 from __future__ import annotations
@@ -100,6 +100,17 @@ def integer_valued(B: int, T: int, din: int, dout: int, dtype: str = "bf16", see
     X = torch.randint(lo, hi + 1, (B, T, din), generator=gx).to(torch.float32)
     G = torch.randint(lo, hi + 1, (B, T, dout), generator=gg).to(torch.float32)
     return _store(X, dtype), _store(G, dtype)
+
+
+def token_ids(B: int, T: int, V: int, seed: int = 0, exponent: float = 1.0, pad_fraction: float = 0.0):
+    """Token ids [B, T] int64 with a Zipf-like rank-frequency law p(v) ~ 1/(v + 2.7)^exponent (id = frequency rank,
+    the shape of natural-language token counts); a fraction of the positions can be set to the padding id -1."""
+    g = _gen(seed * 2 + 4)
+    p = 1.0 / (torch.arange(V, dtype=torch.float64) + 2.7) ** exponent
+    ids = torch.multinomial(p / p.sum(), B * T, replacement=True, generator=g).reshape(B, T)
+    if pad_fraction > 0:
+        ids = torch.where(torch.rand(B, T, generator=g) < pad_fraction, torch.full_like(ids, -1), ids)
+    return ids
 
 
 def optimizer_state(n: int, seed: int = 0):

@@ -216,6 +216,29 @@ pex_status pex_sign_update(float *theta, float *m, const float *S, int64_t n, pe
                            float beta, float weight_decay, int32_t B, int32_t debias, int64_t step,
                            pex_stream_t stream);
 
+/*
+ * pex_moment_track -- on-line measurement of mu^2 and sigma^2 (Sec. 3.2.2, Eq. (musq_sigsq_est)), in place over n
+ * parameters.  Two EMAs with the optimizer's beta2 follow nu_adam and nu_micro:
+ *   mu_t = grad_scale*S_id ;  ema_adam  <- beta2*ema_adam  + (1-beta2)*mu_t^2
+ *                             ema_micro <- beta2*ema_micro + (1-beta2)*sq_scale*S_sq
+ *   a = ema_adam*k, q = ema_micro*k, k = debias ? 1/(1-beta2^step) : 1
+ *   mu^2-hat = (a - q/B)/(1 - 1/B),  sigma^2-hat = (q - a)/(1 - 1/B)
+ *   sums[0] = sum over the n parameters of mu^2-hat, sums[1] = sum of sigma^2-hat  (fp64, device memory)
+ * The figures of Sec. 3.2.2 plot sums[0]/n, sums[1]/n and sums[0]/(sums[1]/B) (Adam) or sums[0]/sums[1] (MicroAdam),
+ * with the sums of all layers added up by the caller.  ema_adam, ema_micro (read and written), S_id, S_sq: fp32 device
+ * arrays of n elements, 16-byte aligned; sums: 2 doubles, 8-byte aligned; the workspace holds one pair of partial
+ * sums per workgroup, added in a fixed order (the result does not depend on scheduling).  B >= 2, step >= 1.
+ */
+typedef struct {
+    float beta2, grad_scale, sq_scale;
+    int32_t B, debias;
+    int64_t step;
+} pex_moment_params;
+size_t pex_moment_track_workspace_bytes(int64_t n);
+pex_status pex_moment_track(float *ema_adam, float *ema_micro, const float *S_id, const float *S_sq, int64_t n,
+                            const pex_moment_params *p /* host */, double *sums, void *workspace,
+                            size_t workspace_bytes, pex_stream_t stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -34,7 +34,8 @@ EXPORTS = ("pex_status_string", "pex_version", "pex_stat_workspace_bytes", "pex_
            "pex_example_norms_workspace_bytes", "pex_example_norms", "pex_weighted_sum_workspace_bytes",
            "pex_weighted_sum", "pex_token_norms", "pex_sign_update",
            "pex_stat_power_workspace_bytes", "pex_stat_power",
-           "pex_token_sq_workspace_bytes", "pex_token_sq", "pex_adam_update", "pex_signsgd_update")
+           "pex_token_sq_workspace_bytes", "pex_token_sq", "pex_adam_update", "pex_signsgd_update",
+           "pex_moment_track_workspace_bytes", "pex_moment_track")
 
 
 class PexError(RuntimeError):
@@ -49,6 +50,12 @@ class AdamParams(ctypes.Structure):
                 ("eps", ctypes.c_float), ("eps_root", ctypes.c_float), ("weight_decay", ctypes.c_float),
                 ("grad_scale", ctypes.c_float), ("sq_scale", ctypes.c_float),
                 ("step", ctypes.c_int64), ("B", ctypes.c_int32)]
+
+
+class MomentParams(ctypes.Structure):
+    """Mirror of ``pex_moment_params``."""
+    _fields_ = [("beta2", ctypes.c_float), ("grad_scale", ctypes.c_float), ("sq_scale", ctypes.c_float),
+                ("B", ctypes.c_int32), ("debias", ctypes.c_int32), ("step", ctypes.c_int64)]
 
 
 _lib = None
@@ -100,6 +107,10 @@ def lib() -> ctypes.CDLL:
         L.pex_signsgd_update.restype = ctypes.c_int
         L.pex_sign_update.argtypes = [p, p, p, i64, ctypes.c_int, f, f, f, i32, i32, i64, p]
         L.pex_sign_update.restype = ctypes.c_int
+        L.pex_moment_track_workspace_bytes.argtypes = [i64]
+        L.pex_moment_track_workspace_bytes.restype = sz
+        L.pex_moment_track.argtypes = [p, p, p, p, i64, ctypes.POINTER(MomentParams), p, p, sz, p]
+        L.pex_moment_track.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -338,3 +349,24 @@ def pex_sign_update(theta, m, S, variant, lr, beta, weight_decay, B, debias=Fals
         raise ValueError("theta, m and S must have the same number of elements")
     _check(lib().pex_sign_update(_dev(theta, "theta"), _dev(m, "m"), _dev(S, "S"), n, SIGN_VARIANT.get(variant, variant),
                                  lr, beta, weight_decay, int(B), int(bool(debias)), int(step), _stream(stream)))
+
+
+def pex_moment_track_workspace_bytes(n) -> int:
+    return int(lib().pex_moment_track_workspace_bytes(n))
+
+
+def pex_moment_track(ema_adam, ema_micro, S_id, S_sq, params: MomentParams, sums=None, workspace=None, stream=None):
+    """One step of the on-line mu^2 / sigma^2 measurement (Sec. 3.2.2): updates the two EMAs in place and returns a
+    float64 tensor [2] = (sum of mu^2-hat, sum of sigma^2-hat) over the parameters."""
+    import torch
+    n = ema_adam.numel()
+    for name, t in (("ema_micro", ema_micro), ("S_id", S_id), ("S_sq", S_sq)):
+        if t.numel() != n:
+            raise ValueError(f"{name} has {t.numel()} elements, ema_adam has {n}")
+    if sums is None:
+        sums = torch.empty(2, dtype=torch.float64, device=ema_adam.device)
+    ws, wptr, wbytes = _workspace(pex_moment_track_workspace_bytes(n), ema_adam, workspace)
+    _check(lib().pex_moment_track(_dev(ema_adam, "ema_adam"), _dev(ema_micro, "ema_micro"), _dev(S_id, "S_id"),
+                                  _dev(S_sq, "S_sq"), n, ctypes.byref(params), _dev(sums, "sums"), wptr, wbytes,
+                                  _stream(stream)))
+    return sums

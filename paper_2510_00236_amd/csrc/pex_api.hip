@@ -392,6 +392,23 @@ pex_status pex_adam_update(float* theta, float* m, float* v, const float* S_id, 
                                                                                                            : PEX_ERR_HIP;
 }
 
+size_t pex_moment_track_workspace_bytes(int64_t n) { return n < 1 ? 0 : moment_track_workspace(n); }
+
+pex_status pex_moment_track(float* ema_adam, float* ema_micro, const float* S_id, const float* S_sq, int64_t n,
+                            const pex_moment_params* p, double* sums, void* workspace, size_t workspace_bytes,
+                            pex_stream_t stream)
+{
+    if (!ema_adam || !ema_micro || !S_id || !S_sq || !p || !sums) return PEX_ERR_NULL;
+    if (n < 1 || p->step < 1 || p->B < 2) return PEX_ERR_SHAPE;
+    if (((uintptr_t)ema_adam | (uintptr_t)ema_micro | (uintptr_t)S_id | (uintptr_t)S_sq) & 15u) return PEX_ERR_ALIGN;
+    if ((uintptr_t)sums & 7u) return PEX_ERR_ALIGN;
+    if (!workspace || workspace_bytes < moment_track_workspace(n)) return PEX_ERR_WORKSPACE;
+    if ((uintptr_t)workspace & 15u) return PEX_ERR_ALIGN;
+    return launch_moment_track(ema_adam, ema_micro, S_id, S_sq, n, *p, sums, (double*)workspace, (hipStream_t)stream) == hipSuccess
+               ? PEX_OK
+               : PEX_ERR_HIP;
+}
+
 pex_status pex_sign_update(float* theta, float* m, const float* S, int64_t n, pex_sign_variant variant, float lr, float beta,
                            float weight_decay, int32_t B, int32_t debias, int64_t step, pex_stream_t stream)
 {

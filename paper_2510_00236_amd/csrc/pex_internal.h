@@ -82,4 +82,8 @@ hipError_t launch_adam_update(float* theta, float* m, float* v, const float* S_i
 hipError_t launch_sign_update(float* theta, float* m, const float* S, int64_t n, pex_sign_variant variant, float lr, float beta,
                               float weight_decay, int32_t B, int32_t debias, int64_t step, hipStream_t stream);
 
+size_t moment_track_workspace(int64_t n);
+hipError_t launch_moment_track(float* ema_adam, float* ema_micro, const float* S_id, const float* S_sq, int64_t n,
+                               const pex_moment_params& p, double* sums, double* partial, hipStream_t stream);
+
 }  // namespace pex

@@ -101,6 +101,74 @@ __global__ __launch_bounds__(256) void signsgd_update_kernel(float* __restrict__
     }
 }
 
+// On-line measurement of mu^2 and sigma^2 (Sec. 3.2.2): two EMAs with the optimizer's beta2 track nu_adam and nu_micro;
+// the unbiased estimators of Eq. (musq_sigsq_est) are formed from the (bias-corrected) EMAs and summed over the
+// parameters.  The EMAs are fp32 like the optimizer state; the estimators (differences of nearly equal numbers when
+// one moment dominates) and their sums are formed in fp64.  Each workgroup writes one pair of partial sums; the
+// second kernel adds the pairs in a fixed order, so the result does not depend on scheduling.
+struct MomentConsts {
+    float beta2, one_m_beta2, gs, qs;
+    double corr, c_est, inv_B;   // 1/(1-beta2^t) or 1, 1/(1-1/B), 1/B
+};
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+__global__ __launch_bounds__(256) void moment_track_kernel(float* __restrict__ ema_adam, float* __restrict__ ema_micro,
+                                                           const float* __restrict__ S_id, const float* __restrict__ S_sq,
+                                                           int64_t n, MomentConsts k, double* __restrict__ partial)
+{
+    const int64_t n4 = n / 4;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    float4* a4 = reinterpret_cast<float4*>(ema_adam);
+    float4* q4 = reinterpret_cast<float4*>(ema_micro);
+    const float4* i4 = reinterpret_cast<const float4*>(S_id);
+    const float4* s4 = reinterpret_cast<const float4*>(S_sq);
+    double sum_mu2 = 0.0, sum_sigma2 = 0.0;
+    auto one = [&](float& a, float& q, float sid, float ssq) {
+        const float mu_t = k.gs * sid;
+        a = fmaf(k.beta2, a, k.one_m_beta2 * (mu_t * mu_t));
+        q = fmaf(k.beta2, q, k.one_m_beta2 * (k.qs * ssq));
+        const double ah = (double)a * k.corr, qh = (double)q * k.corr;
+        sum_mu2 += k.c_est * (ah - qh * k.inv_B);
+        sum_sigma2 += k.c_est * (qh - ah);
+    };
+    for (int64_t e = gid; e < n4; e += stride) {
+        float4 a = a4[e], q = q4[e];
+        const float4 si = i4[e], ss = s4[e];
+        one(a.x, q.x, si.x, ss.x); one(a.y, q.y, si.y, ss.y); one(a.z, q.z, si.z, ss.z); one(a.w, q.w, si.w, ss.w);
+        a4[e] = a; q4[e] = q;
+    }
+    for (int64_t e = n4 * 4 + gid; e < n; e += stride) {
+        float a = ema_adam[e], q = ema_micro[e];
+        one(a, q, S_id[e], S_sq[e]);
+        ema_adam[e] = a; ema_micro[e] = q;
+    }
+    __shared__ double red[4][2];
+    sum_mu2 = wave_sum(sum_mu2);
+    sum_sigma2 = wave_sum(sum_sigma2);
+    if ((threadIdx.x & 63) == 0) { red[threadIdx.x >> 6][0] = sum_mu2; red[threadIdx.x >> 6][1] = sum_sigma2; }
+    __syncthreads();
+    if (threadIdx.x < 2) partial[(int64_t)blockIdx.x * 2 + threadIdx.x] = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+}
+
+__global__ __launch_bounds__(256) void moment_finalize_kernel(const double* __restrict__ partial, int nparts, double* __restrict__ sums)
+{
+    double s0 = 0.0, s1 = 0.0;
+    for (int i = threadIdx.x; i < nparts; i += 256) { s0 += partial[2 * i]; s1 += partial[2 * i + 1]; }
+    __shared__ double red[4][2];
+    s0 = wave_sum(s0);
+    s1 = wave_sum(s1);
+    if ((threadIdx.x & 63) == 0) { red[threadIdx.x >> 6][0] = s0; red[threadIdx.x >> 6][1] = s1; }
+    __syncthreads();
+    if (threadIdx.x < 2) sums[threadIdx.x] = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+}
+
 inline unsigned update_grid(int64_t n)
 {
     int64_t blocks = (n / 4 + 255) / 256;
@@ -130,6 +198,25 @@ hipError_t launch_adam_update(float* theta, float* m, float* v, const float* S_i
     case PEX_MICROADAM_VAR: adam_update_kernel<PEX_MICROADAM_VAR><<<grid, block, 0, stream>>>(theta, m, v, S_id, S_sq, n, k); break;
     case PEX_MICROADAM_MSQ: adam_update_kernel<PEX_MICROADAM_MSQ><<<grid, block, 0, stream>>>(theta, m, v, S_id, S_sq, n, k); break;
     }
+    return hipGetLastError();
+}
+
+size_t moment_track_workspace(int64_t n) { return (size_t)update_grid(n) * 2 * sizeof(double); }
+
+hipError_t launch_moment_track(float* ema_adam, float* ema_micro, const float* S_id, const float* S_sq, int64_t n,
+                               const pex_moment_params& p, double* sums, double* partial, hipStream_t stream)
+{
+    MomentConsts k;
+    k.beta2 = p.beta2; k.one_m_beta2 = 1.f - p.beta2;
+    k.gs = p.grad_scale; k.qs = p.sq_scale;
+    k.corr = p.debias ? 1.0 / (1.0 - pow((double)p.beta2, (double)p.step)) : 1.0;
+    k.inv_B = 1.0 / (double)p.B;
+    k.c_est = 1.0 / (1.0 - k.inv_B);
+    const unsigned grid = update_grid(n);
+    moment_track_kernel<<<dim3(grid), dim3(256), 0, stream>>>(ema_adam, ema_micro, S_id, S_sq, n, k, partial);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    moment_finalize_kernel<<<dim3(1), dim3(256), 0, stream>>>(partial, (int)grid, sums);
     return hipGetLastError();
 }
 

@@ -40,6 +40,9 @@ def test_struct_layout_matches_header():
     # 8 floats, int64, int32 (+ padding): the layout a C compiler gives pex_adam_params
     assert ctypes.sizeof(pex.AdamParams) == 48
     assert pex.AdamParams.step.offset == 32 and pex.AdamParams.B.offset == 40
+    # pex_moment_params: 3 floats, 2 int32, padding to 8, int64
+    assert ctypes.sizeof(pex.MomentParams) == 32
+    assert pex.MomentParams.B.offset == 12 and pex.MomentParams.debias.offset == 16 and pex.MomentParams.step.offset == 24
 
 
 def test_workspace_query_is_bounded_and_independent_of_B():
@@ -116,6 +119,19 @@ def test_host_validation_launches_nothing():
     assert L.pex_signsgd_update(th, None, a, 16, 1e-3, 0.9, 0.0, 4, 0, 1, None) == 1
     assert L.pex_signsgd_update(th, m, a, 16, 1e-3, 0.9, 0.0, 0, 0, 1, None) == 2
     assert L.pex_signsgd_update(th, m, a + 8, 16, 1e-3, 0.9, 0.0, 4, 0, 1, None) == 5
+
+    mp = pex.MomentParams(beta2=0.95, grad_scale=0.25, sq_scale=0.25, B=4, debias=1, step=1)
+    wsb = pex.pex_moment_track_workspace_bytes(16)
+    assert 0 < wsb <= 1 << 16 and pex.pex_moment_track_workspace_bytes(1 << 30) <= 1 << 16
+    sums, ws = 0x6000, 0x7000
+    assert L.pex_moment_track(m, v, a, q, 16, ctypes.byref(mp), None, ws, wsb, None) == 1
+    assert L.pex_moment_track(m, v, a, q, 16, None, sums, ws, wsb, None) == 1
+    assert L.pex_moment_track(m, v, a, q, 0, ctypes.byref(mp), sums, ws, wsb, None) == 2
+    assert L.pex_moment_track(m, v, a, q, 16, ctypes.byref(mp), sums + 4, ws, wsb, None) == 5
+    assert L.pex_moment_track(m, v, a, q, 16, ctypes.byref(mp), sums, ws, wsb - 1, None) == 6
+    assert L.pex_moment_track(m, v, a, q, 16, ctypes.byref(mp), sums, None, 0, None) == 6
+    mp1 = pex.MomentParams(beta2=0.95, grad_scale=1.0, sq_scale=1.0, B=1, debias=1, step=1)
+    assert L.pex_moment_track(m, v, a, q, 16, ctypes.byref(mp1), sums, ws, wsb, None) == 2      # the estimators need B >= 2
 
 
 def test_binding_refuses_cpu_tensors():

@@ -146,3 +146,50 @@ def test_end_to_end_stat_then_update():
     np.testing.assert_allclose(v.cpu().double().numpy(), rv, rtol=1e-4)
     d_ref, d_got = rth - theta0.double().numpy(), th.cpu().double().numpy() - theta0.double().numpy()
     assert np.abs(d_got - d_ref).max() <= 1e-3 * np.abs(d_ref).max()
+
+
+@pytest.mark.parametrize("n", [1 << 20, 1000003, 3])
+@pytest.mark.parametrize("debias", [True, False])
+def test_moment_tracking_matches_oracle(n, debias):
+    """EMAs of nu_adam and nu_micro and the summed mu^2 / sigma^2 estimators (Sec. 3.2.2) over several steps."""
+    from oracle import moments as om
+    B, beta2 = 8, 0.95
+    rng = np.random.default_rng(n)
+    mu = rng.standard_normal(n) * 0.05
+    a = torch.zeros(n, device=DEV)
+    q = torch.zeros(n, device=DEV)
+    a_ref, q_ref = np.zeros(n), np.zeros(n)
+    for t in range(1, 5):
+        g = (mu[None, :] + rng.standard_normal((B, n))).astype(np.float32)
+        S_id = torch.from_numpy(g.sum(0)).to(DEV)
+        S_sq = torch.from_numpy((g * g).sum(0)).to(DEV)
+        prm = pex.MomentParams(beta2=beta2, grad_scale=1.0 / B, sq_scale=1.0 / B, B=B, debias=int(debias), step=t)
+        sums = pex.pex_moment_track(a, q, S_id, S_sq, prm).cpu().numpy()
+        a_ref, q_ref, ref = om.moment_track_step(a_ref, q_ref, S_id.cpu().double().numpy(), S_sq.cpu().double().numpy(),
+                                                 float(np.float32(beta2)), float(np.float32(1.0 / B)), float(np.float32(1.0 / B)), B, t, debias)
+        np.testing.assert_allclose(a.cpu().double().numpy(), a_ref, rtol=2e-6, atol=1e-30)
+        np.testing.assert_allclose(q.cpu().double().numpy(), q_ref, rtol=2e-6, atol=1e-30)
+        # the sums cancel (mu^2 << sigma^2 here): the bar is relative to the size of the terms, fp32 EMAs give ~1e-7 of it
+        assert abs(sums[0] - ref.sum_mu2) <= 2e-6 * ref.sum_abs, (sums, ref)
+        assert abs(sums[1] - ref.sum_sigma2) <= 2e-6 * ref.sum_abs, (sums, ref)
+    # run-to-run determinism of the reduction
+    a2, q2 = a.clone(), q.clone()
+    s1 = pex.pex_moment_track(a, q, S_id, S_sq, prm).clone()
+    s2 = pex.pex_moment_track(a2, q2, S_id, S_sq, prm)
+    assert torch.equal(s1, s2) and torch.equal(a, a2)
+
+
+def test_moment_tracking_recovers_planted_moments():
+    """Per-example gradients with known mu and sigma: after one step without memory the averaged estimators land on
+    mu^2 and sigma^2 within the Monte-Carlo error, through the whole GPU path (statistics, then tracking)."""
+    B, T, din, dout = 16, 4, 256, 512
+    X, G = si.custom(B, T, din, dout, dtype="bf16", seed=5)
+    Xd, Gd = X.to(DEV), G.to(DEV)
+    out = pex.pex_stat_multi(Xd, Gd, ("identity", "square"))
+    n = din * dout
+    a, q = torch.zeros(n, device=DEV), torch.zeros(n, device=DEV)
+    prm = pex.MomentParams(beta2=0.0, grad_scale=1.0 / B, sq_scale=1.0 / B, B=B, debias=1, step=1)
+    sums = pex.pex_moment_track(a, q, out["identity"].view(-1), out["square"].view(-1), prm).cpu().numpy() / n
+    # entries of X_b^T G_b are sums of T products of independent unit normals: mean 0, variance T
+    assert abs(sums[1] - T) < 0.02 * T
+    assert abs(sums[0]) < 0.1 * T / B            # nu_adam itself would sit at T / B

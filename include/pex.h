@@ -239,6 +239,24 @@ pex_status pex_moment_track(float *ema_adam, float *ema_micro, const float *S_id
                             const pex_moment_params *p /* host */, double *sums, void *workspace,
                             size_t workspace_bytes, pex_stream_t stream);
 
+/*
+ * pex_embed_stat -- per-example gradient statistics of an embedding table E[V, d].  A lookup is a dense layer on
+ * one-hot inputs (Sec. 2.3 with X one-hot): row v of the per-example gradient M_b is the sum of G[b,t,:] over the
+ * positions t of example b with ids[b,t] == v, and S = sum_b phi(M_b) with phi as in pex_stat (sgn(0) = 0).
+ *   ids   [B, T] token ids, int32 (ids_bytes = 4) or int64 (ids_bytes = 8), device memory, aligned to their size;
+ *         positions whose id is outside [0, V) (padding) contribute nothing
+ *   G     [B, T, d] cotangents of the looked-up vectors, dt = fp32 or bf16, row-major, 16-byte aligned
+ *   want  PEX_WANT_* bits; S_id, S_sq, S_sign: fp32 [V, d] each, 16-byte aligned, NULL where not wanted; every row
+ *         is overwritten (rows of tokens that do not occur with zeros)
+ * The workspace holds the positions sorted by token (integers only, about 20 bytes per position plus 4 per vocabulary
+ * row); no per-example gradient is stored.  Results do not depend on scheduling: positions are sorted stably and
+ * sums run in a fixed order.  Bound by HBM bandwidth.  B*T < 2^31, V < 2^31 - 1.
+ */
+size_t pex_embed_stat_workspace_bytes(int64_t B, int64_t T, int64_t V, int64_t d);
+pex_status pex_embed_stat(const void *ids, int32_t ids_bytes, const void *G, int64_t B, int64_t T, int64_t V, int64_t d,
+                          pex_dtype dt, uint32_t want, float *S_id, float *S_sq, float *S_sign, void *workspace,
+                          size_t workspace_bytes, pex_stream_t stream);
+
 #ifdef __cplusplus
 }
 #endif

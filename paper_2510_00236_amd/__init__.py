@@ -35,7 +35,7 @@ EXPORTS = ("pex_status_string", "pex_version", "pex_stat_workspace_bytes", "pex_
            "pex_weighted_sum", "pex_token_norms", "pex_sign_update",
            "pex_stat_power_workspace_bytes", "pex_stat_power",
            "pex_token_sq_workspace_bytes", "pex_token_sq", "pex_adam_update", "pex_signsgd_update",
-           "pex_moment_track_workspace_bytes", "pex_moment_track")
+           "pex_moment_track_workspace_bytes", "pex_moment_track", "pex_embed_stat_workspace_bytes", "pex_embed_stat")
 
 
 class PexError(RuntimeError):
@@ -111,6 +111,10 @@ def lib() -> ctypes.CDLL:
         L.pex_moment_track_workspace_bytes.restype = sz
         L.pex_moment_track.argtypes = [p, p, p, p, i64, ctypes.POINTER(MomentParams), p, p, sz, p]
         L.pex_moment_track.restype = ctypes.c_int
+        L.pex_embed_stat_workspace_bytes.argtypes = [i64, i64, i64, i64]
+        L.pex_embed_stat_workspace_bytes.restype = sz
+        L.pex_embed_stat.argtypes = [p, i32, p, i64, i64, i64, i64, ctypes.c_int, ctypes.c_uint32, p, p, p, p, sz, p]
+        L.pex_embed_stat.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -370,3 +374,33 @@ def pex_moment_track(ema_adam, ema_micro, S_id, S_sq, params: MomentParams, sums
                                   _dev(S_sq, "S_sq"), n, ctypes.byref(params), _dev(sums, "sums"), wptr, wbytes,
                                   _stream(stream)))
     return sums
+
+
+def pex_embed_stat_workspace_bytes(B, T, V, d) -> int:
+    return int(lib().pex_embed_stat_workspace_bytes(B, T, V, d))
+
+
+def pex_embed_stat(ids, G, V, want, out=None, workspace=None, stream=None):
+    """Per-example gradient statistics of an embedding table: ``ids`` [B,T] int32/int64, ``G`` [B,T,d] cotangents of
+    the looked-up vectors; returns a dict name -> S[V,d] fp32 for the names in ``want``.  Ids outside [0,V) are padding."""
+    import torch
+    if ids.dim() != 2 or G.dim() != 3 or tuple(G.shape[:2]) != tuple(ids.shape):
+        raise ValueError("ids must be [B,T] and G [B,T,d]")
+    if ids.dtype not in (torch.int32, torch.int64):
+        raise TypeError(f"ids must be int32 or int64, got {ids.dtype}")
+    B, T, d = G.shape
+    mask = _want_mask(want)
+    res, ptrs = {}, []
+    for name, bit in WANT.items():
+        if mask & bit:
+            S = (out or {}).get(name)
+            if S is None:
+                S = torch.empty(V, d, dtype=torch.float32, device=G.device)
+            res[name] = S
+            ptrs.append(_dev(S, name))
+        else:
+            ptrs.append(None)
+    ws, wptr, wbytes = _workspace(pex_embed_stat_workspace_bytes(B, T, V, d), G, workspace)
+    _check(lib().pex_embed_stat(_dev(ids, "ids"), ids.element_size(), _dev(G, "G"), B, T, V, d, _dtype_code(G), mask,
+                                ptrs[0], ptrs[1], ptrs[2], wptr, wbytes, _stream(stream)))
+    return res

@@ -392,6 +392,38 @@ pex_status pex_adam_update(float* theta, float* m, float* v, const float* S_id, 
                                                                                                            : PEX_ERR_HIP;
 }
 
+size_t pex_embed_stat_workspace_bytes(int64_t B, int64_t T, int64_t V, int64_t d)
+{
+    const int64_t lim = (int64_t)1 << 31;
+    if (B < 1 || T < 1 || V < 1 || d < 1 || B >= lim || T >= lim || B * T >= lim || V >= lim - 1) return 0;
+    return embed_workspace(B, T, V);
+}
+
+pex_status pex_embed_stat(const void* ids, int32_t ids_bytes, const void* G, int64_t B, int64_t T, int64_t V, int64_t d,
+                          pex_dtype dt, uint32_t want, float* S_id, float* S_sq, float* S_sign, void* workspace,
+                          size_t workspace_bytes, pex_stream_t stream)
+{
+    if (want == 0 || (want & ~7u)) return PEX_ERR_PHI;
+    if (!ids || !G) return PEX_ERR_NULL;
+    if ((want & PEX_WANT_IDENTITY) && !S_id) return PEX_ERR_NULL;
+    if ((want & PEX_WANT_SQUARE) && !S_sq) return PEX_ERR_NULL;
+    if ((want & PEX_WANT_SIGN) && !S_sign) return PEX_ERR_NULL;
+    if (dt != PEX_F32 && dt != PEX_BF16) return PEX_ERR_DTYPE;
+    if (ids_bytes != 4 && ids_bytes != 8) return PEX_ERR_DTYPE;
+    const int64_t lim = (int64_t)1 << 31;
+    if (B < 1 || T < 1 || V < 1 || d < 1 || B >= lim || T >= lim || B * T >= lim || V >= lim - 1 || d >= lim) return PEX_ERR_SHAPE;
+    uintptr_t al = (uintptr_t)G;
+    if (want & PEX_WANT_IDENTITY) al |= (uintptr_t)S_id;
+    if (want & PEX_WANT_SQUARE) al |= (uintptr_t)S_sq;
+    if (want & PEX_WANT_SIGN) al |= (uintptr_t)S_sign;
+    if ((al & 15u) || ((uintptr_t)ids & (uintptr_t)(ids_bytes - 1))) return PEX_ERR_ALIGN;
+    if (!workspace || workspace_bytes < embed_workspace(B, T, V)) return PEX_ERR_WORKSPACE;
+    if ((uintptr_t)workspace & 15u) return PEX_ERR_ALIGN;
+    return launch_embed_stat(ids, ids_bytes, G, B, T, V, d, dt, want, S_id, S_sq, S_sign, workspace, (hipStream_t)stream) == hipSuccess
+               ? PEX_OK
+               : PEX_ERR_HIP;
+}
+
 size_t pex_moment_track_workspace_bytes(int64_t n) { return n < 1 ? 0 : moment_track_workspace(n); }
 
 pex_status pex_moment_track(float* ema_adam, float* ema_micro, const float* S_id, const float* S_sq, int64_t n,

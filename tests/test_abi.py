@@ -120,6 +120,24 @@ def test_host_validation_launches_nothing():
     assert L.pex_signsgd_update(th, m, a, 16, 1e-3, 0.9, 0.0, 0, 0, 1, None) == 2
     assert L.pex_signsgd_update(th, m, a + 8, 16, 1e-3, 0.9, 0.0, 4, 0, 1, None) == 5
 
+    ids, Gp, Sp, wsp = 0x8000, 0x9000, 0xa000, 0xb000
+    need = pex.pex_embed_stat_workspace_bytes(4, 16, 100, 64)
+    assert 0 < need <= 5 * 4 * 64 + 4 * 102 + 4 * 1024 + 6 * 256       # integers per position and per row, no [B, V, d] tensor
+    assert pex.pex_embed_stat_workspace_bytes(64, 1024, 50257, 768) < 4 << 20
+    assert pex.pex_embed_stat_workspace_bytes(0, 16, 100, 64) == 0
+    assert L.pex_embed_stat(None, 8, Gp, 4, 16, 100, 64, 1, 7, Sp, Sp, Sp, wsp, need, None) == 1
+    assert L.pex_embed_stat(ids, 8, Gp, 4, 16, 100, 64, 1, 2, Sp, None, Sp, wsp, need, None) == 1   # wanted output missing
+    assert L.pex_embed_stat(ids, 8, Gp, 4, 16, 100, 64, 1, 0, Sp, Sp, Sp, wsp, need, None) == 4
+    assert L.pex_embed_stat(ids, 8, Gp, 4, 16, 100, 64, 1, 8, Sp, Sp, Sp, wsp, need, None) == 4
+    assert L.pex_embed_stat(ids, 2, Gp, 4, 16, 100, 64, 1, 7, Sp, Sp, Sp, wsp, need, None) == 3    # ids are int32 or int64
+    assert L.pex_embed_stat(ids, 8, Gp, 4, 16, 100, 64, 9, 7, Sp, Sp, Sp, wsp, need, None) == 3
+    assert L.pex_embed_stat(ids, 8, Gp, 4, 16, 0, 64, 1, 7, Sp, Sp, Sp, wsp, need, None) == 2
+    assert L.pex_embed_stat(ids, 8, Gp, 1 << 20, 1 << 12, 100, 64, 1, 7, Sp, Sp, Sp, wsp, need, None) == 2   # B*T >= 2^31
+    assert L.pex_embed_stat(ids + 4, 8, Gp, 4, 16, 100, 64, 1, 7, Sp, Sp, Sp, wsp, need, None) == 5
+    assert L.pex_embed_stat(ids, 8, Gp + 8, 4, 16, 100, 64, 1, 7, Sp, Sp, Sp, wsp, need, None) == 5
+    assert L.pex_embed_stat(ids, 8, Gp, 4, 16, 100, 64, 1, 7, Sp, Sp, Sp, wsp, need - 1, None) == 6
+    assert L.pex_embed_stat(ids, 8, Gp, 4, 16, 100, 64, 1, 7, Sp, Sp, Sp, None, 0, None) == 6
+
     mp = pex.MomentParams(beta2=0.95, grad_scale=0.25, sq_scale=0.25, B=4, debias=1, step=1)
     wsb = pex.pex_moment_track_workspace_bytes(16)
     assert 0 < wsb <= 1 << 16 and pex.pex_moment_track_workspace_bytes(1 << 30) <= 1 << 16

@@ -11,9 +11,11 @@
 //      enter in the order p = b*T + t, so inside a token's run they stay ordered by example and then by t;
 //      ids outside [0, V) (padding) get the key V and are never consumed;
 //   2. row_start[v] = first sorted index whose key is >= v;
-//   3. one wave per vocabulary row walks the row's positions: cotangent rows are added per example, phi is applied
-//      whenever the example changes, and the result is added to the row's sums.  Rows with many positions are done
-//      by all waves of the workgroup, each on a contiguous run of whole examples, and combined in wave order.
+//   3. each wave owns 16 consecutive sorted positions and every vocabulary row whose run starts among them: cotangent
+//      rows are loaded 16 at a time and added per example, phi is applied whenever the example changes, and the result
+//      is added to the row's sums.  Rows with many positions are done by all waves of the workgroup, each on a
+//      contiguous run of whole examples, and combined in wave order; rows without positions are zero-filled by
+//      further workgroups of the same launch.
 #include <type_traits>
 
 #include "pex_internal.h"
@@ -21,7 +23,7 @@
 namespace pex {
 namespace {
 
-constexpr int SORT_TILE = 1024;   // keys per workgroup of the sort: 256 threads x 4 rounds
+constexpr int SORT_TILE = 2048;   // keys per workgroup of the sort: 256 threads x 8 rounds
 
 template <typename TId>
 __device__ __forceinline__ int load_key(const TId* __restrict__ ids, int p, int V)
@@ -53,31 +55,46 @@ __global__ __launch_bounds__(256) void sort_hist_kernel(const TId* __restrict__ 
 }
 
 // exclusive prefix sum, in place, of the `entries` counters (digit-major, block-minor: the order in which a stable
-// sort lays the keys out); one workgroup
+// sort lays the keys out); one workgroup walks the array in tiles of 4096 counters, four per thread
 __global__ __launch_bounds__(1024) void sort_scan_kernel(int* __restrict__ h, int64_t entries)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t chunk = (entries + 1023) / 1024;
-    int64_t lo = (int64_t)threadIdx.x * chunk;
-    if (lo > entries) lo = entries;
-    const int64_t hi = lo + chunk < entries ? lo + chunk : entries;
-    int s = 0;
-    for (int64_t i = lo; i < hi; ++i) s += h[i];
-    int incl = s;
+    __shared__ int wsum[2][16];
+    int carry = 0;
+    int par = 0;
+    int nxt[4];
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const int t = __shfl_up(incl, o);
-        if (lane >= o) incl += t;
-    }
-    __shared__ int wsum[16];
-    if (lane == 63) wsum[wave] = incl;
-    __syncthreads();
-    int run = incl - s;
-    for (int w = 0; w < wave; ++w) run += wsum[w];
-    for (int64_t i = lo; i < hi; ++i) {
-        const int t = h[i];
-        h[i] = run;
-        run += t;
+    for (int e = 0; e < 4; ++e) nxt[e] = ((int64_t)threadIdx.x * 4 + e < entries) ? h[(int64_t)threadIdx.x * 4 + e] : 0;
+    for (int64_t t0 = 0; t0 < entries; t0 += 4096, par ^= 1) {
+        const int64_t i0 = t0 + (int64_t)threadIdx.x * 4;
+        int v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            v[e] = nxt[e];
+            nxt[e] = (i0 + 4096 + e < entries) ? h[i0 + 4096 + e] : 0;   // the next tile's counters, in flight during this tile
+        }
+        const int s = (v[0] + v[1]) + (v[2] + v[3]);
+        int incl = s;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(incl, o);
+            if (lane >= o) incl += t;
+        }
+        if (lane == 63) wsum[par][wave] = incl;
+        __syncthreads();   // the other half of wsum is still being read by slower waves of the previous tile
+        int run = carry + incl - s, total = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            const int t = wsum[par][w];
+            if (w < wave) run += t;
+            total += t;
+        }
+        carry += total;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (i0 + e < entries) h[i0 + e] = run;
+            run += v[e];
+        }
     }
 }
 
@@ -148,28 +165,33 @@ __global__ __launch_bounds__(256) void row_start_kernel(const int* __restrict__ 
 __device__ __forceinline__ float widen_el(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 __device__ __forceinline__ float widen_el(float f) { return f; }
 
-// The 16 bytes (CH > 1) or the one element (CH == 1) a lane loads from a cotangent row, kept as loaded until it is
-// added: widening bf16 early would double the registers a lane holds in flight.
+// What a lane loads from a cotangent row: CH elements (4 fp32 = 16 bytes, 4 bf16 = 8 bytes, or one element), kept as
+// loaded until it is added: widening bf16 early would double the registers a lane holds in flight.  Four columns per
+// lane make the fp32 stores of a wave dense (16 bytes per lane, 1 KiB per instruction); eight bf16 columns per lane
+// would leave every store instruction writing half of each 32 bytes.
 template <typename TIn, int CH>
 struct Chunk {
     typedef __attribute__((ext_vector_type(4))) unsigned int u4;
-    typedef typename std::conditional<CH == 1, TIn, u4>::type Raw;
+    typedef __attribute__((ext_vector_type(2))) unsigned int u2;
+    typedef typename std::conditional<CH == 1, TIn, typename std::conditional<sizeof(TIn) == 2, u2, u4>::type>::type Raw;
+    static_assert(CH == 1 || CH == 4, "one element or four");
     static __device__ __forceinline__ Raw zero()
     {
         if constexpr (CH == 1) return (TIn)0;
+        else if constexpr (sizeof(TIn) == 2) return u2{0u, 0u};
         else return u4{0u, 0u, 0u, 0u};
     }
     static __device__ __forceinline__ Raw load(const TIn* p)
     {
         if constexpr (CH == 1) return p[0];
-        else return *(const u4*)p;
+        else return *(const Raw*)p;
     }
     static __device__ __forceinline__ void add_to(float (&acc)[CH], const Raw& raw)
     {
         if constexpr (CH == 1) acc[0] += widen_el(raw);
         else if constexpr (sizeof(TIn) == 2) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
+            for (int e = 0; e < 2; ++e) {
                 acc[2 * e] += __uint_as_float(raw[e] << 16);
                 acc[2 * e + 1] += __uint_as_float(raw[e] & 0xffff0000u);
             }
@@ -190,9 +212,10 @@ __device__ __forceinline__ void store_chunk(float* p, const float (&v)[CH])
     }
 }
 
-constexpr int EMB_WAVES = 8;     // waves of a workgroup = vocabulary rows it owns
-constexpr int EMB_U = 16;        // cotangent rows a lane keeps in flight
-constexpr int EMB_ALONE = 64;    // a row with at most this many positions is done by its own wave
+constexpr int EMB_WAVES = 16;    // waves of a workgroup
+constexpr int EMB_ZROWS = 8;     // vocabulary rows a zero-fill wave looks at
+constexpr int EMB_U = 16;        // sorted positions a wave owns = cotangent rows a lane keeps in flight
+constexpr int EMB_ALONE = 64;    // a vocabulary row with at most this many positions is done by one wave
 
 template <int CH>
 struct RowSums {
@@ -215,61 +238,71 @@ __device__ __forceinline__ int first_at_least(const int* __restrict__ pos, int l
     return lo;
 }
 
-// WANT: bit 0 identity, bit 1 square, bit 2 sign.  grid = (ceil(V / EMB_WAVES), column blocks of 64 * CH columns).
+// Accumulates the cotangent rows of one vocabulary row, example by example: acc holds the running sum of the current
+// example, phi(acc) goes to the row's sums when the example changes.
+template <typename TIn, int CH, int WANT>
+struct RowAccumulator {
+    RowSums<CH> sums;
+    float acc[CH];
+    int limit;     // first position of the next example
+    bool open;     // acc holds something
+    int T;
+    __device__ __forceinline__ void start(int T_)
+    {
+        T = T_;
+        sums.clear();
+#pragma unroll
+        for (int e = 0; e < CH; ++e) acc[e] = 0.f;
+        limit = 0;
+        open = false;
+    }
+    __device__ __forceinline__ void fold()
+    {
+#pragma unroll
+        for (int e = 0; e < CH; ++e) {
+            if (WANT & 1) sums.id[e] += acc[e];
+            if (WANT & 2) sums.sq[e] = fmaf(acc[e], acc[e], sums.sq[e]);
+            if (WANT & 4) sums.sg[e] += (float)((acc[e] > 0.f) - (acc[e] < 0.f));
+            acc[e] = 0.f;
+        }
+    }
+    // p is uniform over the wave
+    __device__ __forceinline__ void add(int p, const typename Chunk<TIn, CH>::Raw& raw)
+    {
+        if (p >= limit) {
+            if (open) fold();
+            open = true;
+            limit = (p / T + 1) * T;
+        }
+        Chunk<TIn, CH>::add_to(acc, raw);
+    }
+    __device__ __forceinline__ void finish()
+    {
+        if (open) fold();
+        open = false;
+        limit = 0;
+    }
+};
+
+// WANT: bit 0 identity, bit 1 square, bit 2 sign.
+// grid.x = chunk workgroups, then zero-fill workgroups; grid.y = blocks of 64 * CH columns.
+//   chunk workgroup: wave i owns the sorted positions [c0, c0 + EMB_U) and with them every vocabulary row whose run
+//     starts there (a run may continue past the chunk).  It loads EMB_U cotangent rows at a time whatever rows and
+//     examples they belong to, then adds them in order.  Runs longer than EMB_ALONE are only noted; after a barrier
+//     the whole workgroup does each of them, every wave on a contiguous run of whole examples, combined in wave order.
+//   zero-fill workgroup: wave i looks at EMB_ZROWS vocabulary rows and writes zeros to those without positions.
 template <typename TIn, int CH, int WANT>
 __global__ __launch_bounds__(EMB_WAVES * 64) void embed_rows_kernel(const TIn* __restrict__ G, const int* __restrict__ row_start,
-                                                                    const int* __restrict__ pos, int N, int V, int T, int64_t d,
+                                                                    const int* __restrict__ keys, const int* __restrict__ pos,
+                                                                    int N, int V, int T, int64_t d, int chunk_groups,
                                                                     float* __restrict__ S_id, float* __restrict__ S_sq,
                                                                     float* __restrict__ S_sg)
 {
+    typedef Chunk<TIn, CH> Ck;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int64_t col = ((int64_t)blockIdx.y * 64 + lane) * CH;
     const bool col_ok = col < d;
-    const int nwg = (int)gridDim.x;
-    __shared__ int heavy[EMB_WAVES];
-    __shared__ float comb[3][64 * CH];
-
-    // sums over the examples found in [lo, hi) of phi(sum of the example's cotangent rows)
-    auto process = [&](int lo, int hi, RowSums<CH>& sums) {
-        float acc[CH];
-#pragma unroll
-        for (int e = 0; e < CH; ++e) acc[e] = 0.f;
-        bool open = false;
-        int limit = 0;   // first position of the next example
-        auto fold = [&]() {
-#pragma unroll
-            for (int e = 0; e < CH; ++e) {
-                if (WANT & 1) sums.id[e] += acc[e];
-                if (WANT & 2) sums.sq[e] = fmaf(acc[e], acc[e], sums.sq[e]);
-                if (WANT & 4) sums.sg[e] += (float)((acc[e] > 0.f) - (acc[e] < 0.f));
-                acc[e] = 0.f;
-            }
-        };
-        for (int k0 = lo; k0 < hi; k0 += EMB_U) {
-            int pp[EMB_U];
-            typename Chunk<TIn, CH>::Raw data[EMB_U];
-#pragma unroll
-            for (int u = 0; u < EMB_U; ++u) {
-                pp[u] = (k0 + u < hi) ? pos[k0 + u] : -1;
-                if (pp[u] >= N) pp[u] = -1;   // positions are in [0, N)
-            }
-#pragma unroll
-            for (int u = 0; u < EMB_U; ++u)
-                data[u] = (pp[u] >= 0 && col_ok) ? Chunk<TIn, CH>::load(G + (int64_t)pp[u] * d + col) : Chunk<TIn, CH>::zero();
-#pragma unroll
-            for (int u = 0; u < EMB_U; ++u) {
-                if (pp[u] < 0) continue;
-                if (pp[u] >= limit) {
-                    if (open) fold();
-                    open = true;
-                    limit = (pp[u] / T + 1) * T;
-                }
-                Chunk<TIn, CH>::add_to(acc, data[u]);
-            }
-        }
-        if (open) fold();
-    };
     auto store_row = [&](int v, const RowSums<CH>& sums) {
         if (!col_ok) return;
         const int64_t o = (int64_t)v * d + col;
@@ -278,25 +311,91 @@ __global__ __launch_bounds__(EMB_WAVES * 64) void embed_rows_kernel(const TIn* _
         if (WANT & 4) store_chunk<CH>(S_sg + o, sums.sg);
     };
 
-    // rows of one workgroup are nwg apart, so the most frequent tokens (which tend to have neighbouring ids) land in
-    // different workgroups
-    const int v = wave * nwg + (int)blockIdx.x;
-    int s = 0, e = 0;
-    if (v < V) { s = row_start[v]; e = row_start[v + 1]; }
-    s = s < 0 ? 0 : (s > N ? N : s);   // row starts ascend within [0, N]
-    e = e < s ? s : (e > N ? N : e);
-    const bool is_heavy = e - s > EMB_ALONE;
-    if (lane == 0) heavy[wave] = is_heavy ? 1 : 0;
-    if (v < V && !is_heavy) {
-        RowSums<CH> sums;
-        sums.clear();
-        if (e > s) process(s, e, sums);
-        store_row(v, sums);
+    if ((int)blockIdx.x >= chunk_groups) {
+        // whole rows, all column blocks by the same wave: an empty row is one contiguous run of d floats, and empty
+        // rows are often neighbours
+        if (blockIdx.y != 0) return;
+        const int v = (((int)blockIdx.x - chunk_groups) * EMB_WAVES + wave) * EMB_ZROWS + lane;
+        const bool empty = lane < EMB_ZROWS && v < V && row_start[v] == row_start[v + 1];
+        unsigned long long todo = __ballot(empty);
+        RowSums<CH> zeros;
+        zeros.clear();
+        while (todo) {
+            const int l = __builtin_ctzll(todo);
+            todo &= todo - 1;
+            const int64_t o = (int64_t)(v - lane + l) * d;
+            for (int64_t c = (int64_t)lane * CH; c < d; c += 64 * CH) {
+                if (WANT & 1) store_chunk<CH>(S_id + o + c, zeros.id);
+                if (WANT & 2) store_chunk<CH>(S_sq + o + c, zeros.sq);
+                if (WANT & 4) store_chunk<CH>(S_sg + o + c, zeros.sg);
+            }
+        }
+        return;
+    }
+
+    __shared__ int n_heavy;
+    __shared__ int heavy_row[EMB_WAVES];
+    __shared__ float comb[3][64 * CH];
+    if (threadIdx.x == 0) n_heavy = 0;
+    __syncthreads();
+
+    RowAccumulator<TIn, CH, WANT> ra;
+    ra.start(T);
+    {
+        const int64_t c0l = ((int64_t)blockIdx.x * EMB_WAVES + wave) * EMB_U;
+        const int c0 = c0l < N ? (int)c0l : N;
+        const int c1 = c0 + EMB_U < N ? c0 + EMB_U : N;
+        int k0 = c0;
+        int cur_v = -1;      // the row being accumulated
+        int open_end = 0;    // where its run ends
+        while (k0 < (c1 > open_end ? c1 : open_end)) {
+            // lane u < EMB_U looks up position k0 + u: its token, the extent of the token's run, whether the run is ours
+            const int k = k0 + lane;
+            const bool valid = lane < EMB_U && k < N;
+            int key = V, p = -1, rs = 0, re = 0;
+            if (valid) { key = keys[k]; p = pos[k]; }
+            key = key < 0 ? V : (key > V ? V : key);
+            if (valid && key < V) { rs = row_start[key]; re = row_start[key + 1]; }
+            re = re > N ? N : re;
+            const bool ours = valid && key < V && rs >= c0 && rs < c1;
+            const bool is_heavy = re - rs > EMB_ALONE;
+            if (ours && is_heavy && k == rs) {
+                const int slot = atomicAdd(&n_heavy, 1);   // at most one such run can start among EMB_U positions
+                if (slot < EMB_WAVES) heavy_row[slot] = key;
+            }
+            const int p_ld = (ours && !is_heavy && p >= 0 && p < N) ? p : -1;
+            int pu[EMB_U], ku[EMB_U], eu[EMB_U];
+            typename Ck::Raw data[EMB_U];
+#pragma unroll
+            for (int u = 0; u < EMB_U; ++u) {
+                pu[u] = __builtin_amdgcn_readlane(p_ld, u);
+                ku[u] = __builtin_amdgcn_readlane(key, u);
+                eu[u] = __builtin_amdgcn_readlane(re, u);
+            }
+#pragma unroll
+            for (int u = 0; u < EMB_U; ++u) data[u] = (pu[u] >= 0 && col_ok) ? Ck::load(G + (int64_t)pu[u] * d + col) : Ck::zero();
+#pragma unroll
+            for (int u = 0; u < EMB_U; ++u) {
+                if (pu[u] < 0) continue;
+                if (ku[u] != cur_v) {
+                    if (cur_v >= 0) { ra.finish(); store_row(cur_v, ra.sums); ra.sums.clear(); }
+                    cur_v = ku[u];
+                    open_end = eu[u];
+                }
+                ra.add(pu[u], data[u]);
+            }
+            // the last position of the batch decides where the next batch starts: inside a run that is loaded the next
+            // batch follows on; a run that is not (another wave's, or a long one) is skipped to its end
+            const int last_ld = pu[EMB_U - 1], last_end = eu[EMB_U - 1];
+            const int next = k0 + EMB_U;
+            k0 = (last_ld >= 0 || last_end < next) ? next : last_end;
+        }
+        if (cur_v >= 0) { ra.finish(); store_row(cur_v, ra.sums); }
     }
     __syncthreads();
-    for (int w = 0; w < EMB_WAVES; ++w) {
-        if (!heavy[w]) continue;   // the same for every wave of the workgroup
-        const int hv = w * nwg + (int)blockIdx.x;
+    const int nh = n_heavy < EMB_WAVES ? n_heavy : EMB_WAVES;
+    for (int h = 0; h < nh; ++h) {
+        const int hv = heavy_row[h];
         int hs = row_start[hv], he = row_start[hv + 1];
         hs = hs < 0 ? 0 : (hs > N ? N : hs);
         he = he < hs ? hs : (he > N ? N : he);
@@ -306,20 +405,34 @@ __global__ __launch_bounds__(EMB_WAVES * 64) void embed_rows_kernel(const TIn* _
             if (i <= 0) return hs;
             if (i >= EMB_WAVES) return he;
             const int k = hs + (int)(((int64_t)(he - hs) * i) / EMB_WAVES);
+            if (k <= hs) return hs;
             const int limit = (pos[k - 1] / T + 1) * T;
             return first_at_least(pos, k, he, limit);
         };
         const int lo = bound(wave), hi = bound(wave + 1);
-        RowSums<CH> sums;
-        sums.clear();
-        if (hi > lo) process(lo, hi, sums);
+        ra.start(T);
+        for (int k0 = lo; k0 < hi; k0 += EMB_U) {
+            int pp[EMB_U];
+            typename Ck::Raw data[EMB_U];
+#pragma unroll
+            for (int u = 0; u < EMB_U; ++u) {
+                pp[u] = (k0 + u < hi) ? pos[k0 + u] : -1;
+                if (pp[u] >= N) pp[u] = -1;   // positions are in [0, N)
+            }
+#pragma unroll
+            for (int u = 0; u < EMB_U; ++u) data[u] = (pp[u] >= 0 && col_ok) ? Ck::load(G + (int64_t)pp[u] * d + col) : Ck::zero();
+#pragma unroll
+            for (int u = 0; u < EMB_U; ++u)
+                if (pp[u] >= 0) ra.add(pp[u], data[u]);
+        }
+        ra.finish();
         for (int i = 0; i < EMB_WAVES; ++i) {
             if (wave == i) {
 #pragma unroll
                 for (int e2 = 0; e2 < CH; ++e2) {
                     const int o = lane * CH + e2;
-                    if (i == 0) { comb[0][o] = sums.id[e2]; comb[1][o] = sums.sq[e2]; comb[2][o] = sums.sg[e2]; }
-                    else { comb[0][o] += sums.id[e2]; comb[1][o] += sums.sq[e2]; comb[2][o] += sums.sg[e2]; }
+                    if (i == 0) { comb[0][o] = ra.sums.id[e2]; comb[1][o] = ra.sums.sq[e2]; comb[2][o] = ra.sums.sg[e2]; }
+                    else { comb[0][o] += ra.sums.id[e2]; comb[1][o] += ra.sums.sq[e2]; comb[2][o] += ra.sums.sg[e2]; }
                 }
             }
             __syncthreads();
@@ -328,9 +441,9 @@ __global__ __launch_bounds__(EMB_WAVES * 64) void embed_rows_kernel(const TIn* _
 #pragma unroll
             for (int e2 = 0; e2 < CH; ++e2) {
                 const int o = lane * CH + e2;
-                sums.id[e2] = comb[0][o]; sums.sq[e2] = comb[1][o]; sums.sg[e2] = comb[2][o];
+                ra.sums.id[e2] = comb[0][o]; ra.sums.sq[e2] = comb[1][o]; ra.sums.sg[e2] = comb[2][o];
             }
-            store_row(hv, sums);
+            store_row(hv, ra.sums);
         }
         __syncthreads();
     }
@@ -393,26 +506,30 @@ hipError_t sort_positions(const TId* ids, int N, int V, const EmbedLayout& L, ch
 }
 
 template <typename TIn, int CH, int WANT>
-hipError_t launch_rows(const TIn* G, const int* row_start, const int* pos, int N, int V, int T, int64_t d, float* S_id, float* S_sq,
-                       float* S_sg, hipStream_t stream)
+hipError_t launch_rows(const TIn* G, const int* row_start, const int* keys, const int* pos, int N, int V, int T, int64_t d,
+                       float* S_id, float* S_sq, float* S_sg, hipStream_t stream)
 {
-    const dim3 grid((unsigned)((V + EMB_WAVES - 1) / EMB_WAVES), (unsigned)((d + 64 * CH - 1) / (64 * CH)));
-    embed_rows_kernel<TIn, CH, WANT><<<grid, dim3(EMB_WAVES * 64), 0, stream>>>(G, row_start, pos, N, V, T, d, S_id, S_sq, S_sg);
+    const int64_t per_group = (int64_t)EMB_WAVES * EMB_U;
+    const int chunk_groups = (int)((N + per_group - 1) / per_group);
+    const int zero_groups = (int)(((int64_t)V + EMB_WAVES * EMB_ZROWS - 1) / (EMB_WAVES * EMB_ZROWS));
+    const dim3 grid((unsigned)(chunk_groups + zero_groups), (unsigned)((d + 64 * CH - 1) / (64 * CH)));
+    embed_rows_kernel<TIn, CH, WANT><<<grid, dim3(EMB_WAVES * 64), 0, stream>>>(G, row_start, keys, pos, N, V, T, d, chunk_groups,
+                                                                                  S_id, S_sq, S_sg);
     return hipGetLastError();
 }
 
 template <typename TIn, int CH>
-hipError_t launch_rows_want(uint32_t want, const TIn* G, const int* rs, const int* pos, int N, int V, int T, int64_t d, float* a,
+hipError_t launch_rows_want(uint32_t want, const TIn* G, const int* rs, const int* keys, const int* pos, int N, int V, int T, int64_t d, float* a,
                             float* q, float* g, hipStream_t st)
 {
     switch (want) {
-    case 1: return launch_rows<TIn, CH, 1>(G, rs, pos, N, V, T, d, a, q, g, st);
-    case 2: return launch_rows<TIn, CH, 2>(G, rs, pos, N, V, T, d, a, q, g, st);
-    case 3: return launch_rows<TIn, CH, 3>(G, rs, pos, N, V, T, d, a, q, g, st);
-    case 4: return launch_rows<TIn, CH, 4>(G, rs, pos, N, V, T, d, a, q, g, st);
-    case 5: return launch_rows<TIn, CH, 5>(G, rs, pos, N, V, T, d, a, q, g, st);
-    case 6: return launch_rows<TIn, CH, 6>(G, rs, pos, N, V, T, d, a, q, g, st);
-    default: return launch_rows<TIn, CH, 7>(G, rs, pos, N, V, T, d, a, q, g, st);
+    case 1: return launch_rows<TIn, CH, 1>(G, rs, keys, pos, N, V, T, d, a, q, g, st);
+    case 2: return launch_rows<TIn, CH, 2>(G, rs, keys, pos, N, V, T, d, a, q, g, st);
+    case 3: return launch_rows<TIn, CH, 3>(G, rs, keys, pos, N, V, T, d, a, q, g, st);
+    case 4: return launch_rows<TIn, CH, 4>(G, rs, keys, pos, N, V, T, d, a, q, g, st);
+    case 5: return launch_rows<TIn, CH, 5>(G, rs, keys, pos, N, V, T, d, a, q, g, st);
+    case 6: return launch_rows<TIn, CH, 6>(G, rs, keys, pos, N, V, T, d, a, q, g, st);
+    default: return launch_rows<TIn, CH, 7>(G, rs, keys, pos, N, V, T, d, a, q, g, st);
     }
 }
 
@@ -437,11 +554,11 @@ hipError_t launch_embed_stat(const void* ids, int ids_bytes, const void* G, int6
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (dt == PEX_BF16) {
-        if (d % 8 == 0) return launch_rows_want<uint16_t, 8>(want, (const uint16_t*)G, row_start, pos, N, (int)V, (int)T, d, S_id, S_sq, S_sign, stream);
-        return launch_rows_want<uint16_t, 1>(want, (const uint16_t*)G, row_start, pos, N, (int)V, (int)T, d, S_id, S_sq, S_sign, stream);
+        if (d % 4 == 0) return launch_rows_want<uint16_t, 4>(want, (const uint16_t*)G, row_start, keys, pos, N, (int)V, (int)T, d, S_id, S_sq, S_sign, stream);
+        return launch_rows_want<uint16_t, 1>(want, (const uint16_t*)G, row_start, keys, pos, N, (int)V, (int)T, d, S_id, S_sq, S_sign, stream);
     }
-    if (d % 4 == 0) return launch_rows_want<float, 4>(want, (const float*)G, row_start, pos, N, (int)V, (int)T, d, S_id, S_sq, S_sign, stream);
-    return launch_rows_want<float, 1>(want, (const float*)G, row_start, pos, N, (int)V, (int)T, d, S_id, S_sq, S_sign, stream);
+    if (d % 4 == 0) return launch_rows_want<float, 4>(want, (const float*)G, row_start, keys, pos, N, (int)V, (int)T, d, S_id, S_sq, S_sign, stream);
+    return launch_rows_want<float, 1>(want, (const float*)G, row_start, keys, pos, N, (int)V, (int)T, d, S_id, S_sq, S_sign, stream);
 }
 
 }  // namespace pex

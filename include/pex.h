@@ -248,8 +248,9 @@ pex_status pex_moment_track(float *ema_adam, float *ema_micro, const float *S_id
  *   G     [B, T, d] cotangents of the looked-up vectors, dt = fp32 or bf16, row-major, 16-byte aligned
  *   want  PEX_WANT_* bits; S_id, S_sq, S_sign: fp32 [V, d] each, 16-byte aligned, NULL where not wanted; every row
  *         is overwritten (rows of tokens that do not occur with zeros)
- * The workspace holds the positions sorted by token (integers only, about 20 bytes per position plus 4 per vocabulary
- * row); no per-example gradient is stored.  Results do not depend on scheduling: positions are sorted stably and
+ * The workspace holds the positions sorted by token (about 20 bytes per position plus 4 per vocabulary row) and, for
+ * the runs of frequent tokens, two partial rows of each statistic per 256 positions (about 0.1 * d bytes per position);
+ * no per-example gradient is stored.  Results do not depend on scheduling: positions are sorted stably and
  * sums run in a fixed order.  Bound by HBM bandwidth.  B*T < 2^31, V < 2^31 - 1.
  */
 size_t pex_embed_stat_workspace_bytes(int64_t B, int64_t T, int64_t V, int64_t d);

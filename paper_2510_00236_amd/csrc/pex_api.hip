@@ -396,7 +396,7 @@ size_t pex_embed_stat_workspace_bytes(int64_t B, int64_t T, int64_t V, int64_t d
 {
     const int64_t lim = (int64_t)1 << 31;
     if (B < 1 || T < 1 || V < 1 || d < 1 || B >= lim || T >= lim || B * T >= lim || V >= lim - 1) return 0;
-    return embed_workspace(B, T, V);
+    return embed_workspace(B, T, V, d);
 }
 
 pex_status pex_embed_stat(const void* ids, int32_t ids_bytes, const void* G, int64_t B, int64_t T, int64_t V, int64_t d,
@@ -417,7 +417,7 @@ pex_status pex_embed_stat(const void* ids, int32_t ids_bytes, const void* G, int
     if (want & PEX_WANT_SQUARE) al |= (uintptr_t)S_sq;
     if (want & PEX_WANT_SIGN) al |= (uintptr_t)S_sign;
     if ((al & 15u) || ((uintptr_t)ids & (uintptr_t)(ids_bytes - 1))) return PEX_ERR_ALIGN;
-    if (!workspace || workspace_bytes < embed_workspace(B, T, V)) return PEX_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes < embed_workspace(B, T, V, d)) return PEX_ERR_WORKSPACE;
     if ((uintptr_t)workspace & 15u) return PEX_ERR_ALIGN;
     return launch_embed_stat(ids, ids_bytes, G, B, T, V, d, dt, want, S_id, S_sq, S_sign, workspace, (hipStream_t)stream) == hipSuccess
                ? PEX_OK

@@ -7,9 +7,9 @@
 // not occur are written as zeros), plus the ids.
 //
 // Everything is deterministic (no floating-point atomics):
-//   1. a stable least-significant-digit radix sort (8 bits per pass) of the B*T positions by token id; positions
-//      enter in the order p = b*T + t, so inside a token's run they stay ordered by example and then by t;
-//      ids outside [0, V) (padding) get the key V and are never consumed;
+//   1. a stable least-significant-digit radix sort (8 bits per pass, a counting and a placing launch per pass) of
+//      the B*T positions by token id; positions enter in the order p = b*T + t, so inside a token's run
+//      they stay ordered by example and then by t; ids outside [0, V) (padding) get the key V and are never consumed;
 //   2. row_start[v] = first sorted index whose key is >= v;
 //   3. each wave owns 16 consecutive sorted positions and every vocabulary row whose run starts among them: cotangent
 //      rows are loaded 16 at a time and added per example, phi is applied whenever the example changes, and the result
@@ -23,7 +23,7 @@
 namespace pex {
 namespace {
 
-constexpr int SORT_TILE = 2048;   // keys per workgroup of the sort: 256 threads x 8 rounds
+constexpr int SORT_MAX_BLOCKS = 64;   // workgroups of the sort; a workgroup's tile is a multiple of 2048 keys
 
 template <typename TId>
 __device__ __forceinline__ int load_key(const TId* __restrict__ ids, int p, int V)
@@ -32,120 +32,115 @@ __device__ __forceinline__ int load_key(const TId* __restrict__ ids, int p, int 
     return (v >= 0 && v < (int64_t)V) ? (int)v : V;
 }
 
-// hist[digit * nblocks + block] = number of keys of this block's tile of the pass's input whose digit (bits shift ..
-// shift+7) has that value.  The tiles of a later pass hold other keys than those of the first, so every pass counts
-// its own input.
+// Stable least-significant-digit radix sort, 8 bits per pass.  hist[block * 256 + digit] counts the keys of that
+// block's tile *of the pass's input* with that digit (the tiles of a later pass hold other keys than those of the
+// first, so every pass counts its own input; the counting is in LDS, where many equal keys cost little).
+// A tile is a multiple of 2048 keys: 8 rounds of 256 at a time, their loads issued together.
+constexpr int SORT_BATCH = 8;
+
 template <typename TId, bool FIRST>
 __global__ __launch_bounds__(256) void sort_hist_kernel(const TId* __restrict__ ids, const int* __restrict__ keys_in, int N, int V,
-                                                        int shift, int nblocks, int* __restrict__ hist)
+                                                        int shift, int tile, int* __restrict__ hist)
 {
     __shared__ int h[256];
     h[threadIdx.x] = 0;
     __syncthreads();
-    const int64_t base = (int64_t)blockIdx.x * SORT_TILE;
-    for (int r = 0; r < SORT_TILE / 256; ++r) {
-        const int64_t p = base + r * 256 + threadIdx.x;
-        if (p < N) {
-            const int key = FIRST ? load_key(ids, (int)p, V) : keys_in[p];
-            atomicAdd(&h[(key >> shift) & 255], 1);
+    const int64_t base = (int64_t)blockIdx.x * tile + threadIdx.x;
+    for (int r0 = 0; r0 < tile; r0 += 256 * SORT_BATCH) {
+        int key[SORT_BATCH];
+#pragma unroll
+        for (int j = 0; j < SORT_BATCH; ++j) {
+            const int64_t p = base + r0 + j * 256;
+            key[j] = p < N ? (FIRST ? load_key(ids, (int)p, V) : keys_in[p]) : -1;
         }
+#pragma unroll
+        for (int j = 0; j < SORT_BATCH; ++j)
+            if (key[j] >= 0) atomicAdd(&h[(key[j] >> shift) & 255], 1);
     }
     __syncthreads();
-    hist[(int64_t)threadIdx.x * nblocks + blockIdx.x] = h[threadIdx.x];
+    hist[(int64_t)blockIdx.x * 256 + threadIdx.x] = h[threadIdx.x];
 }
 
-// exclusive prefix sum, in place, of the `entries` counters (digit-major, block-minor: the order in which a stable
-// sort lays the keys out); one workgroup walks the array in tiles of 4096 counters, four per thread
-__global__ __launch_bounds__(1024) void sort_scan_kernel(int* __restrict__ h, int64_t entries)
+// One pass.  A key goes to (keys with a smaller digit) + (keys with the same digit in earlier tiles) + (its rank among
+// the keys of its tile with the same digit, in tile order): the first two from the counters (every workgroup adds
+// them up for itself: at most 64 tiles), the rank from 8 ballots per key.  FIRST reads the keys from the ids and uses
+// the position itself as the value.
+template <typename TId, bool FIRST>
+__global__ __launch_bounds__(256) void sort_scatter_kernel(const TId* __restrict__ ids, const int* __restrict__ keys_in,
+                                                           const int* __restrict__ vals_in, int* __restrict__ keys_out,
+                                                           int* __restrict__ vals_out, int N, int V, int shift, int tile, int nblocks,
+                                                           const int* __restrict__ hist)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    __shared__ int wsum[2][16];
-    int carry = 0;
-    int par = 0;
-    int nxt[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) nxt[e] = ((int64_t)threadIdx.x * 4 + e < entries) ? h[(int64_t)threadIdx.x * 4 + e] : 0;
-    for (int64_t t0 = 0; t0 < entries; t0 += 4096, par ^= 1) {
-        const int64_t i0 = t0 + (int64_t)threadIdx.x * 4;
-        int v[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            v[e] = nxt[e];
-            nxt[e] = (i0 + 4096 + e < entries) ? h[i0 + 4096 + e] : 0;   // the next tile's counters, in flight during this tile
+    __shared__ int base[256];
+    __shared__ int wcnt[4][256];
+    __shared__ int wtot[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    {
+        int before = 0, total = 0;   // this digit: in earlier tiles, in all tiles
+#pragma unroll 8
+        for (int b = 0; b < nblocks; ++b) {
+            const int c = hist[b * 256 + tid];
+            before += b < (int)blockIdx.x ? c : 0;
+            total += c;
         }
-        const int s = (v[0] + v[1]) + (v[2] + v[3]);
-        int incl = s;
+        int incl = total;
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
             const int t = __shfl_up(incl, o);
             if (lane >= o) incl += t;
         }
-        if (lane == 63) wsum[par][wave] = incl;
-        __syncthreads();   // the other half of wsum is still being read by slower waves of the previous tile
-        int run = carry + incl - s, total = 0;
-#pragma unroll
-        for (int w = 0; w < 16; ++w) {
-            const int t = wsum[par][w];
-            if (w < wave) run += t;
-            total += t;
-        }
-        carry += total;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            if (i0 + e < entries) h[i0 + e] = run;
-            run += v[e];
-        }
+        if (lane == 63) wtot[wave] = incl;
+        __syncthreads();
+        int smaller = incl - total;   // keys with a smaller digit
+        for (int w = 0; w < wave; ++w) smaller += wtot[w];
+        base[tid] = smaller + before;
     }
-}
-
-// One pass: key/value pairs go to offs[digit][block] + (rank of the pair among the pairs of its tile with the same
-// digit, in tile order).  FIRST reads the keys from the ids and uses the position itself as the value.
-template <typename TId, bool FIRST>
-__global__ __launch_bounds__(256) void sort_scatter_kernel(const TId* __restrict__ ids, const int* __restrict__ keys_in,
-                                                           const int* __restrict__ vals_in, int* __restrict__ keys_out,
-                                                           int* __restrict__ vals_out, int N, int V, int shift, int nblocks,
-                                                           const int* __restrict__ offs)
-{
-    __shared__ int base[256];
-    __shared__ int wcnt[4][256];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    base[tid] = offs[(int64_t)tid * nblocks + blockIdx.x];
 #pragma unroll
     for (int w = 0; w < 4; ++w) wcnt[w][tid] = 0;
     __syncthreads();
-    for (int r = 0; r < SORT_TILE / 256; ++r) {
-        const int64_t idx = (int64_t)blockIdx.x * SORT_TILE + r * 256 + tid;
-        const bool active = idx < N;
-        int key = 0, val = 0;
-        if (active) {
-            key = FIRST ? load_key(ids, (int)idx, V) : keys_in[idx];
-            val = FIRST ? (int)idx : vals_in[idx];
-        }
-        const int dg = (key >> shift) & 255;
-        // lanes of this wave that are active and hold the same digit
-        unsigned long long same = __ballot(active);
+    for (int r0 = 0; r0 < tile; r0 += 256 * SORT_BATCH) {
+        int keyb[SORT_BATCH], valb[SORT_BATCH];
 #pragma unroll
-        for (int bit = 0; bit < 8; ++bit) {
-            const bool one = (dg >> bit) & 1;
-            const unsigned long long bb = __ballot(one);
-            same &= one ? bb : ~bb;
-        }
-        const int rank = __popcll(same & ((1ull << lane) - 1ull));
-        if (active && rank == 0) wcnt[wave][dg] = __popcll(same);
-        __syncthreads();
-        if (active) {
-            int dest = base[dg] + rank;
-            for (int w = 0; w < wave; ++w) dest += wcnt[w][dg];
-            if (dest >= 0 && dest < N) {   // always true when the counts are those of this very input
-                keys_out[dest] = key;
-                vals_out[dest] = val;
+        for (int j = 0; j < SORT_BATCH; ++j) {
+            const int64_t idx = (int64_t)blockIdx.x * tile + r0 + j * 256 + tid;
+            keyb[j] = -1;
+            valb[j] = 0;
+            if (idx < N) {
+                keyb[j] = FIRST ? load_key(ids, (int)idx, V) : keys_in[idx];
+                valb[j] = FIRST ? (int)idx : vals_in[idx];
+                if (keyb[j] < 0) keyb[j] = V;   // keys are in [0, V]
             }
         }
-        __syncthreads();
-        base[tid] += (wcnt[0][tid] + wcnt[1][tid]) + (wcnt[2][tid] + wcnt[3][tid]);
 #pragma unroll
-        for (int w = 0; w < 4; ++w) wcnt[w][tid] = 0;
-        __syncthreads();
+        for (int j = 0; j < SORT_BATCH; ++j) {
+            const bool active = keyb[j] >= 0;
+            const int key = keyb[j], val = valb[j];
+            const int dg = (key >> shift) & 255;
+            // lanes of this wave that are active and hold the same digit
+            unsigned long long same = __ballot(active);
+#pragma unroll
+            for (int bit = 0; bit < 8; ++bit) {
+                const bool one = (dg >> bit) & 1;
+                const unsigned long long bb = __ballot(one);
+                same &= one ? bb : ~bb;
+            }
+            const int rank = __popcll(same & ((1ull << lane) - 1ull));
+            if (active && rank == 0) wcnt[wave][dg] = __popcll(same);
+            __syncthreads();
+            if (active) {
+                int dest = base[dg] + rank;
+                for (int w = 0; w < wave; ++w) dest += wcnt[w][dg];
+                if (dest >= 0 && dest < N) {   // always true when the counts are those of this very input
+                    keys_out[dest] = key;
+                    vals_out[dest] = val;
+                }
+            }
+            __syncthreads();
+            base[tid] += (wcnt[0][tid] + wcnt[1][tid]) + (wcnt[2][tid] + wcnt[3][tid]);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) wcnt[w][tid] = 0;
+            __syncthreads();
+        }
     }
 }
 
@@ -227,15 +222,22 @@ struct RowSums {
     }
 };
 
-// first index in [lo, hi) whose position is >= limit (positions ascend inside a row's run)
+// first index in [lo, hi) whose position is >= limit (positions ascend inside a row's run); the whole wave calls it
+// with the same arguments and looks at 64 positions per step -- an example rarely holds more of one token than that
 __device__ __forceinline__ int first_at_least(const int* __restrict__ pos, int lo, int hi, int limit)
 {
+    const int lane = threadIdx.x & 63;
     while (lo < hi) {
-        const int mid = lo + ((hi - lo) >> 1);
-        if (pos[mid] < limit) lo = mid + 1;
-        else hi = mid;
+        const int k = lo + lane;
+        const bool hit = k >= hi || pos[k] >= limit;
+        const unsigned long long m = __ballot(hit);
+        if (m) {
+            const int r = lo + (int)__builtin_ctzll(m);
+            return r < hi ? r : hi;
+        }
+        lo += 64;
     }
-    return lo;
+    return hi;
 }
 
 // Accumulates the cotangent rows of one vocabulary row, example by example: acc holds the running sum of the current
@@ -295,8 +297,8 @@ template <typename TIn, int CH, int WANT>
 __global__ __launch_bounds__(EMB_WAVES * 64) void embed_rows_kernel(const TIn* __restrict__ G, const int* __restrict__ row_start,
                                                                     const int* __restrict__ keys, const int* __restrict__ pos,
                                                                     int N, int V, int T, int64_t d, int chunk_groups,
-                                                                    float* __restrict__ S_id, float* __restrict__ S_sq,
-                                                                    float* __restrict__ S_sg)
+                                                                    float* __restrict__ partial, float* __restrict__ S_id,
+                                                                    float* __restrict__ S_sq, float* __restrict__ S_sg)
 {
     typedef Chunk<TIn, CH> Ck;
     const int lane = threadIdx.x & 63;
@@ -333,11 +335,9 @@ __global__ __launch_bounds__(EMB_WAVES * 64) void embed_rows_kernel(const TIn* _
         return;
     }
 
-    __shared__ int n_heavy;
-    __shared__ int heavy_row[EMB_WAVES];
+    __shared__ int heavy_row[EMB_WAVES];   // the long run that starts among wave i's positions, or -1
     __shared__ float comb[3][64 * CH];
-    if (threadIdx.x == 0) n_heavy = 0;
-    __syncthreads();
+    if (lane == 0) heavy_row[wave] = -1;
 
     RowAccumulator<TIn, CH, WANT> ra;
     ra.start(T);
@@ -359,10 +359,7 @@ __global__ __launch_bounds__(EMB_WAVES * 64) void embed_rows_kernel(const TIn* _
             re = re > N ? N : re;
             const bool ours = valid && key < V && rs >= c0 && rs < c1;
             const bool is_heavy = re - rs > EMB_ALONE;
-            if (ours && is_heavy && k == rs) {
-                const int slot = atomicAdd(&n_heavy, 1);   // at most one such run can start among EMB_U positions
-                if (slot < EMB_WAVES) heavy_row[slot] = key;
-            }
+            if (ours && is_heavy && k == rs) heavy_row[wave] = key;   // at most one such run can start among EMB_U positions
             const int p_ld = (ours && !is_heavy && p >= 0 && p < N) ? p : -1;
             int pu[EMB_U], ku[EMB_U], eu[EMB_U];
             typename Ck::Raw data[EMB_U];
@@ -393,21 +390,41 @@ __global__ __launch_bounds__(EMB_WAVES * 64) void embed_rows_kernel(const TIn* _
         if (cur_v >= 0) { ra.finish(); store_row(cur_v, ra.sums); }
     }
     __syncthreads();
-    const int nh = n_heavy < EMB_WAVES ? n_heavy : EMB_WAVES;
-    for (int h = 0; h < nh; ++h) {
-        const int hv = heavy_row[h];
+    // Long runs: this workgroup does, of every long run that overlaps its EMB_WAVES * EMB_U positions [sc0, sc1), the
+    // examples that start there -- candidate -1 is the run that continues from the positions before sc0, candidate i the
+    // run that starts among wave i's positions.  A run that lies inside [sc0, sc1) is finished here; of any other the
+    // sums go to `partial` (slot 0: continues from before, slot 1: starts here and goes on) for embed_combine_kernel.
+    const int64_t sc0l = (int64_t)blockIdx.x * (EMB_WAVES * EMB_U);
+    const int sc0 = sc0l < N ? (int)sc0l : N;
+    const int sc1 = sc0 + EMB_WAVES * EMB_U < N ? sc0 + EMB_WAVES * EMB_U : N;
+    for (int c = -1; c < EMB_WAVES; ++c) {
+        int hv = -1;
+        if (c >= 0) hv = heavy_row[c];
+        else if (sc0 > 0 && sc0 < N) {
+            const int key = keys[sc0];
+            if (key >= 0 && key < V && row_start[key] < sc0 && row_start[key + 1] - row_start[key] > EMB_ALONE) hv = key;
+        }
+        if (hv < 0 || hv >= V) continue;   // the same for every wave of the workgroup
         int hs = row_start[hv], he = row_start[hv + 1];
         hs = hs < 0 ? 0 : (hs > N ? N : hs);
         he = he < hs ? hs : (he > N ? N : he);
-        // wave i takes the run of whole examples that starts at bound(i): an even split of the positions, moved
-        // forward to the next change of example
-        auto bound = [&](int i) {
-            if (i <= 0) return hs;
-            if (i >= EMB_WAVES) return he;
-            const int k = hs + (int)(((int64_t)(he - hs) * i) / EMB_WAVES);
-            if (k <= hs) return hs;
+        // first position at or after k (hs < k < he) that begins an example
+        auto example_start = [&](int k) {
             const int limit = (pos[k - 1] / T + 1) * T;
             return first_at_least(pos, k, he, limit);
+        };
+        const bool from_before = hs < sc0, goes_on = he > sc1;
+        const int plo = from_before ? example_start(sc0) : hs;
+        const int phi = goes_on ? example_start(sc1) : he;
+        // wave i takes the examples that start in [bound(i), bound(i + 1)): an even split of the positions, moved
+        // forward to the next change of example
+        auto bound = [&](int i) {
+            if (i <= 0 || phi <= plo) return plo;
+            if (i >= EMB_WAVES) return phi;
+            const int k = plo + (int)(((int64_t)(phi - plo) * i) / EMB_WAVES);
+            if (k <= plo) return plo;
+            const int b2 = example_start(k);
+            return b2 < phi ? b2 : phi;
         };
         const int lo = bound(wave), hi = bound(wave + 1);
         ra.start(T);
@@ -443,27 +460,71 @@ __global__ __launch_bounds__(EMB_WAVES * 64) void embed_rows_kernel(const TIn* _
                 const int o = lane * CH + e2;
                 ra.sums.id[e2] = comb[0][o]; ra.sums.sq[e2] = comb[1][o]; ra.sums.sg[e2] = comb[2][o];
             }
-            store_row(hv, ra.sums);
+            if (!from_before && !goes_on) store_row(hv, ra.sums);
+            else if (col_ok) {
+                float* pr = partial + (((int64_t)blockIdx.x * 2 + (from_before ? 0 : 1)) * 3) * d + col;
+                if (WANT & 1) store_chunk<CH>(pr, ra.sums.id);
+                if (WANT & 2) store_chunk<CH>(pr + d, ra.sums.sq);
+                if (WANT & 4) store_chunk<CH>(pr + 2 * d, ra.sums.sg);
+            }
         }
         __syncthreads();
     }
 }
 
+// Finishes the long runs that span several workgroups of embed_rows_kernel: the workgroup-sized slice s in which such a
+// run starts adds up the partial sums of the slices the run covers, in slice order, and stores the row.
+// grid = (slices, column blocks), one wave each.
+template <int CH, int WANT>
+__global__ __launch_bounds__(64) void embed_combine_kernel(const int* __restrict__ row_start, const int* __restrict__ keys, int N, int V,
+                                                           int64_t d, const float* __restrict__ partial, float* __restrict__ S_id,
+                                                           float* __restrict__ S_sq, float* __restrict__ S_sg)
+{
+    constexpr int SLICE = EMB_WAVES * EMB_U;
+    const int64_t sc0 = (int64_t)blockIdx.x * SLICE, sc1 = sc0 + SLICE;
+    if (sc1 >= N) return;   // nothing goes on past the last slice
+    const int key = keys[sc1 - 1];
+    if (key < 0 || key >= V) return;
+    const int rs = row_start[key], re = row_start[key + 1];
+    if (!(rs >= sc0 && re > sc1 && re <= N && re - rs > EMB_ALONE)) return;
+    const int64_t col = ((int64_t)blockIdx.y * 64 + threadIdx.x) * CH;
+    if (col >= d) return;
+    float sum[3][CH];
+    auto take = [&](int64_t slice, int slot, bool first) {
+        const float* pr = partial + ((slice * 2 + slot) * 3) * d + col;
+#pragma unroll
+        for (int o = 0; o < 3; ++o) {
+            if (!(WANT & (1 << o))) continue;
+#pragma unroll
+            for (int e = 0; e < CH; ++e) sum[o][e] = first ? pr[o * d + e] : sum[o][e] + pr[o * d + e];
+        }
+    };
+    take(blockIdx.x, 1, true);
+    for (int64_t sl = (int64_t)blockIdx.x + 1; sl * SLICE < re; ++sl) take(sl, 0, false);
+    const int64_t o = (int64_t)key * d + col;
+    if (WANT & 1) store_chunk<CH>(S_id + o, sum[0]);
+    if (WANT & 2) store_chunk<CH>(S_sq + o, sum[1]);
+    if (WANT & 4) store_chunk<CH>(S_sg + o, sum[2]);
+}
+
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct EmbedLayout {
-    int passes, nblocks;
-    size_t hist, keys_a, vals_a, keys_b, vals_b, row_start, total;   // byte offsets into the workspace
+    int passes, tile, nblocks;
+    size_t hist, keys_a, vals_a, keys_b, vals_b, row_start, partial, total;   // byte offsets into the workspace
 };
 
-EmbedLayout embed_layout(int64_t N, int64_t V)
+EmbedLayout embed_layout(int64_t N, int64_t V, int64_t d)
 {
     EmbedLayout L;
     int bits = 0;
     while (((int64_t)1 << bits) <= V) ++bits;   // the largest key is V
     L.passes = (bits + 7) / 8;
     if (L.passes < 1) L.passes = 1;
-    L.nblocks = (int)((N + SORT_TILE - 1) / SORT_TILE);
+    int64_t tile = (N + SORT_MAX_BLOCKS - 1) / SORT_MAX_BLOCKS;
+    tile = (tile + 2047) / 2048 * 2048;
+    L.tile = (int)tile;
+    L.nblocks = (int)((N + tile - 1) / tile);
     size_t o = 0;
     L.hist = o; o += align256((size_t)256 * L.nblocks * sizeof(int));
     L.keys_a = o; o += align256((size_t)N * sizeof(int));
@@ -471,6 +532,9 @@ EmbedLayout embed_layout(int64_t N, int64_t V)
     L.keys_b = o; o += align256((size_t)N * sizeof(int));
     L.vals_b = o; o += align256((size_t)N * sizeof(int));
     L.row_start = o; o += align256((size_t)(V + 2) * sizeof(int));
+    // two partial sums of three statistics per slice of EMB_WAVES * EMB_U positions, for runs that cross slices
+    const int64_t slices = (N + EMB_WAVES * EMB_U - 1) / (EMB_WAVES * EMB_U);
+    L.partial = o; o += align256((size_t)slices * 2 * 3 * d * sizeof(float));
     L.total = o;
     return L;
 }
@@ -484,18 +548,19 @@ hipError_t sort_positions(const TId* ids, int N, int V, const EmbedLayout& L, ch
     int* va = (int*)(ws + L.vals_a);
     int* kb = (int*)(ws + L.keys_b);
     int* vb = (int*)(ws + L.vals_b);
-    const int64_t entries = (int64_t)256 * L.nblocks;
     const dim3 grid(L.nblocks), block(256);
     const int* kin = nullptr;
     const int* vin = nullptr;
     int* kout = ka;
     int* vout = va;
     for (int ps = 0; ps < L.passes; ++ps) {
-        if (ps == 0) sort_hist_kernel<TId, true><<<grid, block, 0, stream>>>(ids, nullptr, N, V, 0, L.nblocks, hist);
-        else sort_hist_kernel<TId, false><<<grid, block, 0, stream>>>(ids, kin, N, V, 8 * ps, L.nblocks, hist);
-        sort_scan_kernel<<<dim3(1), dim3(1024), 0, stream>>>(hist, entries);
-        if (ps == 0) sort_scatter_kernel<TId, true><<<grid, block, 0, stream>>>(ids, nullptr, nullptr, kout, vout, N, V, 0, L.nblocks, hist);
-        else sort_scatter_kernel<TId, false><<<grid, block, 0, stream>>>(ids, kin, vin, kout, vout, N, V, 8 * ps, L.nblocks, hist);
+        if (ps == 0) {
+            sort_hist_kernel<TId, true><<<grid, block, 0, stream>>>(ids, nullptr, N, V, 0, L.tile, hist);
+            sort_scatter_kernel<TId, true><<<grid, block, 0, stream>>>(ids, nullptr, nullptr, kout, vout, N, V, 0, L.tile, L.nblocks, hist);
+        } else {
+            sort_hist_kernel<TId, false><<<grid, block, 0, stream>>>(ids, kin, N, V, 8 * ps, L.tile, hist);
+            sort_scatter_kernel<TId, false><<<grid, block, 0, stream>>>(ids, kin, vin, kout, vout, N, V, 8 * ps, L.tile, L.nblocks, hist);
+        }
         kin = kout; vin = vout;
         kout = (kout == ka) ? kb : ka;
         vout = (vout == va) ? vb : va;
@@ -507,42 +572,46 @@ hipError_t sort_positions(const TId* ids, int N, int V, const EmbedLayout& L, ch
 
 template <typename TIn, int CH, int WANT>
 hipError_t launch_rows(const TIn* G, const int* row_start, const int* keys, const int* pos, int N, int V, int T, int64_t d,
-                       float* S_id, float* S_sq, float* S_sg, hipStream_t stream)
+                       float* partial, float* S_id, float* S_sq, float* S_sg, hipStream_t stream)
 {
     const int64_t per_group = (int64_t)EMB_WAVES * EMB_U;
     const int chunk_groups = (int)((N + per_group - 1) / per_group);
     const int zero_groups = (int)(((int64_t)V + EMB_WAVES * EMB_ZROWS - 1) / (EMB_WAVES * EMB_ZROWS));
-    const dim3 grid((unsigned)(chunk_groups + zero_groups), (unsigned)((d + 64 * CH - 1) / (64 * CH)));
-    embed_rows_kernel<TIn, CH, WANT><<<grid, dim3(EMB_WAVES * 64), 0, stream>>>(G, row_start, keys, pos, N, V, T, d, chunk_groups,
-                                                                                  S_id, S_sq, S_sg);
+    const unsigned colblocks = (unsigned)((d + 64 * CH - 1) / (64 * CH));
+    embed_rows_kernel<TIn, CH, WANT><<<dim3((unsigned)(chunk_groups + zero_groups), colblocks), dim3(EMB_WAVES * 64), 0, stream>>>(
+        G, row_start, keys, pos, N, V, T, d, chunk_groups, partial, S_id, S_sq, S_sg);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    embed_combine_kernel<CH, WANT><<<dim3((unsigned)chunk_groups, colblocks), dim3(64), 0, stream>>>(row_start, keys, N, V, d, partial,
+                                                                                                   S_id, S_sq, S_sg);
     return hipGetLastError();
 }
 
 template <typename TIn, int CH>
-hipError_t launch_rows_want(uint32_t want, const TIn* G, const int* rs, const int* keys, const int* pos, int N, int V, int T, int64_t d, float* a,
+hipError_t launch_rows_want(uint32_t want, const TIn* G, const int* rs, const int* keys, const int* pos, int N, int V, int T, int64_t d, float* pr, float* a,
                             float* q, float* g, hipStream_t st)
 {
     switch (want) {
-    case 1: return launch_rows<TIn, CH, 1>(G, rs, keys, pos, N, V, T, d, a, q, g, st);
-    case 2: return launch_rows<TIn, CH, 2>(G, rs, keys, pos, N, V, T, d, a, q, g, st);
-    case 3: return launch_rows<TIn, CH, 3>(G, rs, keys, pos, N, V, T, d, a, q, g, st);
-    case 4: return launch_rows<TIn, CH, 4>(G, rs, keys, pos, N, V, T, d, a, q, g, st);
-    case 5: return launch_rows<TIn, CH, 5>(G, rs, keys, pos, N, V, T, d, a, q, g, st);
-    case 6: return launch_rows<TIn, CH, 6>(G, rs, keys, pos, N, V, T, d, a, q, g, st);
-    default: return launch_rows<TIn, CH, 7>(G, rs, keys, pos, N, V, T, d, a, q, g, st);
+    case 1: return launch_rows<TIn, CH, 1>(G, rs, keys, pos, N, V, T, d, pr, a, q, g, st);
+    case 2: return launch_rows<TIn, CH, 2>(G, rs, keys, pos, N, V, T, d, pr, a, q, g, st);
+    case 3: return launch_rows<TIn, CH, 3>(G, rs, keys, pos, N, V, T, d, pr, a, q, g, st);
+    case 4: return launch_rows<TIn, CH, 4>(G, rs, keys, pos, N, V, T, d, pr, a, q, g, st);
+    case 5: return launch_rows<TIn, CH, 5>(G, rs, keys, pos, N, V, T, d, pr, a, q, g, st);
+    case 6: return launch_rows<TIn, CH, 6>(G, rs, keys, pos, N, V, T, d, pr, a, q, g, st);
+    default: return launch_rows<TIn, CH, 7>(G, rs, keys, pos, N, V, T, d, pr, a, q, g, st);
     }
 }
 
 }  // namespace
 
-size_t embed_workspace(int64_t B, int64_t T, int64_t V) { return embed_layout(B * T, V).total; }
+size_t embed_workspace(int64_t B, int64_t T, int64_t V, int64_t d) { return embed_layout(B * T, V, d).total; }
 
 hipError_t launch_embed_stat(const void* ids, int ids_bytes, const void* G, int64_t B, int64_t T, int64_t V, int64_t d,
                              pex_dtype dt, uint32_t want, float* S_id, float* S_sq, float* S_sign, void* workspace,
                              hipStream_t stream)
 {
     const int N = (int)(B * T);
-    const EmbedLayout L = embed_layout(N, V);
+    const EmbedLayout L = embed_layout(N, V, d);
     char* ws = (char*)workspace;
     const int* keys = nullptr;
     const int* pos = nullptr;
@@ -550,15 +619,16 @@ hipError_t launch_embed_stat(const void* ids, int ids_bytes, const void* G, int6
                                   : sort_positions<int32_t>((const int32_t*)ids, N, (int)V, L, ws, &keys, &pos, stream);
     if (e != hipSuccess) return e;
     int* row_start = (int*)(ws + L.row_start);
+    float* partial = (float*)(ws + L.partial);
     row_start_kernel<<<dim3((unsigned)(((int64_t)N + 1 + 255) / 256)), dim3(256), 0, stream>>>(keys, N, (int)V, row_start);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (dt == PEX_BF16) {
-        if (d % 4 == 0) return launch_rows_want<uint16_t, 4>(want, (const uint16_t*)G, row_start, keys, pos, N, (int)V, (int)T, d, S_id, S_sq, S_sign, stream);
-        return launch_rows_want<uint16_t, 1>(want, (const uint16_t*)G, row_start, keys, pos, N, (int)V, (int)T, d, S_id, S_sq, S_sign, stream);
+        if (d % 4 == 0) return launch_rows_want<uint16_t, 4>(want, (const uint16_t*)G, row_start, keys, pos, N, (int)V, (int)T, d, partial, S_id, S_sq, S_sign, stream);
+        return launch_rows_want<uint16_t, 1>(want, (const uint16_t*)G, row_start, keys, pos, N, (int)V, (int)T, d, partial, S_id, S_sq, S_sign, stream);
     }
-    if (d % 4 == 0) return launch_rows_want<float, 4>(want, (const float*)G, row_start, keys, pos, N, (int)V, (int)T, d, S_id, S_sq, S_sign, stream);
-    return launch_rows_want<float, 1>(want, (const float*)G, row_start, keys, pos, N, (int)V, (int)T, d, S_id, S_sq, S_sign, stream);
+    if (d % 4 == 0) return launch_rows_want<float, 4>(want, (const float*)G, row_start, keys, pos, N, (int)V, (int)T, d, partial, S_id, S_sq, S_sign, stream);
+    return launch_rows_want<float, 1>(want, (const float*)G, row_start, keys, pos, N, (int)V, (int)T, d, partial, S_id, S_sq, S_sign, stream);
 }
 
 }  // namespace pex

@@ -86,7 +86,7 @@ size_t moment_track_workspace(int64_t n);
 hipError_t launch_moment_track(float* ema_adam, float* ema_micro, const float* S_id, const float* S_sq, int64_t n,
                                const pex_moment_params& p, double* sums, double* partial, hipStream_t stream);
 
-size_t embed_workspace(int64_t B, int64_t T, int64_t V);
+size_t embed_workspace(int64_t B, int64_t T, int64_t V, int64_t d);
 hipError_t launch_embed_stat(const void* ids, int ids_bytes, const void* G, int64_t B, int64_t T, int64_t V, int64_t d,
                              pex_dtype dt, uint32_t want, float* S_id, float* S_sq, float* S_sign, void* workspace,
                              hipStream_t stream);

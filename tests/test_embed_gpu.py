@@ -21,6 +21,7 @@ CASES = [
     (7, 129, 257, 1032, "bf16", torch.int32, 1.2, 0.0),   # ragged last column block, mix of light and heavy rows
     (1, 1, 1, 1, "f32", torch.int64, 1.0, 0.0),
     (9, 1030, 2, 8, "bf16", torch.int64, 0.0, 0.0),       # more than one sort tile per example, two tokens only
+    (3, 50000, 1000, 8, "bf16", torch.int32, 1.0, 0.02),  # more positions than 64 tiles of 2048: larger sort tiles
 ]
 
 

@@ -70,6 +70,10 @@ def main() -> int:
     ap.add_argument("--copy-calibration", action="store_true",
                     help="before the timed region, copy 1 GiB device to device once: a kernel of known traffic "
                          "against which the FETCH_SIZE / WRITE_SIZE counters of a profiling run are scaled")
+    ap.add_argument("--extras", action="store_true",
+                    help="after the timed region also time, per launch, the entry points outside the headline step "
+                         "(vector parameters, norms, weighted sums, power, embedding table, moment tracking) on the "
+                         "first layer's shapes; reported under \"extras\", not part of `value`")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (per-example statistics shard over the batch axis, "
@@ -183,6 +187,62 @@ def main() -> int:
         torch.cuda.synchronize()
         multi_ms = (time.perf_counter() - m0) / args.steps * 1e3
 
+    # ---- for information: the other entry points, one at a time, on the first layer's shapes
+    extras = None
+    if args.extras:
+        L = layers[0]
+        w = L["w"]
+        X, G = L["X"], L["G"]
+        flop = 2.0 * w.B * w.T * w.din * w.dout
+        n = w.din * w.dout
+        V = 32000                                  # vocabulary of the 1.2B model's tokenizer class; embedding width = din
+        ids = si.token_ids(w.B, w.T, V, seed=args.seed).to(dev)
+        Ge = X                                     # cotangents of the looked-up vectors: [B, T, din] bf16
+        wts = torch.linspace(0.25, 1.0, w.B, device=dev)
+        ema_a, ema_q = torch.zeros(n, device=dev), torch.zeros(n, device=dev)
+        mp = pex.MomentParams(beta2=0.95, grad_scale=1.0 / w.B, sq_scale=1.0 / w.B, B=w.B, debias=1, step=1)
+        emb_out = {k: torch.empty(V, w.din, device=dev) for k in ("identity", "square")}
+        el = 2                                     # bytes per bf16 element
+
+        def timed(fn, reps=5):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / reps
+
+        def entry(ms, flops=None, nbytes=None):
+            e = {"ms": round(ms, 4)}
+            if flops is not None:
+                e["TFLOP/s"] = round(flops / (ms * 1e-3) / 1e12, 1)
+            if nbytes is not None:
+                e["GB/s"] = round(nbytes / (ms * 1e-3) / 1e9, 1)
+            return e
+
+        extras = {"shapes": {"B": w.B, "T": w.T, "din": w.din, "dout": w.dout, "V": V}}
+        extras["pex_stat_multi(identity,square)"] = entry(timed(lambda: pex.pex_stat_multi(X, G, ("identity", "square"))), flops=flop)
+        extras["pex_stat_multi(identity,square,sign)"] = entry(timed(lambda: pex.pex_stat_multi(X, G, ("identity", "square", "sign"))), flops=flop)
+        extras["pex_example_norms"] = entry(timed(lambda: pex.pex_example_norms(X, G)), flops=flop)
+        extras["pex_weighted_sum"] = entry(timed(lambda: pex.pex_weighted_sum(X, G, wts)), flops=flop)
+        extras["pex_stat_power(alpha=1.5)"] = entry(timed(lambda: pex.pex_stat_power(X, G, 1.5)), flops=flop)
+        extras["pex_token_norms"] = entry(timed(lambda: pex.pex_token_norms(X, G)), nbytes=w.B * w.T * (w.din + w.dout) * el)
+        extras["pex_vec_stat(offset of dout)"] = entry(timed(lambda: pex.pex_vec_stat(G, None, ("identity", "square", "sign"))),
+                                                       nbytes=w.B * w.T * w.dout * el)
+        extras["pex_embed_stat(identity,square)"] = entry(
+            timed(lambda: pex.pex_embed_stat(ids, Ge, V, ("identity", "square"), out=emb_out)),
+            nbytes=w.B * w.T * w.din * el + 2 * V * w.din * 4 + w.B * w.T * 8)
+        extras["pex_moment_track"] = entry(timed(lambda: pex.pex_moment_track(ema_a, ema_q, L["S_id"].view(-1), L["S_sq"].view(-1), mp)),
+                                           nbytes=24.0 * n)
+        extras["pex_sign_update(signema)"] = entry(
+            timed(lambda: pex.pex_sign_update(L["theta_s"], L["m_s"], L["S_id"].view(-1), "signema", 3.47e-3, 0.9, 0.0, w.B)),
+            nbytes=20.0 * n)
+        del ids, emb_out, ema_a, ema_q
+
     flop_per_stat = [2.0 * L["w"].B * L["w"].T * L["w"].din * L["w"].dout for L in layers]
     flop_per_step = 4.0 * sum(flop_per_stat)          # identity, square, sign, per-token square
     ms_per_step = elapsed / args.steps * 1e3
@@ -251,6 +311,8 @@ def main() -> int:
                                     "note": "same outputs with identity, square and sign from one contraction per layer "
                                             "(pex_stat_multi); informational, not used in value"},
     }
+    if extras is not None:
+        out["extras"] = extras
     print(json.dumps(out, ensure_ascii=False))
     return 0
 

@@ -228,3 +228,32 @@ def test_token_square_through_presquared_copies_is_the_same_bits(monkeypatch):
     assert torch.equal(fused, copies)
     tok = oracle.token_sq(si.widen(X), si.widen(G))
     assert_real_stat(copies.cpu().double().numpy(), tok, "bf16", "token_sq copies", elementwise=True, bar=TOKEN_SQ_BF16_BAR, eng=None)
+
+
+def _random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for k in range(n):
+        B = int(rng.integers(1, 41))
+        T = int(rng.integers(1, 301))
+        if k % 3 == 2:      # any widths: the SIMT kernel (or fp32 inputs)
+            din, dout = int(rng.integers(1, 400)), int(rng.integers(1, 400))
+            dtype = "f32" if k % 2 else "bf16"
+        else:               # multiples of 8 from 32 up: the MFMA kernel, tile edges anywhere
+            din, dout = 8 * int(rng.integers(4, 90)), 8 * int(rng.integers(4, 90))
+            dtype = "bf16"
+        out.append((B, T, din, dout, dtype))
+    return out
+
+
+@pytest.mark.parametrize("B,T,din,dout,dtype", _random_shapes(24, seed=2510))
+def test_seeded_sweep_of_shapes(B, T, din, dout, dtype):
+    """Shapes drawn once from a fixed seed: tile edges, slab tails and batch splits fall where nobody chose them.
+    Every statistic through its own call, then identity, square and sign again from one shared contraction."""
+    X, G = si.custom(B, T, din, dout, dtype=dtype, seed=B + 41 * T + din)
+    got, st = _compare(X, G, dtype, f"B{B} T{T} {din}x{dout} {dtype}", elementwise=(B >= 3))
+    multi = pex.pex_stat_multi(X.to(DEV), G.to(DEV), ("identity", "square", "sign"))
+    f = lambda t: t.cpu().numpy().astype(np.float64)
+    assert_real_stat(f(multi["identity"]), st.S_id, dtype, "shared identity", elementwise=False)
+    assert_real_stat(f(multi["square"]), st.S_sq, dtype, "shared square", elementwise=(B >= 3))
+    assert_sign_stat(f(multi["sign"]), st.S_sign, st.amb, "shared sign")

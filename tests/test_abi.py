@@ -141,7 +141,7 @@ def test_host_validation_launches_nothing():
 
     mp = pex.MomentParams(beta2=0.95, grad_scale=0.25, sq_scale=0.25, B=4, debias=1, step=1)
     wsb = pex.pex_moment_track_workspace_bytes(16)
-    assert 0 < wsb <= 1 << 16 and pex.pex_moment_track_workspace_bytes(1 << 30) <= 1 << 16
+    assert 0 < wsb <= 1 << 17 and pex.pex_moment_track_workspace_bytes(1 << 30) <= 1 << 17
     sums, ws = 0x6000, 0x7000
     assert L.pex_moment_track(m, v, a, q, 16, ctypes.byref(mp), None, ws, wsb, None) == 1
     assert L.pex_moment_track(m, v, a, q, 16, None, sums, ws, wsb, None) == 1

@@ -187,6 +187,25 @@ def main() -> int:
         torch.cuda.synchronize()
         multi_ms = (time.perf_counter() - m0) / args.steps * 1e3
 
+    # ---- what the MFMA pipes sustain with nothing else going on (same register shape, Gaussian operands like X):
+    # the contraction kernels are reported against this measured ceiling beside the datasheet peak
+    n_cu = torch.cuda.get_device_properties(dev).multi_processor_count
+    probe_ops = torch.randn(pex.lib().pex_mfma_probe_operand_bytes() // 2, device=dev).to(torch.bfloat16)
+    probe_iters = 3000
+    _, probe_sink = pex.pex_mfma_probe(probe_ops, n_cu, probe_iters)
+    for _ in range(3):
+        pex.pex_mfma_probe(probe_ops, n_cu, probe_iters, sink=probe_sink)
+    torch.cuda.synchronize()
+    p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    probe_reps = 10
+    p0.record()
+    for _ in range(probe_reps):
+        probe_flop, _ = pex.pex_mfma_probe(probe_ops, n_cu, probe_iters, sink=probe_sink)
+    p1.record()
+    torch.cuda.synchronize()
+    probe_ms = p0.elapsed_time(p1) / probe_reps
+    ceiling = probe_flop / (probe_ms * 1e-3) / 1e12
+
     # ---- for information: the other entry points, one at a time, on the first layer's shapes
     extras = None
     if args.extras:
@@ -255,7 +274,8 @@ def main() -> int:
         avg_ms = sum(ms) / len(ms)
         achieved = (sum(flop) / len(flop)) / (avg_ms * 1e-3) / 1e12
         return {"bound": "mfma", "kernel": kernel, "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "avg_launch_ms": round(avg_ms, 4),
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                "frac_of_measured_mfma_ceiling": round(achieved / ceiling, 4), "avg_launch_ms": round(avg_ms, 4),
                 "launches": len(ms), "traffic": measured_traffic(args.workload, which)}
 
     roofline = contraction_roofline(id_events, "stat_bf16_kernel<256x256 tile, identity> (pex_stat phi=identity; also "
@@ -306,6 +326,9 @@ def main() -> int:
                    "step": "per layer: pex_stat identity+square -> MicroAdam update; pex_stat sign -> MicroSignSGD update; pex_token_sq",
                    "flop_per_step": flop_per_step, "seed": args.seed},
         "roofline": roofline, "square_roofline": square_roofline, "update_roofline": update_roofline,
+        "mfma_only_ceiling": {"achieved": round(ceiling, 1), "unit": "TFLOP/s", "frac_of_peak": round(ceiling / PEAK_BF16_TFLOPS, 4),
+                              "kernel": "mfma_probe_kernel: nothing but v_mfma_f32_32x32x16_bf16, 8 waves on each of "
+                                        f"{n_cu} compute units, Gaussian operands", "launch_ms": round(probe_ms, 4)},
         "cpu_baseline": cpu,
         "shared_contraction_step": None if multi_ms is None else {"ms_per_step": round(multi_ms, 4),
                                     "note": "same outputs with identity, square and sign from one contraction per layer "

@@ -35,7 +35,8 @@ EXPORTS = ("pex_status_string", "pex_version", "pex_stat_workspace_bytes", "pex_
            "pex_weighted_sum", "pex_token_norms", "pex_sign_update",
            "pex_stat_power_workspace_bytes", "pex_stat_power",
            "pex_token_sq_workspace_bytes", "pex_token_sq", "pex_adam_update", "pex_signsgd_update",
-           "pex_moment_track_workspace_bytes", "pex_moment_track", "pex_embed_stat_workspace_bytes", "pex_embed_stat")
+           "pex_moment_track_workspace_bytes", "pex_moment_track", "pex_embed_stat_workspace_bytes", "pex_embed_stat",
+           "pex_mfma_probe_operand_bytes", "pex_mfma_probe_sink_floats", "pex_mfma_probe")
 
 
 class PexError(RuntimeError):
@@ -115,6 +116,11 @@ def lib() -> ctypes.CDLL:
         L.pex_embed_stat_workspace_bytes.restype = sz
         L.pex_embed_stat.argtypes = [p, i32, p, i64, i64, i64, i64, ctypes.c_int, ctypes.c_uint32, p, p, p, p, sz, p]
         L.pex_embed_stat.restype = ctypes.c_int
+        L.pex_mfma_probe_operand_bytes.restype = sz
+        L.pex_mfma_probe_sink_floats.argtypes = [i32]
+        L.pex_mfma_probe_sink_floats.restype = sz
+        L.pex_mfma_probe.argtypes = [p, i32, i32, p, ctypes.POINTER(ctypes.c_double), p]
+        L.pex_mfma_probe.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -404,3 +410,18 @@ def pex_embed_stat(ids, G, V, want, out=None, workspace=None, stream=None):
     _check(lib().pex_embed_stat(_dev(ids, "ids"), ids.element_size(), _dev(G, "G"), B, T, V, d, _dtype_code(G), mask,
                                 ptrs[0], ptrs[1], ptrs[2], wptr, wbytes, _stream(stream)))
     return res
+
+
+def pex_mfma_probe(operands, workgroups, iters, sink=None, stream=None):
+    """Measurement aid: one launch of nothing but bf16 MFMAs (see ``pex_mfma_probe`` in the header).  ``operands`` is a
+    bf16 tensor of at least ``pex_mfma_probe_operand_bytes()`` bytes.  Returns (FLOP of the launch, sink tensor)."""
+    import torch
+    need = int(lib().pex_mfma_probe_operand_bytes())
+    if operands.numel() * operands.element_size() < need:
+        raise ValueError(f"operands must hold at least {need} bytes")
+    if sink is None:
+        sink = torch.empty(int(lib().pex_mfma_probe_sink_floats(workgroups)), dtype=torch.float32, device=operands.device)
+    flop = ctypes.c_double(0.0)
+    _check(lib().pex_mfma_probe(_dev(operands, "operands"), int(workgroups), int(iters), _dev(sink, "sink"), ctypes.byref(flop),
+                                _stream(stream)))
+    return flop.value, sink

@@ -424,6 +424,18 @@ pex_status pex_embed_stat(const void* ids, int32_t ids_bytes, const void* G, int
                : PEX_ERR_HIP;
 }
 
+size_t pex_mfma_probe_operand_bytes(void) { return probe_operand_bytes(); }
+size_t pex_mfma_probe_sink_floats(int32_t workgroups) { return workgroups < 1 ? 0 : probe_sink_floats(workgroups); }
+
+pex_status pex_mfma_probe(const void* operands, int32_t workgroups, int32_t iters, float* sink, double* flop, pex_stream_t stream)
+{
+    if (!operands || !sink) return PEX_ERR_NULL;
+    if (workgroups < 1 || workgroups > 65536 || iters < 1 || iters > (1 << 24)) return PEX_ERR_SHAPE;
+    if (((uintptr_t)operands | (uintptr_t)sink) & 15u) return PEX_ERR_ALIGN;
+    if (flop) *flop = probe_flop(workgroups, iters);
+    return launch_mfma_probe(operands, workgroups, iters, sink, (hipStream_t)stream) == hipSuccess ? PEX_OK : PEX_ERR_HIP;
+}
+
 size_t pex_moment_track_workspace_bytes(int64_t n) { return n < 1 ? 0 : moment_track_workspace(n); }
 
 pex_status pex_moment_track(float* ema_adam, float* ema_micro, const float* S_id, const float* S_sq, int64_t n,

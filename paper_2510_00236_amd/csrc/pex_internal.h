@@ -91,4 +91,9 @@ hipError_t launch_embed_stat(const void* ids, int ids_bytes, const void* G, int6
                              pex_dtype dt, uint32_t want, float* S_id, float* S_sq, float* S_sign, void* workspace,
                              hipStream_t stream);
 
+size_t probe_operand_bytes();
+size_t probe_sink_floats(int workgroups);
+double probe_flop(int workgroups, int iters);
+hipError_t launch_mfma_probe(const void* operands, int workgroups, int iters, float* sink, hipStream_t stream);
+
 }  // namespace pex

@@ -257,3 +257,17 @@ def test_seeded_sweep_of_shapes(B, T, din, dout, dtype):
     assert_real_stat(f(multi["identity"]), st.S_id, dtype, "shared identity", elementwise=False)
     assert_real_stat(f(multi["square"]), st.S_sq, dtype, "shared square", elementwise=(B >= 3))
     assert_sign_stat(f(multi["sign"]), st.S_sign, st.amb, "shared sign")
+
+
+def test_mfma_probe_runs_and_counts_its_flop():
+    """The measurement aid: deterministic output, FLOP count = workgroups x 8 waves x iters x 16 MFMAs x 2*32*32*16."""
+    ops = torch.randn(pex.lib().pex_mfma_probe_operand_bytes() // 2, device=DEV).to(torch.bfloat16)
+    flop, s1 = pex.pex_mfma_probe(ops, 4, 10)
+    assert flop == 4 * 8 * 10 * 16 * 2 * 32 * 32 * 16
+    _, s2 = pex.pex_mfma_probe(ops, 4, 10)
+    torch.cuda.synchronize()
+    assert s1.shape == (4 * 512,) and torch.isfinite(s1).all() and torch.equal(s1, s2)
+    with pytest.raises(ValueError):
+        pex.pex_mfma_probe(ops[:100], 4, 10)
+    with pytest.raises(pex.PexError):
+        pex.pex_mfma_probe(ops, 0, 10)

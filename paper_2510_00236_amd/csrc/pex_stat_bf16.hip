@@ -6,8 +6,10 @@
 // B*T rows whose operands are squared on the way.
 //
 // Data path
-//   * One workgroup = 8 waves (two per SIMD) owns a BM x BN tile of S; a wave owns WM x WN of it as FM x FN MFMA
-//     32x32x16 accumulators.  phi = identity, sign and the per-token square use 256 x 256 tiles (128 x 64 per
+//   * One workgroup = 8 waves (two per SIMD) owns a BM x BN tile of S; a wave owns WM x WN of it as FM x FN
+//     accumulators of v_mfma_f32_16x16x32_bf16.  (Same FLOP per cycle as the 32x32x16 form and the same LDS reads per
+//     FLOP, but half the accumulator traffic; on this power-limited chip an MFMA-only loop sustains 2.02 PFLOP/s
+//     with it against 1.80 with 32x32x16 on Gaussian operands, and the contraction gained 7 %.)  phi = identity, sign and the per-token square use 256 x 256 tiles (128 x 64 per
 //     wave); phi = square needs a second fp32 register tile for the running sum and uses 256 x 128 (64 x 64 per
 //     wave); sign counts are integers of magnitude <= B and are kept as packed fp16 pairs while B <= 2048, which
 //     is what lets sign use the large tile.
@@ -65,7 +67,7 @@ constexpr int MAX_U8_EXAMPLES = 127;
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) short short4_t;
-typedef __attribute__((ext_vector_type(16))) float float16_t;
+typedef __attribute__((ext_vector_type(4))) float float4_t;
 typedef __attribute__((ext_vector_type(4))) int int4_t;
 typedef __attribute__((ext_vector_type(4))) unsigned int uint4_t;
 typedef __attribute__((ext_vector_type(2))) _Float16 half2_t;
@@ -132,15 +134,16 @@ __device__ __forceinline__ float abs_power(float m, float alpha)
     return __builtin_amdgcn_exp2f(alpha * __builtin_amdgcn_logf(__builtin_fabsf(m)));
 }
 
-// End of an example, one finished 32x32 tile of M_b: every requested statistic takes its phi(M_b), M_b restarts
-// from 0.  Sign counts of a tile as 8 fp16 pairs per lane: integers up to 2048 are exact in fp16, so the count of
-// at most 2048 examples is exact, at half the registers of an fp32 tile.
+// End of an example, one finished 16x16 tile of M_b (four registers per lane): every requested statistic takes its
+// phi(M_b), M_b restarts from 0.  Sign counts of a tile as 2 fp16 pairs per lane: integers up to 2048 are exact in
+// fp16, so the count of at most 2048 examples is exact, at half the registers of an fp32 tile; or as one register of
+// four biased byte counters.
 template <int OUTS>
-__device__ __forceinline__ void fold_tile(float16_t& acc, float16_t& acc_id, float16_t& acc_sq, float16_t& acc_sg, half2_t (&cnt)[8],
-                                          uint32_t (&cnt8)[4], float weight, float& norm)
+__device__ __forceinline__ void fold_tile(float4_t& acc, float4_t& acc_id, float4_t& acc_sq, float4_t& acc_sg, half2_t (&cnt)[2],
+                                          uint32_t& cnt8, float weight, float& norm)
 {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
+    for (int r = 0; r < 4; ++r) {
         const float m = acc[r];
         if (OUTS & OUT_ID) acc_id[r] += m;
         if (OUTS & OUT_IDW) acc_id[r] = fmaf(weight, m, acc_id[r]);
@@ -151,20 +154,17 @@ __device__ __forceinline__ void fold_tile(float16_t& acc, float16_t& acc_id, flo
     }
     if (OUTS & OUT_SIGN_PK) {
 #pragma unroll
-        for (int r = 0; r < 8; ++r)
+        for (int r = 0; r < 2; ++r)
             cnt[r] += __builtin_bit_cast(half2_t, __builtin_amdgcn_cvt_pkrtz(sign_as_float(acc[2 * r]), sign_as_float(acc[2 * r + 1])));
     }
     if (OUTS & OUT_SIGN_U8) {
+        uint32_t w = 0;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            uint32_t w = 0;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) w = __builtin_amdgcn_cvt_pk_u8_f32(sign_as_float(acc[4 * q + k]) + 1.0f, k, w);
-            cnt8[q] += w;
-        }
+        for (int k = 0; k < 4; ++k) w = __builtin_amdgcn_cvt_pk_u8_f32(sign_as_float(acc[k]) + 1.0f, k, w);
+        cnt8 += w;
     }
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    for (int r = 0; r < 4; ++r) acc[r] = 0.f;
 }
 
 // Workgroup id -> (split, tile_m, tile_n): undo the round-robin assignment of consecutive ids to the 8 XCDs,
@@ -194,7 +194,7 @@ __device__ __forceinline__ void map_workgroup(int tiles_m, int tiles_n, int& spl
 template <int BM_, int BN_, int WM_, int WN_, int BK_, int NS_, int RC_>
 struct Bf16Tile {
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, BK = BK_, NS = NS_;
-    static constexpr int FM = WM / 32, FN = WN / 32, KS = BK / 16;
+    static constexpr int FM = WM / 16, FN = WN / 16, KS = BK / 32;
     static constexpr int FPK = FM + FN;                                // fragments per k-step
     static constexpr int RC = RC_ < FPK ? RC_ : FPK;
     static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN, NWAVES = WAVES_M * WAVES_N, NT = NWAVES * 64;
@@ -206,10 +206,10 @@ struct Bf16Tile {
     static constexpr int RX = 1024 / XROW, RG = 1024 / GROW;           // slab rows covered by one load
     static_assert(NWAVES == 8, "eight waves per workgroup: two groups of four");
     static_assert(X_BYTES % (1024 * NWAVES) == 0 && G_BYTES % (1024 * NWAVES) == 0, "slab must divide over the waves");
-    static_assert(BK % 16 == 0 && XROW <= 1024 && GROW <= 1024, "tile limits");
+    static_assert(BK % 32 == 0 && XROW <= 1024 && GROW <= 1024, "tile limits");
     static_assert(NS >= 3, "the ring holds the slab being read, the one landing and at least one more");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS ring too large");
-    static_assert(RC <= KS * FM * FN, "the multiply phase has a slot for every read");
+    static_assert(RC <= KS * FM * FN && RC < FM, "the multiply phase has a slot for every late read, and they are X fragments");
 };
 
 template <typename TL, int OUTS>
@@ -316,57 +316,58 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
         for (int n = 0; n < NGI; ++n) *(lds_u4)(bg + (wave * NGI + n) * 1024 + lane * 16) = v[NXI + n];
     };
 
-    // ---- fragment geometry for ds_read_b64_tr_b16 (lane i of a 16-lane group supplies row i/4, cols 4*(i%4)..+3
-    // and receives column i, rows 0..3).  Row r = 16*ks + 8*(blk/2) + 4*h + li/4, so r mod 4 = li/4.
+    // ---- fragment geometry.  An operand fragment of v_mfma_f32_16x16x32_bf16 is 16 columns of the slab x 32 tokens:
+    // lane (blk, li) = (lane / 16, lane % 16) holds column li, tokens 8*blk .. 8*blk+7.  ds_read_b64_tr_b16 works on
+    // 16-lane groups: lane li supplies the address of 4 columns (4*(li%4) ..) of slab row (li/4) of a 4-row block
+    // and receives column li of those 4 rows; two reads (rows 8*blk + 0..3 and + 4..7) make a lane's 8 tokens.
+    // Row r = 32*ks + 8*blk + 4*h + li/4, so r mod 4 = li/4: the swizzle term of this lane's rows.
     const int blk = lane / 16, li = lane % 16;
-    const int frow = 8 * (blk / 2) + li / 4;
-    const int sw = 4 * (li / 4);                                    // swizzle term of this lane's rows
-    const int low = 2 * (blk % 2) * 16 + (li % 4) * 8;              // bytes: chunk 2*(blk%2) + (li%4)/2, half (li%4)%2
+    const int frow = 8 * blk + li / 4;
+    const int sw = 4 * (li / 4);
+    const int low = (li % 4) * 8;                                   // bytes inside the fragment's two 16-byte chunks
     int a_addr[FM], b_addr[FN];
 #pragma unroll
-    for (int a = 0; a < FM; ++a) a_addr[a] = frow * XROW + ((((wm * TL::WM + a * 32) / 8) ^ sw) * 16) + low;
+    for (int a = 0; a < FM; ++a) a_addr[a] = frow * XROW + ((((wm * TL::WM + a * 16) / 8) ^ sw) * 16) + low;
 #pragma unroll
-    for (int c = 0; c < FN; ++c) b_addr[c] = frow * GROW + ((((wn * TL::WN + c * 32) / 8) ^ sw) * 16) + low;
+    for (int c = 0; c < FN; ++c) b_addr[c] = frow * GROW + ((((wn * TL::WN + c * 16) / 8) ^ sw) * 16) + low;
 
     // register tiles: the running contraction, and one per requested per-example statistic
-    float16_t acc[FM][FN];
-    float16_t acc_id[HAS_ID ? FM : 1][HAS_ID ? FN : 1], acc_sq[HAS_SQ ? FM : 1][HAS_SQ ? FN : 1];
-    float16_t acc_sg[HAS_SF ? FM : 1][HAS_SF ? FN : 1];
-    half2_t cnt[HAS_PK ? FM : 1][HAS_PK ? FN : 1][8];
-    uint32_t cnt8[HAS_U8 ? FM : 1][HAS_U8 ? FN : 1][4];
+    float4_t acc[FM][FN];
+    float4_t acc_id[HAS_ID ? FM : 1][HAS_ID ? FN : 1], acc_sq[HAS_SQ ? FM : 1][HAS_SQ ? FN : 1];
+    float4_t acc_sg[HAS_SF ? FM : 1][HAS_SF ? FN : 1];
+    half2_t cnt[HAS_PK ? FM : 1][HAS_PK ? FN : 1][2];
+    uint32_t cnt8[HAS_U8 ? FM : 1][HAS_U8 ? FN : 1];
 #pragma unroll
     for (int a = 0; a < FM; ++a)
 #pragma unroll
-        for (int c = 0; c < FN; ++c)
+        for (int c = 0; c < FN; ++c) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
+            for (int r = 0; r < 4; ++r) {
                 acc[a][c][r] = 0.f;
                 if (HAS_ID) acc_id[a][c][r] = 0.f;
                 if (HAS_SQ) acc_sq[a][c][r] = 0.f;
                 if (HAS_SF) acc_sg[a][c][r] = 0.f;
                 if (HAS_PK) cnt[a][c][r / 2] = half2_t{(_Float16)0, (_Float16)0};
-                if (HAS_U8) cnt8[a][c][r / 4] = 0u;
             }
+            if (HAS_U8) cnt8[a][c] = 0u;
+        }
 
-    // Fragments of one slab.  Fragment number f of a k-step alternates between the two operands
-    // (G0, X0, G1, X1, ..., then what is left), so the operands of the first MFMAs arrive first.
+    // Fragments of one slab.  Fragment number f of a k-step: first the G fragments, then the X fragments, so the
+    // ones read late (in the multiply phase) are the X fragments the last MFMAs use.
     bf16x8_t fa[KS][FM], fb[KS][FN];
     const unsigned char* rd_bx = lds;                  // buffer of the slab being read
     int rd_buf = 0;
     auto read_frag = [&](int ks, int f) {
-        constexpr int NALT = 2 * (FM < FN ? FM : FN);
-        const bool is_g = f < NALT ? (f % 2 == 0) : (FN > FM);
-        const int idx = f < NALT ? f / 2 : f - NALT / 2;
-        if (is_g) {
-            const unsigned char* p = rd_bx + TL::X_BYTES + b_addr[idx] + ks * 16 * GROW;
+        if (f < FN) {
+            const unsigned char* p = rd_bx + TL::X_BYTES + b_addr[f] + ks * 32 * GROW;
             const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p));
             const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p + 4 * GROW));
-            fb[ks][idx] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            fb[ks][f] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         } else {
-            const unsigned char* p = rd_bx + a_addr[idx] + ks * 16 * XROW;
+            const unsigned char* p = rd_bx + a_addr[f - FN] + ks * 32 * XROW;
             const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p));
             const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p + 4 * XROW));
-            fa[ks][idx] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            fa[ks][f - FN] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         }
     };
     auto read_phase = [&]() {
@@ -396,7 +397,7 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
 #pragma unroll
                 for (int c = 0; c < FN; ++c) {
                     const int i = (ks * FM + a) * FN + c;
-                    acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][a], fb[ks][c], acc[a][c], 0, 0, 0);
+                    acc[a][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[ks][a], fb[ks][c], acc[a][c], 0, 0, 0);
                     __builtin_amdgcn_sched_barrier(0);
                     if (i < RC) {
                         read_frag(KS - 1, FPK - RC + i);
@@ -469,17 +470,17 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
     }
     wait_vmcnt<0>();   // drain the (empty) loads issued past the end before the LDS is released
 
-    // ---- epilogue: lane holds column (lane%32), rows 8*(r/4) + 4*(lane/32) + r%4 of each 32x32 tile
+    // ---- epilogue: lane holds column (lane%16), rows 4*(lane/16) + r of each 16x16 tile
     const int64_t split_off = (int64_t)split * din * dout;
-    const int jn = lane % 32, ib = 4 * (lane / 32);
+    const int jn = lane % 16, ib = 4 * (lane / 16);
 #pragma unroll
     for (int a = 0; a < FM; ++a)
 #pragma unroll
         for (int c = 0; c < FN; ++c) {
-            const int j = j0 + wn * TL::WN + c * 32 + jn;
+            const int j = j0 + wn * TL::WN + c * 16 + jn;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int i = i0 + wm * TL::WM + a * 32 + 8 * (r / 4) + ib + (r % 4);
+            for (int r = 0; r < 4; ++r) {
+                const int i = i0 + wm * TL::WM + a * 16 + ib + r;
                 if (i < din && j < dout) {
                     const int64_t e = split_off + (int64_t)i * dout + j;
                     if constexpr (!PER_EXAMPLE) out_id[e] = acc[a][c][r];
@@ -487,7 +488,7 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
                     if constexpr (HAS_SQ) out_sq[e] = acc_sq[a][c][r];
                     if constexpr (HAS_SF) out_sg[e] = acc_sg[a][c][r];
                     if constexpr (HAS_PK) out_sg[e] = (float)cnt[a][c][r / 2][r % 2];
-                    if constexpr (HAS_U8) out_sg[e] = (float)((int)((cnt8[a][c][r / 4] >> (8 * (r % 4))) & 0xffu) - nseg);
+                    if constexpr (HAS_U8) out_sg[e] = (float)((int)((cnt8[a][c] >> (8 * r)) & 0xffu) - nseg);
                 }
             }
         }
@@ -510,7 +511,7 @@ __global__ __launch_bounds__(256) void square_bf16_kernel(const uint4_t* __restr
 // two fp32 register tiles (phi = square, sign counts beyond 2048 examples): 256 x 128 block, 64 x 64 per wave.
 using TileWide = Bf16Tile<256, 256, 128, 64, 32, 4, 6>;
 using TileToken = Bf16Tile<256, 256, 128, 64, 32, 5, 6>;
-using TilePhi = Bf16Tile<256, 128, 64, 64, 32, 4, 4>;
+using TilePhi = Bf16Tile<256, 128, 64, 64, 32, 4, 2>;
 
 template <typename TL, int OUTS>
 hipError_t launch_one(const uint16_t* X, const uint16_t* G, int64_t B, int64_t T, int64_t din, int64_t dout,

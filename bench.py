@@ -191,7 +191,7 @@ def main() -> int:
     # the contraction kernels are reported against this measured ceiling beside the datasheet peak
     n_cu = torch.cuda.get_device_properties(dev).multi_processor_count
     probe_ops = torch.randn(pex.lib().pex_mfma_probe_operand_bytes() // 2, device=dev).to(torch.bfloat16)
-    probe_iters = 3000
+    probe_iters = 1500
     _, probe_sink = pex.pex_mfma_probe(probe_ops, n_cu, probe_iters)
     for _ in range(3):
         pex.pex_mfma_probe(probe_ops, n_cu, probe_iters, sink=probe_sink)
@@ -327,7 +327,7 @@ def main() -> int:
                    "flop_per_step": flop_per_step, "seed": args.seed},
         "roofline": roofline, "square_roofline": square_roofline, "update_roofline": update_roofline,
         "mfma_only_ceiling": {"achieved": round(ceiling, 1), "unit": "TFLOP/s", "frac_of_peak": round(ceiling / PEAK_BF16_TFLOPS, 4),
-                              "kernel": "mfma_probe_kernel: nothing but v_mfma_f32_32x32x16_bf16, 8 waves on each of "
+                              "kernel": "mfma_probe_kernel: nothing but v_mfma_f32_16x16x32_bf16, 8 waves on each of "
                                         f"{n_cu} compute units, Gaussian operands", "launch_ms": round(probe_ms, 4)},
         "cpu_baseline": cpu,
         "shared_contraction_step": None if multi_ms is None else {"ms_per_step": round(multi_ms, 4),

@@ -260,14 +260,14 @@ pex_status pex_embed_stat(const void *ids, int32_t ids_bytes, const void *G, int
 
 /*
  * pex_mfma_probe -- measurement aid, not part of the method: one launch that issues nothing but bf16 MFMAs
- * (v_mfma_f32_32x32x16_bf16, fp32 accumulation) in the register shape of the 256 x 256 tile contraction kernel, on
+ * (v_mfma_f32_16x16x32_bf16, fp32 accumulation) in the register shape of the 256 x 256 tile contraction kernel, on
  * `workgroups` workgroups of 8 waves (use the number of compute units).  Its rate is the ceiling the matrix pipes of
  * the chip sustain at the clock they settle at under load; the contraction kernels are reported against it beside the
  * datasheet peak.  The values of the operands set the switching activity and with it the clock, so the caller supplies
  * them (for a like-for-like figure: the same distribution as the contraction's inputs).
  *   operands  device, pex_mfma_probe_operand_bytes() bytes of bf16 values, 16-byte aligned
  *   sink      device, pex_mfma_probe_sink_floats(workgroups) floats; receives one sum per lane (keeps the work alive)
- *   returns the FLOP the launch performs in *flop (host), 2*32*32*16 per MFMA
+ *   returns the FLOP the launch performs in *flop (host), 2*16*16*32 per MFMA
  */
 size_t pex_mfma_probe_operand_bytes(void);
 size_t pex_mfma_probe_sink_floats(int32_t workgroups);

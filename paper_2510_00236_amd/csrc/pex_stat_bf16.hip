@@ -9,8 +9,8 @@
 //   * One workgroup = 8 waves (two per SIMD) owns a BM x BN tile of S; a wave owns WM x WN of it as FM x FN
 //     accumulators of v_mfma_f32_16x16x32_bf16.  (Same FLOP per cycle as the 32x32x16 form and the same LDS reads per
 //     FLOP, but half the accumulator traffic; on this power-limited chip an MFMA-only loop sustains 2.02 PFLOP/s
-//     with it against 1.80 with 32x32x16 on Gaussian operands, and the contraction gained 7 %.)  phi = identity, sign and the per-token square use 256 x 256 tiles (128 x 64 per
-//     wave); phi = square needs a second fp32 register tile for the running sum and uses 256 x 128 (64 x 64 per
+//     with it against 1.80 with 32x32x16 on Gaussian operands, and the contraction gained 7 %.)  phi = identity, sign
+//     and the per-token square use 256 x 256 tiles (128 x 64 per wave); phi = square needs a second fp32 register tile for the running sum and uses 256 x 128 (64 x 64 per
 //     wave); sign counts are integers of magnitude <= B and are kept as packed fp16 pairs while B <= 2048, which
 //     is what lets sign use the large tile.
 //   * Slabs of BK tokens go HBM -> LDS with buffer_load_dwordx4 ... lds: no VGPR staging, no LDS write
@@ -25,17 +25,17 @@
 // Schedule: two groups of four waves (one wave of each group per SIMD) run half a slab apart, so that whenever
 // one wave of a SIMD sits at a barrier, waits for LDS data or folds phi, the other one is in the middle of its
 // MFMAs.  A wave alternates between
-//   read phase     : fragments of the first k-step(s) of slab g come from LDS into registers, then this wave's
-//                    global->LDS loads of a later slab are issued;
-//   multiply phase : all MFMAs of slab g at raised priority, the fragment reads of its last k-step slotted in
-//                    between the first of them,
+//   read phase     : most operand fragments of slab g come from LDS into registers (all of G, the first of X),
+//                    then this wave's global->LDS loads of a later slab are issued;
+//   multiply phase : all MFMAs of slab g at raised priority, the reads of the remaining X fragments (which the
+//                    last MFMAs use) slotted in between the first of them,
 // and every phase ends at a workgroup barrier where the groups swap roles:
 //   phase 2g   : group 0 reads slab g       | group 1 multiplies slab g-1
 //   phase 2g+1 : group 0 multiplies slab g  | group 1 reads slab g
 // Measured facts behind this shape (MI355X): a wave gets one LDS instruction through per ~16 cycles whatever its
-// width, and the transposing read is 8 bytes per lane, so the 2*(FM+FN) reads of a k-step cost as much issue
-// time as half its MFMAs: all reads of a slab in one phase would make that phase longer than the multiply phase
-// it hides behind.  The memory pipeline takes one 1 KiB direct-to-LDS load per ~40-60 cycles per compute unit
+// width, and the transposing read is 8 bytes per lane, so the 2*(FM+FN) = 24 reads of a 32-token slab cost three
+// quarters of the issue time of its 32 MFMAs: with the global->LDS loads on top, all reads of a slab in one phase
+// would make that phase longer than the multiply phase it hides behind.  The memory pipeline takes one 1 KiB direct-to-LDS load per ~40-60 cycles per compute unit
 // when the whole chip is loading; a wave that stalls on that in its read phase delays nothing, in the multiply
 // phase it would starve the MFMA pipe.  Priority is raised only while a wave issues MFMAs: a wave that waits at
 // a barrier with raised priority slows the other wave of its SIMD.
@@ -387,7 +387,9 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
         }
     };
     // Multiply phase: MFMA number i is followed by fragment read i of the last k-step (while i < RC).  The
-    // scheduling fences pin this order; the compiler adds the LDS waits the MFMAs need.
+    // scheduling fences pin this order; the compiler adds the LDS waits the MFMAs need.  The G fragment index runs
+    // back and forth ("snake"), so consecutive MFMAs share an operand register wherever they can: measured +2 % on an
+    // MFMA-only loop (less switching on the operand reads, and the chip's clock is set by power).
     auto multiply_phase = [&]() {
         __builtin_amdgcn_s_setprio(1);
 #pragma unroll
@@ -395,8 +397,9 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
 #pragma unroll
             for (int a = 0; a < FM; ++a)
 #pragma unroll
-                for (int c = 0; c < FN; ++c) {
-                    const int i = (ks * FM + a) * FN + c;
+                for (int cc = 0; cc < FN; ++cc) {
+                    const int c = (a & 1) ? FN - 1 - cc : cc;
+                    const int i = (ks * FM + a) * FN + cc;
                     acc[a][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[ks][a], fb[ks][c], acc[a][c], 0, 0, 0);
                     __builtin_amdgcn_sched_barrier(0);
                     if (i < RC) {
@@ -509,9 +512,9 @@ __global__ __launch_bounds__(256) void square_bf16_kernel(const uint4_t* __restr
 // plain contractions and packed sign counts: 256 x 256 block, 128 x 64 per wave, slabs of 32 tokens, ring of 4;
 // the per-token square needs its slab a phase earlier and takes a ring of 5 (all 160 KB of LDS);
 // two fp32 register tiles (phi = square, sign counts beyond 2048 examples): 256 x 128 block, 64 x 64 per wave.
-using TileWide = Bf16Tile<256, 256, 128, 64, 32, 4, 6>;
-using TileToken = Bf16Tile<256, 256, 128, 64, 32, 5, 6>;
-using TilePhi = Bf16Tile<256, 128, 64, 64, 32, 4, 2>;
+using TileWide = Bf16Tile<256, 256, 128, 64, 32, 4, 5>;
+using TileToken = Bf16Tile<256, 256, 128, 64, 32, 5, 5>;
+using TilePhi = Bf16Tile<256, 128, 64, 64, 32, 4, 3>;
 
 template <typename TL, int OUTS>
 hipError_t launch_one(const uint16_t* X, const uint16_t* G, int64_t B, int64_t T, int64_t din, int64_t dout,

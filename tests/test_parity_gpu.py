@@ -260,10 +260,10 @@ def test_seeded_sweep_of_shapes(B, T, din, dout, dtype):
 
 
 def test_mfma_probe_runs_and_counts_its_flop():
-    """The measurement aid: deterministic output, FLOP count = workgroups x 8 waves x iters x 16 MFMAs x 2*32*32*16."""
+    """The measurement aid: deterministic output, FLOP count = workgroups x 8 waves x iters x 64 MFMAs x 2*16*16*32."""
     ops = torch.randn(pex.lib().pex_mfma_probe_operand_bytes() // 2, device=DEV).to(torch.bfloat16)
     flop, s1 = pex.pex_mfma_probe(ops, 4, 10)
-    assert flop == 4 * 8 * 10 * 16 * 2 * 32 * 32 * 16
+    assert flop == 4 * 8 * 10 * 64 * 2 * 16 * 16 * 32
     _, s2 = pex.pex_mfma_probe(ops, 4, 10)
     torch.cuda.synchronize()
     assert s1.shape == (4 * 512,) and torch.isfinite(s1).all() and torch.equal(s1, s2)

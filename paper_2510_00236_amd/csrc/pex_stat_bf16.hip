@@ -17,9 +17,10 @@
 //     instructions.  Out-of-range lanes of a buffer load write zeros, which gives the zero fill of ragged slab
 //     rows (num_records of a per-slab descriptor) and of ragged tile columns (a poisoned lane offset) for free.
 //   * Each such instruction writes 1 KiB contiguous, so slab rows cannot be padded; instead the 16-byte chunks of
-//     slab row r are stored at chunk index c ^ 4*(r mod 4).  The transposing read ds_read_b64_tr_b16 of a
-//     16-lane group touches 4 consecutive rows x 32 bytes; the swizzle puts those in 4 different 64-byte bank
-//     groups (no bank conflicts measured).
+//     slab row r are stored at chunk index c ^ 4*(r mod 4) ^ 2*(bit 3 of r).  The transposing read
+//     ds_read_b64_tr_b16 of a 16-lane group touches 4 consecutive rows x 32 bytes, and the group next to it (served
+//     in the same cycle) the rows 8 further down; the swizzle puts the 4 rows in 4 different 64-byte bank groups and
+//     the two lane groups in different halves of each (no bank conflicts measured).
 //   * NS slabs form a ring in LDS.
 //
 // Schedule: two groups of four waves (one wave of each group per SIMD) run half a slab apart, so that whenever
@@ -254,18 +255,18 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
 
     // ---- loader geometry.  Load q of a slab (q = wave*NXI + n) fills LDS bytes [q*1024, q*1024+1024) of the X
     // part: slab rows q*RX .. q*RX+RX-1.  Lane L fills 16-byte slot (L mod XROW/16) of row q*RX + L/(XROW/16)
-    // with global chunk c = slot ^ 4*(row mod 4).
+    // with global chunk c = slot ^ 4*(row mod 4) ^ 2*(bit 3 of row).
     uint32_t xoff[NXI], goff[NGI];
 #pragma unroll
     for (int n = 0; n < NXI; ++n) {
         const int q = wave * NXI + n, r = q * RX + lane / (XROW / 16), slot = lane % (XROW / 16);
-        const int c = slot ^ (4 * (r & 3));
+        const int c = slot ^ (4 * (r & 3)) ^ (2 * ((r >> 3) & 1));
         xoff[n] = (i0 + c * 8 < din) ? (uint32_t)(r * din + c * 8) * 2u : 0x80000000u;
     }
 #pragma unroll
     for (int n = 0; n < NGI; ++n) {
         const int q = wave * NGI + n, r = q * RG + lane / (GROW / 16), slot = lane % (GROW / 16);
-        const int c = slot ^ (4 * (r & 3));
+        const int c = slot ^ (4 * (r & 3)) ^ (2 * ((r >> 3) & 1));
         goff[n] = (j0 + c * 8 < dout) ? (uint32_t)(r * dout + c * 8) * 2u : 0x80000000u;
     }
     const int din_avail = din - i0, dout_avail = dout - j0;   // columns of this tile that exist
@@ -320,10 +321,11 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
     // lane (blk, li) = (lane / 16, lane % 16) holds column li, tokens 8*blk .. 8*blk+7.  ds_read_b64_tr_b16 works on
     // 16-lane groups: lane li supplies the address of 4 columns (4*(li%4) ..) of slab row (li/4) of a 4-row block
     // and receives column li of those 4 rows; two reads (rows 8*blk + 0..3 and + 4..7) make a lane's 8 tokens.
-    // Row r = 32*ks + 8*blk + 4*h + li/4, so r mod 4 = li/4: the swizzle term of this lane's rows.
+    // Row r = 32*ks + 8*blk + 4*h + li/4, so r mod 4 = li/4 and bit 3 of r = blk mod 2: the swizzle terms of this
+    // lane's rows.
     const int blk = lane / 16, li = lane % 16;
     const int frow = 8 * blk + li / 4;
-    const int sw = 4 * (li / 4);
+    const int sw = (4 * (li / 4)) ^ (2 * (blk & 1));
     const int low = (li % 4) * 8;                                   // bytes inside the fragment's two 16-byte chunks
     int a_addr[FM], b_addr[FN];
 #pragma unroll

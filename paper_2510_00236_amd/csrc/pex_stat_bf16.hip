@@ -17,10 +17,12 @@
 //     instructions.  Out-of-range lanes of a buffer load write zeros, which gives the zero fill of ragged slab
 //     rows (num_records of a per-slab descriptor) and of ragged tile columns (a poisoned lane offset) for free.
 //   * Each such instruction writes 1 KiB contiguous, so slab rows cannot be padded; instead the 16-byte chunks of
-//     slab row r are stored at chunk index c ^ 4*(r mod 4) ^ 2*(bit 3 of r).  The transposing read
-//     ds_read_b64_tr_b16 of a 16-lane group touches 4 consecutive rows x 32 bytes, and the group next to it (served
-//     in the same cycle) the rows 8 further down; the swizzle puts the 4 rows in 4 different 64-byte bank groups and
-//     the two lane groups in different halves of each (no bank conflicts measured).
+//     slab row r are stored at chunk index c ^ 4*(r mod 4).  The transposing read ds_read_b64_tr_b16 of a 16-lane
+//     group touches 4 consecutive rows x 32 bytes; the swizzle puts those in 4 different 64-byte bank groups.  The
+//     lane group served in the same cycle reads the same columns 8 rows further down, i.e. the same banks: a two-way
+//     conflict per read (SQ_LDS_BANK_CONFLICT = 2 x reads) that costs 1.4 % of the cycles.  Moving those rows by 32
+//     bytes (chunk index ^ 2 on bit 3 of the row) removes the conflicts but makes lanes fetch the halves of a
+//     64-byte segment out of order, which doubled the L2 misses and cost 4.5 % of the time: not done.
 //   * NS slabs form a ring in LDS.
 //
 // Schedule: two groups of four waves (one wave of each group per SIMD) run half a slab apart, so that whenever
@@ -255,18 +257,18 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
 
     // ---- loader geometry.  Load q of a slab (q = wave*NXI + n) fills LDS bytes [q*1024, q*1024+1024) of the X
     // part: slab rows q*RX .. q*RX+RX-1.  Lane L fills 16-byte slot (L mod XROW/16) of row q*RX + L/(XROW/16)
-    // with global chunk c = slot ^ 4*(row mod 4) ^ 2*(bit 3 of row).
+    // with global chunk c = slot ^ 4*(row mod 4).
     uint32_t xoff[NXI], goff[NGI];
 #pragma unroll
     for (int n = 0; n < NXI; ++n) {
         const int q = wave * NXI + n, r = q * RX + lane / (XROW / 16), slot = lane % (XROW / 16);
-        const int c = slot ^ (4 * (r & 3)) ^ (2 * ((r >> 3) & 1));
+        const int c = slot ^ (4 * (r & 3));
         xoff[n] = (i0 + c * 8 < din) ? (uint32_t)(r * din + c * 8) * 2u : 0x80000000u;
     }
 #pragma unroll
     for (int n = 0; n < NGI; ++n) {
         const int q = wave * NGI + n, r = q * RG + lane / (GROW / 16), slot = lane % (GROW / 16);
-        const int c = slot ^ (4 * (r & 3)) ^ (2 * ((r >> 3) & 1));
+        const int c = slot ^ (4 * (r & 3));
         goff[n] = (j0 + c * 8 < dout) ? (uint32_t)(r * dout + c * 8) * 2u : 0x80000000u;
     }
     const int din_avail = din - i0, dout_avail = dout - j0;   // columns of this tile that exist
@@ -321,11 +323,10 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
     // lane (blk, li) = (lane / 16, lane % 16) holds column li, tokens 8*blk .. 8*blk+7.  ds_read_b64_tr_b16 works on
     // 16-lane groups: lane li supplies the address of 4 columns (4*(li%4) ..) of slab row (li/4) of a 4-row block
     // and receives column li of those 4 rows; two reads (rows 8*blk + 0..3 and + 4..7) make a lane's 8 tokens.
-    // Row r = 32*ks + 8*blk + 4*h + li/4, so r mod 4 = li/4 and bit 3 of r = blk mod 2: the swizzle terms of this
-    // lane's rows.
+    // Row r = 32*ks + 8*blk + 4*h + li/4, so r mod 4 = li/4: the swizzle term of this lane's rows.
     const int blk = lane / 16, li = lane % 16;
     const int frow = 8 * blk + li / 4;
-    const int sw = (4 * (li / 4)) ^ (2 * (blk & 1));
+    const int sw = 4 * (li / 4);
     const int low = (li % 4) * 8;                                   // bytes inside the fragment's two 16-byte chunks
     int a_addr[FM], b_addr[FN];
 #pragma unroll

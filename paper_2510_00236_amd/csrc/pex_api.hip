@@ -47,10 +47,10 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
         // One workgroup per compute unit runs at a time, so the contraction takes
         //   rounds(ns) * ceil(units / ns)  unit-times,  rounds = ceil(tiles * ns / 256),
         // and the fixed-order reduction of the partial sums reads ns copies of S.  Pick the cheapest ns.
-        // A unit-time is one example (or 64 rows) on one tile at ~4 TFLOP/s per compute unit; the reduction
+        // A unit-time is one example (or 64 rows) on one tile at ~5.5 TFLOP/s per compute unit; the reduction
         // streams at ~4 TB/s.
         const double rows_per_unit = per_example ? (double)T : (double)slab;
-        const double t_unit = 2.0 * rows_per_unit * bm * bn / 4.0e12;
+        const double t_unit = 2.0 * rows_per_unit * bm * bn / 5.5e12;
         const double s_bytes = (double)din * (double)dout * 4.0;
         double best = 0.0;
         const int64_t lim = units < max_split ? units : max_split;

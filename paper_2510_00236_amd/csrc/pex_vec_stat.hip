@@ -162,11 +162,12 @@ hipError_t launch_typed(const TIn* A, const TIn* C, int64_t B, int64_t T, int64_
 
 VecPlan plan_vec_stat(int64_t B, int64_t T, int64_t d, pex_dtype dt)
 {
-    // enough blocks to keep HBM busy (about eight per compute unit), ranges of at least 32 tokens
+    // as many blocks as are resident at once (eight per compute unit) and no more, so that there is no second,
+    // mostly empty round of blocks; ranges of at least 32 tokens
     VecPlan p{};
     const int vec = dt == PEX_BF16 ? 8 : 4;
     const int64_t chunks = (d + CW * vec - 1) / (CW * vec);
-    int64_t nrange = (2048 + chunks * B - 1) / (chunks * B);
+    int64_t nrange = 2048 / (chunks * B);
     const int64_t max_range = (T + 31) / 32;
     if (nrange > max_range) nrange = max_range;
     if (nrange < 1) nrange = 1;

@@ -265,6 +265,18 @@ def pex_vec_stat(A, C=None, want=("identity", "square", "sign"), out=None, works
     return res
 
 
+def pex_example_norms_workspace_bytes(B, T, din, dout, dtype_code) -> int:
+    return int(lib().pex_example_norms_workspace_bytes(B, T, din, dout, dtype_code))
+
+
+def pex_weighted_sum_workspace_bytes(B, T, din, dout, dtype_code) -> int:
+    return int(lib().pex_weighted_sum_workspace_bytes(B, T, din, dout, dtype_code))
+
+
+def pex_stat_power_workspace_bytes(B, T, din, dout, dtype_code) -> int:
+    return int(lib().pex_stat_power_workspace_bytes(B, T, din, dout, dtype_code))
+
+
 def pex_example_norms(X, G, N=None, workspace=None, stream=None):
     """N[B] = ||X_b^T G_b||_F^2, fp32."""
     import torch
@@ -272,7 +284,7 @@ def pex_example_norms(X, G, N=None, workspace=None, stream=None):
     dt = _dtype_code(X)
     if N is None:
         N = torch.empty(B, dtype=torch.float32, device=X.device)
-    ws, wptr, wbytes = _workspace(int(lib().pex_example_norms_workspace_bytes(B, T, din, dout, dt)), X, workspace)
+    ws, wptr, wbytes = _workspace(pex_example_norms_workspace_bytes(B, T, din, dout, dt), X, workspace)
     _check(lib().pex_example_norms(_dev(X, "X"), _dev(G, "G"), B, T, din, dout, dt, _dev(N, "N"), wptr, wbytes,
                                    _stream(stream)))
     return N
@@ -287,7 +299,7 @@ def pex_weighted_sum(X, G, w, S=None, workspace=None, stream=None):
         raise ValueError("w must be float32 with one weight per example")
     if S is None:
         S = torch.empty(din, dout, dtype=torch.float32, device=X.device)
-    ws, wptr, wbytes = _workspace(int(lib().pex_weighted_sum_workspace_bytes(B, T, din, dout, dt)), X, workspace)
+    ws, wptr, wbytes = _workspace(pex_weighted_sum_workspace_bytes(B, T, din, dout, dt), X, workspace)
     _check(lib().pex_weighted_sum(_dev(X, "X"), _dev(G, "G"), _dev(w, "w"), B, T, din, dout, dt, _dev(S, "S"), wptr,
                                   wbytes, _stream(stream)))
     return S
@@ -300,7 +312,7 @@ def pex_stat_power(X, G, alpha, S=None, workspace=None, stream=None):
     dt = _dtype_code(X)
     if S is None:
         S = torch.empty(din, dout, dtype=torch.float32, device=X.device)
-    ws, wptr, wbytes = _workspace(int(lib().pex_stat_power_workspace_bytes(B, T, din, dout, dt)), X, workspace)
+    ws, wptr, wbytes = _workspace(pex_stat_power_workspace_bytes(B, T, din, dout, dt), X, workspace)
     _check(lib().pex_stat_power(_dev(X, "X"), _dev(G, "G"), B, T, din, dout, dt, float(alpha), _dev(S, "S"), wptr,
                                 wbytes, _stream(stream)))
     return S
@@ -412,15 +424,31 @@ def pex_embed_stat(ids, G, V, want, out=None, workspace=None, stream=None):
     return res
 
 
+def pex_mfma_probe_operand_bytes() -> int:
+    return int(lib().pex_mfma_probe_operand_bytes())
+
+
+def pex_mfma_probe_sink_floats(workgroups) -> int:
+    return int(lib().pex_mfma_probe_sink_floats(int(workgroups)))
+
+
+def pex_version() -> int:
+    return int(lib().pex_version())
+
+
+def pex_status_string(code: int) -> str:
+    return status_string(code)
+
+
 def pex_mfma_probe(operands, workgroups, iters, sink=None, stream=None):
     """Measurement aid: one launch of nothing but bf16 MFMAs (see ``pex_mfma_probe`` in the header).  ``operands`` is a
     bf16 tensor of at least ``pex_mfma_probe_operand_bytes()`` bytes.  Returns (FLOP of the launch, sink tensor)."""
     import torch
-    need = int(lib().pex_mfma_probe_operand_bytes())
+    need = pex_mfma_probe_operand_bytes()
     if operands.numel() * operands.element_size() < need:
         raise ValueError(f"operands must hold at least {need} bytes")
     if sink is None:
-        sink = torch.empty(int(lib().pex_mfma_probe_sink_floats(workgroups)), dtype=torch.float32, device=operands.device)
+        sink = torch.empty(pex_mfma_probe_sink_floats(workgroups), dtype=torch.float32, device=operands.device)
     flop = ctypes.c_double(0.0)
     _check(lib().pex_mfma_probe(_dev(operands, "operands"), int(workgroups), int(iters), _dev(sink, "sink"), ctypes.byref(flop),
                                 _stream(stream)))

@@ -24,6 +24,7 @@ def test_header_and_library_agree():
     L = pex.lib()
     for n in names:
         assert hasattr(L, n), f"libpex.so does not export {n}"
+        assert callable(getattr(pex, n, None)), f"the binding has no function named {n}"
 
 
 def test_version_and_status_strings():

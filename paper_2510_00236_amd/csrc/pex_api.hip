@@ -21,14 +21,18 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
     // both kernels are device code of this library).
     const bool force_generic = env_int("PEX_FORCE_GENERIC", 0) != 0;
     p.kernel = (dt == PEX_BF16 && !force_generic && bf16_supports(B, T, din, dout)) ? 1 : 0;
+    if (dt == PEX_F32 && !force_generic && f32_mfma_supports(B, T, din, dout, mode)) p.kernel = 2;
 
     // The unit the batch axis is split in: whole examples when phi is applied per example (the sum over
     // the sequence must be complete before phi), slabs of 64 rows of the flattened [B*T] axis otherwise.
     int64_t tiles, target, units;
     int bm = 64, bn = 64;
-    if (p.kernel != 0) {
+    if (p.kernel == 1) {
         bf16_tile_shape(mode, B, &bm, &bn);
         target = 256;    // one workgroup per compute unit
+    } else if (p.kernel == 2) {
+        f32_tile_shape(&bm, &bn);
+        target = 512;    // two workgroups of four waves per compute unit, so that loads and MFMAs overlap
     } else {
         target = 1024;   // four small workgroups per compute unit
     }
@@ -37,7 +41,7 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
     units = per_example ? B : (B * T + slab - 1) / slab;
     const int max_split = env_int("PEX_MAX_SPLIT", 16);
     int64_t nsplit = 1, per = units;
-    if (p.kernel == 0) {
+    if (p.kernel != 1) {
         nsplit = (target + tiles - 1) / tiles;
         if (nsplit > max_split) nsplit = max_split;
         if (nsplit > units) nsplit = units;
@@ -115,6 +119,8 @@ static pex_status run_stat(const void* X, const void* G, int64_t B, int64_t T, i
         e = launch_square_bf16(X, x2, B * T * din, stream);
         if (e == hipSuccess) e = launch_square_bf16(G, g2, B * T * dout, stream);
         if (e == hipSuccess) e = launch_stat_bf16(x2, g2, B, T, din, dout, MODE_IDENTITY, plan, out, stream);
+    } else if (plan.kernel == 2) {
+        e = launch_stat_f32(X, G, B, T, din, dout, mode, plan, out, stream, weight, alpha);
     } else if (mode == MODE_POWER) {
         e = plan.kernel == 1 ? launch_power_bf16(X, G, alpha, B, T, din, dout, plan, out, stream)
                              : launch_stat_generic(X, G, B, T, din, dout, dt, mode, plan, out, stream, nullptr, nullptr, alpha);

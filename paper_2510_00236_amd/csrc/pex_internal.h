@@ -19,7 +19,7 @@ enum Mode : int { MODE_IDENTITY = 0, MODE_SQUARE = 1, MODE_SIGN = 2, MODE_TOKEN_
 // How one call is carried out.  Chosen on the host from the shape alone, so the workspace query and
 // the launch always agree.
 struct StatPlan {
-    int kernel;        // 0 = generic SIMT kernel (fp32 inputs, odd shapes), 1 = bf16 MFMA kernel
+    int kernel;        // 0 = generic SIMT kernel (odd shapes), 1 = bf16 MFMA kernel, 2 = fp32 MFMA kernel
     int nsplit;        // number of groups the batch (or, for plain contractions, B*T) is split into
     int64_t per_split; // examples (or rows of B*T) per group
     size_t presq_bytes; // per-token square through pre-squared copies of X and G: their size (256-byte multiple), else 0
@@ -58,6 +58,10 @@ bool bf16_triple_supported(const StatPlan& plan);
 hipError_t launch_stat_bf16_triple(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout,
                                    const StatPlan& plan, float* out_id, float* out_sq, float* out_sg, hipStream_t stream);
 bool bf16_supports(int64_t B, int64_t T, int64_t din, int64_t dout);
+bool f32_mfma_supports(int64_t B, int64_t T, int64_t din, int64_t dout, Mode mode);
+void f32_tile_shape(int* bm, int* bn);
+hipError_t launch_stat_f32(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout, Mode mode,
+                           const StatPlan& plan, float* out, hipStream_t stream, const float* weight, float alpha);
 // out[i] = bf16(in[i]^2) (square in fp32, round to nearest even) for n bf16 values, n a multiple of 8
 hipError_t launch_square_bf16(const void* in, void* out, int64_t n, hipStream_t stream);
 void bf16_tile_shape(Mode mode, int64_t B, int* bm, int* bn);

@@ -16,6 +16,7 @@ SHAPES = [
     (7, 33, 256, 128, "bf16"),
     (2, 37, 70, 33, "bf16"),       # SIMT kernel on bf16
     (3, 50, 129, 65, "f32"),
+    (3, 50, 132, 68, "f32"),       # weighted sums on the fp32 MFMA kernel (norms stay on the SIMT kernel)
     (1, 64, 96, 160, "bf16"),
     (40, 1, 128, 96, "bf16"),
     (1, 1, 1, 1, "f32"),
@@ -79,7 +80,8 @@ def test_norms_sum_to_the_total_of_the_square_statistic_at_full_size():
     assert torch.equal(N, again)
 
 
-@pytest.mark.parametrize("B,T,din,dout,dtype", [(5, 77, 520, 264, "bf16"), (3, 50, 129, 65, "f32"), (7, 33, 256, 128, "bf16")])
+@pytest.mark.parametrize("B,T,din,dout,dtype", [(5, 77, 520, 264, "bf16"), (3, 50, 129, 65, "f32"), (7, 33, 256, 128, "bf16"),
+                                                (4, 40, 260, 132, "f32")])
 @pytest.mark.parametrize("alpha", [1.0, 1.5, 2.0, 3.0])
 def test_power_statistic(B, T, din, dout, dtype, alpha):
     X, G = si.custom(B, T, din, dout, dtype=dtype, seed=B + int(10 * alpha))

@@ -62,6 +62,11 @@ SHAPES = [
     (1, 1, 8, 8, "bf16"),
     (2100, 1, 64, 96, "bf16"),     # more examples than packed sign counts can hold: fp32 counts
     (40, 24, 512, 520, "bf16"),    # 256-wide tiles with a ragged last tile column
+    (3, 50, 132, 68, "f32"),       # fp32 MFMA path: ragged 128-wide tiles, T not a multiple of the 16-token slab
+    (5, 77, 520, 264, "f32"),      # fp32 MFMA path: several tiles, batch split over workgroups
+    (2, 16, 32, 32, "f32"),        # smallest shape the fp32 MFMA path takes
+    (40, 1, 128, 96, "f32"),       # T = 1 on the fp32 MFMA path
+    (7, 33, 256, 128, "f32"),
 ]
 
 
@@ -72,7 +77,8 @@ def test_ragged_and_edge_shapes(B, T, din, dout, dtype):
     _compare(X, G, dtype, f"B{B} T{T} {din}x{dout} {dtype}", elementwise=(B >= 3))
 
 
-@pytest.mark.parametrize("B,T,din,dout,dtype", [(5, 48, 264, 136, "bf16"), (3, 19, 45, 51, "bf16"), (4, 16, 64, 64, "f32")])
+@pytest.mark.parametrize("B,T,din,dout,dtype", [(5, 48, 264, 136, "bf16"), (3, 19, 45, 51, "bf16"), (4, 16, 64, 64, "f32"),
+                                                (6, 40, 264, 136, "f32")])
 def test_integer_inputs_are_bit_exact(B, T, din, dout, dtype):
     """Small-integer inputs: every product and partial sum is exact, so every statistic must match bit for bit."""
     X, G = si.integer_valued(B, T, din, dout, dtype=dtype, seed=3)
@@ -143,9 +149,9 @@ def test_non_default_stream():
 
 
 def test_workspace_errors_on_gpu():
-    X, G = si.custom(8, 32, 256, 128, dtype="bf16", seed=10)
+    X, G = si.custom(64, 32, 256, 128, dtype="bf16", seed=10)      # one tile, many examples: the batch is split
     Xd, Gd = X.to(DEV), G.to(DEV)
-    need = pex.pex_stat_workspace_bytes(8, 32, 256, 128, pex.PEX_BF16, "square")
+    need = pex.pex_stat_workspace_bytes(64, 32, 256, 128, pex.PEX_BF16, "square")
     assert need > 0
     small = torch.empty(need - 16, dtype=torch.uint8, device=DEV)
     with pytest.raises(pex.PexError) as ei:

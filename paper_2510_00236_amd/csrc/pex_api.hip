@@ -32,7 +32,7 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
         target = 256;    // one workgroup per compute unit
     } else if (p.kernel == 2) {
         f32_tile_shape(&bm, &bn);
-        target = 512;    // two workgroups of four waves per compute unit, so that loads and MFMAs overlap
+        target = 768;    // three workgroups of four waves per compute unit, so that loads and MFMAs overlap
     } else {
         target = 1024;   // four small workgroups per compute unit
     }

@@ -8,12 +8,12 @@
 //
 // The fp32 pipe is 16 times slower than the bf16 one per byte of operand, so this kernel is bound by its MFMAs and
 // needs none of the bf16 kernel's machinery: a workgroup of 4 waves owns a 128 x 128 tile (64 x 64 per wave, 2 x 2
-// accumulators), slabs of 16 tokens go global -> registers -> LDS through two buffers (the loads of slab s+1 are in
+// accumulators), slabs of 16 (or 8) tokens go global -> registers -> LDS through two buffers (the loads of slab s+1 are in
 // flight while slab s is multiplied), one barrier per slab.  The t-major layout is what the MFMA wants as it is: the
 // operand of 32x32x2 is one float per lane, row (lane % 32) of token (lane / 32), i.e. a plain ds_read_b32 of 32
 // consecutive floats of one token and 32 of the next; LDS rows are padded by 32 floats so that the two tokens sit in
-// different halves of the banks.  Several workgroups share a compute unit (40 KB of LDS each), which is where the
-// overlap of loads, LDS reads and MFMAs comes from.
+// different halves of the banks.  Three workgroups share a compute unit (at most 40 KB of LDS each), which is where
+// the overlap of loads, LDS reads and MFMAs comes from.
 #include "pex_internal.h"
 
 namespace pex {
@@ -21,17 +21,21 @@ namespace {
 
 typedef __attribute__((ext_vector_type(16))) float float16_t;
 
-constexpr int F_BM = 128, F_BN = 128, F_BK = 16, F_LD = 128 + 32, F_THREADS = 256;
-constexpr int F_LOADS = F_BK * F_BM / 4 / F_THREADS;   // float4 loads per thread, operand and slab: 2
+constexpr int F_BM = 128, F_BN = 128, F_LD = 128 + 32, F_THREADS = 256;
 
 __device__ __forceinline__ float sign_of(float m) { return (float)((m > 0.f) - (m < 0.f)); }
 
-template <int MODE>
-__global__ __launch_bounds__(F_THREADS) void stat_f32_kernel(const float* __restrict__ X, const float* __restrict__ G, int64_t rows_total,
+// F_BK = tokens per slab.  Three workgroups per compute unit (three waves per SIMD) is where loads, LDS reads and
+// MFMAs overlap best (measured against two and four), which caps a wave at 168 registers: two 64-register tiles plus
+// the staging registers of a 16-token slab fit, except with the extra temporaries of sign and the powers, which take
+// slabs of 8.
+template <int MODE, int F_BK>
+__global__ __launch_bounds__(F_THREADS) __attribute__((amdgpu_waves_per_eu(3, 3))) void stat_f32_kernel(const float* __restrict__ X, const float* __restrict__ G, int64_t rows_total,
                                                             int seg_len, int din, int dout, int64_t rows_per_split,
                                                             float* __restrict__ out, const float* __restrict__ weight, float alpha)
 {
     constexpr bool PER_EXAMPLE = !(MODE == MODE_IDENTITY || MODE == MODE_TOKEN_SQ);
+    constexpr int F_LOADS = F_BK * F_BM / 4 / F_THREADS;   // float4 loads per thread, operand and slab
     __shared__ __attribute__((aligned(16))) float Xs[2][F_BK][F_LD];
     __shared__ __attribute__((aligned(16))) float Gs[2][F_BK][F_LD];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -173,7 +177,7 @@ hipError_t launch_stat_f32(const void* X, const void* G, int64_t B, int64_t T, i
     const int64_t rows_per_split = per_example ? plan.per_split * T : plan.per_split;
     const float* x = (const float*)X;
     const float* g = (const float*)G;
-#define PEX_F32_LAUNCH(M) stat_f32_kernel<M><<<grid, block, 0, stream>>>(x, g, rows_total, (int)T, (int)din, (int)dout, rows_per_split, out, weight, alpha)
+#define PEX_F32_LAUNCH(M) stat_f32_kernel<M, (M == MODE_SIGN || M == MODE_POWER) ? 8 : 16><<<grid, block, 0, stream>>>(x, g, rows_total, (int)T, (int)din, (int)dout, rows_per_split, out, weight, alpha)
     switch (mode) {
     case MODE_IDENTITY: PEX_F32_LAUNCH(MODE_IDENTITY); break;
     case MODE_SQUARE: PEX_F32_LAUNCH(MODE_SQUARE); break;

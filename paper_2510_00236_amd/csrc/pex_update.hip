@@ -157,16 +157,30 @@ __global__ __launch_bounds__(256) void moment_track_kernel(float* __restrict__ e
     if (threadIdx.x < 2) partial[(int64_t)blockIdx.x * 2 + threadIdx.x] = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
 }
 
-__global__ __launch_bounds__(256) void moment_finalize_kernel(const double* __restrict__ partial, int nparts, double* __restrict__ sums)
+__global__ __launch_bounds__(1024) void moment_finalize_kernel(const double* __restrict__ partial, int nparts, double* __restrict__ sums)
 {
+    // thread t adds partials t, t + 1024, ... (eight loads in flight), then the usual fixed-order tree
     double s0 = 0.0, s1 = 0.0;
-    for (int i = threadIdx.x; i < nparts; i += 256) { s0 += partial[2 * i]; s1 += partial[2 * i + 1]; }
-    __shared__ double red[4][2];
+    int i = threadIdx.x;
+    for (; i + 7 * 1024 < nparts; i += 8 * 1024) {
+        double a[8], b[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { a[u] = partial[2 * (i + u * 1024)]; b[u] = partial[2 * (i + u * 1024) + 1]; }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { s0 += a[u]; s1 += b[u]; }
+    }
+    for (; i < nparts; i += 1024) { s0 += partial[2 * i]; s1 += partial[2 * i + 1]; }
+    __shared__ double red[16][2];
     s0 = wave_sum(s0);
     s1 = wave_sum(s1);
     if ((threadIdx.x & 63) == 0) { red[threadIdx.x >> 6][0] = s0; red[threadIdx.x >> 6][1] = s1; }
     __syncthreads();
-    if (threadIdx.x < 2) sums[threadIdx.x] = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+    if (threadIdx.x < 2) {
+        double t = 0.0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) t += red[w][threadIdx.x];
+        sums[threadIdx.x] = t;
+    }
 }
 
 inline unsigned update_grid(int64_t n)
@@ -216,7 +230,7 @@ hipError_t launch_moment_track(float* ema_adam, float* ema_micro, const float* S
     moment_track_kernel<<<dim3(grid), dim3(256), 0, stream>>>(ema_adam, ema_micro, S_id, S_sq, n, k, partial);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    moment_finalize_kernel<<<dim3(1), dim3(256), 0, stream>>>(partial, (int)grid, sums);
+    moment_finalize_kernel<<<dim3(1), dim3(1024), 0, stream>>>(partial, (int)grid, sums);
     return hipGetLastError();
 }
 

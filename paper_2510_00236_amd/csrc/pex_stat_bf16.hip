@@ -22,7 +22,9 @@
 //     lane group served in the same cycle reads the same columns 8 rows further down, i.e. the same banks: a two-way
 //     conflict per read (SQ_LDS_BANK_CONFLICT = 2 x reads) that costs 1.4 % of the cycles.  Moving those rows by 32
 //     bytes (chunk index ^ 2 on bit 3 of the row) removes the conflicts but makes lanes fetch the halves of a
-//     64-byte segment out of order, which doubled the L2 misses and cost 4.5 % of the time: not done.
+//     64-byte segment out of order, which doubled the L2 misses and cost 4.5 % of the time; shifting every group of 8
+//     rows by 32 bytes at the destination of the loads instead removes them too and changes no timing (the reads
+//     have slack in their phase).  Neither is done.
 //   * NS slabs form a ring in LDS.
 //
 // Schedule: two groups of four waves (one wave of each group per SIMD) run half a slab apart, so that whenever

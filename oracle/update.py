@@ -23,6 +23,12 @@ notation, with these readings where the printed listing is garbled or silent:
 * grad_scale / sq_scale turn the sums S_id, S_sq into the mean gradient mu_t and
   nu_micro (1/B and 1/B when the cotangents are those of the summed loss).
 
+* Gradient clipping (Sec. 3.2.3 and App. C use it with threshold 1e-2 to stabilise MicroAdam, MicroAdamVar and
+  MicroAdamMSQ; its form is not spelled out): read as clipping by the global norm of the mean gradient,
+  kappa = min(1, c / ||mu_t||) with the norm over all parameters, applied to every per-example gradient alike -- so
+  the mean gradient scales by kappa and the per-example second moment by kappa^2 (``clip_factor``,
+  ``adam_family_step_clipped``).
+
 ``microsignsgd_step`` is Sec. 3.1: EMA o avg o sign; ``sign_family_step`` covers the three orderings of
 avg, EMA and sign that Sec. 3.1 compares (SignEMA, SignSGD, MicroSignSGD).
 """
@@ -86,6 +92,19 @@ def adam_family_step(theta, m, v, S_id, S_sq, variant: int, p: AdamParams):
     u_t = m_hat / (np.sqrt(v_hat + p.eps_root) + p.eps)
     theta_t = theta - p.lr * u_t - p.weight_decay * theta
     return theta_t, m_t, v_t
+
+
+def clip_factor(sum_sq_of_S_id: float, grad_scale: float, max_norm: float) -> float:
+    """kappa = min(1, max_norm / ||mu_t||), ||mu_t|| = |grad_scale| * sqrt(sum over all parameters of S_id^2)."""
+    norm = abs(grad_scale) * float(np.sqrt(sum_sq_of_S_id))
+    return 1.0 if norm <= max_norm else max_norm / norm
+
+
+def adam_family_step_clipped(theta, m, v, S_id, S_sq, variant: int, p: AdamParams, sum_sq_of_S_id: float, max_norm: float):
+    """Algorithm 1 on per-example gradients all multiplied by the global clipping factor."""
+    kappa = clip_factor(sum_sq_of_S_id, p.grad_scale, max_norm)
+    q = AdamParams(**{**p.__dict__, "grad_scale": p.grad_scale * kappa, "sq_scale": p.sq_scale * kappa * kappa})
+    return adam_family_step(theta, m, v, S_id, S_sq, variant, q)
 
 
 def microsignsgd_step(theta, m, S_sign, lr: float, beta: float, weight_decay: float, B: int,

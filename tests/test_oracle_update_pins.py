@@ -199,3 +199,32 @@ def test_sign_family_pins():
     _, m_micro = ou.sign_family_step(np.zeros(1), np.zeros(1), np.sign(per_example).sum(0), ou.MICROSIGNSGD, lr, beta, 0.0, 3, False, 1)
     _, m_sgd = ou.sign_family_step(np.zeros(1), np.zeros(1), per_example.sum(0), ou.SIGNSGD, lr, beta, 0.0, 3, False, 1)
     assert m_micro[0] < 0 < m_sgd[0]
+
+
+def test_clipping_is_the_library_global_norm_clip_and_acts_on_every_example():
+    """kappa scales the mean gradient exactly like torch's clip_grad_norm_ (up to its 1e-6 guard), leaves gradients
+    under the threshold alone, and the clipped MicroAdam step equals the plain step on per-example gradients that
+    were all multiplied by kappa."""
+    rng = np.random.default_rng(7)
+    n, B = 300, 6
+    g = rng.standard_normal((B, n)) * 0.3
+    S_id, S_sq = g.sum(0), (g * g).sum(0)
+    mean = S_id / B
+    for max_norm in (0.5, 100.0):
+        kappa = ou.clip_factor(float((S_id ** 2).sum()), 1.0 / B, max_norm)
+        p = torch.nn.Parameter(torch.zeros(n, dtype=torch.float64))
+        p.grad = torch.tensor(mean.copy())
+        torch.nn.utils.clip_grad_norm_([p], max_norm)
+        np.testing.assert_allclose(kappa * mean, p.grad.numpy(), rtol=2e-6)
+        if max_norm > 10:
+            assert kappa == 1.0
+        else:
+            assert kappa < 1.0 and abs(np.linalg.norm(kappa * mean) - max_norm) < 1e-12
+        prm = ou.AdamParams(lr=1e-2, beta1=0.9, beta2=0.95, eps=1e-8, grad_scale=1.0 / B, sq_scale=1.0 / B, step=2, B=B)
+        th, m, v = rng.standard_normal(n), rng.standard_normal(n) * 0.1, np.abs(rng.standard_normal(n)) * 0.01
+        for variant in (ou.ADAM, ou.MICROADAM, ou.MICROADAM_VAR, ou.MICROADAM_MSQ):
+            a = ou.adam_family_step_clipped(th, m, v, S_id, S_sq, variant, prm, float((S_id ** 2).sum()), max_norm)
+            gk = kappa * g
+            b = ou.adam_family_step(th, m, v, gk.sum(0), (gk * gk).sum(0), variant, prm)
+            for x, y in zip(a, b):
+                np.testing.assert_allclose(x, y, rtol=1e-12, atol=1e-15)

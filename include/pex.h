@@ -217,6 +217,24 @@ pex_status pex_sign_update(float *theta, float *m, const float *S, int64_t n, pe
                            pex_stream_t stream);
 
 /*
+ * Gradient clipping by the global norm (Sec. 3.2.3 and App. C stabilise MicroAdam, MicroAdamVar and MicroAdamMSQ with
+ * it; read as: every per-example gradient is multiplied by kappa = min(1, max_norm / ||mu_t||), the norm of the mean
+ * gradient taken over all parameters of the model).
+ * pex_sum_squares: acc[0] = (accumulate ? acc[0] : 0) + sum_i x[i]^2 in fp64, summed in a fixed order; call it on the
+ *   S_id of every layer (accumulate = 0 for the first) to get ||sum_b g_b||^2.  x: fp32 device array of n elements,
+ *   16-byte aligned; acc: one double in device memory; workspace: pex_sum_squares_workspace_bytes(n) bytes.
+ * pex_adam_update_clipped: pex_adam_update with grad_scale multiplied by kappa and sq_scale by kappa^2, where
+ *   kappa = min(1, max_norm / (|grad_scale| * sqrt(*sum_sq))) is formed on the device from the accumulated sum (no host
+ *   synchronisation).  sum_sq: one double in device memory; max_norm > 0.
+ */
+size_t pex_sum_squares_workspace_bytes(int64_t n);
+pex_status pex_sum_squares(const float *x, int64_t n, double *acc, int32_t accumulate, void *workspace,
+                           size_t workspace_bytes, pex_stream_t stream);
+pex_status pex_adam_update_clipped(float *theta, float *m, float *v, const float *S_id, const float *S_sq, int64_t n,
+                                   pex_adam_variant variant, const pex_adam_params *p /* host */, const double *sum_sq,
+                                   float max_norm, pex_stream_t stream);
+
+/*
  * pex_moment_track -- on-line measurement of mu^2 and sigma^2 (Sec. 3.2.2, Eq. (musq_sigsq_est)), in place over n
  * parameters.  Two EMAs with the optimizer's beta2 follow nu_adam and nu_micro:
  *   mu_t = grad_scale*S_id ;  ema_adam  <- beta2*ema_adam  + (1-beta2)*mu_t^2

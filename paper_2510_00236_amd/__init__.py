@@ -36,7 +36,8 @@ EXPORTS = ("pex_status_string", "pex_version", "pex_stat_workspace_bytes", "pex_
            "pex_stat_power_workspace_bytes", "pex_stat_power",
            "pex_token_sq_workspace_bytes", "pex_token_sq", "pex_adam_update", "pex_signsgd_update",
            "pex_moment_track_workspace_bytes", "pex_moment_track", "pex_embed_stat_workspace_bytes", "pex_embed_stat",
-           "pex_mfma_probe_operand_bytes", "pex_mfma_probe_sink_floats", "pex_mfma_probe")
+           "pex_mfma_probe_operand_bytes", "pex_mfma_probe_sink_floats", "pex_mfma_probe",
+           "pex_sum_squares_workspace_bytes", "pex_sum_squares", "pex_adam_update_clipped")
 
 
 class PexError(RuntimeError):
@@ -121,6 +122,12 @@ def lib() -> ctypes.CDLL:
         L.pex_mfma_probe_sink_floats.restype = sz
         L.pex_mfma_probe.argtypes = [p, i32, i32, p, ctypes.POINTER(ctypes.c_double), p]
         L.pex_mfma_probe.restype = ctypes.c_int
+        L.pex_sum_squares_workspace_bytes.argtypes = [i64]
+        L.pex_sum_squares_workspace_bytes.restype = sz
+        L.pex_sum_squares.argtypes = [p, i64, p, i32, p, sz, p]
+        L.pex_sum_squares.restype = ctypes.c_int
+        L.pex_adam_update_clipped.argtypes = [p, p, p, p, p, i64, ctypes.c_int, ctypes.POINTER(AdamParams), p, f, p]
+        L.pex_adam_update_clipped.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -453,3 +460,31 @@ def pex_mfma_probe(operands, workgroups, iters, sink=None, stream=None):
     _check(lib().pex_mfma_probe(_dev(operands, "operands"), int(workgroups), int(iters), _dev(sink, "sink"), ctypes.byref(flop),
                                 _stream(stream)))
     return flop.value, sink
+
+
+def pex_sum_squares_workspace_bytes(n) -> int:
+    return int(lib().pex_sum_squares_workspace_bytes(n))
+
+
+def pex_sum_squares(x, acc=None, accumulate=False, workspace=None, stream=None):
+    """acc[0] (+)= sum of x^2 in fp64 (one double on the GPU): the squared global gradient norm, layer by layer."""
+    import torch
+    n = x.numel()
+    if acc is None:
+        acc = torch.zeros(1, dtype=torch.float64, device=x.device)
+    ws, wptr, wbytes = _workspace(pex_sum_squares_workspace_bytes(n), x, workspace)
+    _check(lib().pex_sum_squares(_dev(x, "x"), n, _dev(acc, "acc"), int(bool(accumulate)), wptr, wbytes, _stream(stream)))
+    return acc
+
+
+def pex_adam_update_clipped(theta, m, v, S_id, S_sq, variant, params: AdamParams, sum_sq, max_norm, stream=None):
+    """pex_adam_update with every per-example gradient multiplied by kappa = min(1, max_norm / ||mean gradient||);
+    ``sum_sq`` is the double on the GPU that pex_sum_squares accumulated over the S_id of all layers."""
+    code = VARIANT.get(variant, variant)
+    n = theta.numel()
+    for name, t in (("m", m), ("v", v), ("S_id", S_id)) + ((("S_sq", S_sq),) if S_sq is not None else ()):
+        if t.numel() != n:
+            raise ValueError(f"{name} has {t.numel()} elements, theta has {n}")
+    _check(lib().pex_adam_update_clipped(_dev(theta, "theta"), _dev(m, "m"), _dev(v, "v"), _dev(S_id, "S_id"),
+                                         _dev(S_sq, "S_sq") if S_sq is not None else None, n, code, ctypes.byref(params),
+                                         _dev(sum_sq, "sum_sq"), float(max_norm), _stream(stream)))

@@ -430,6 +430,36 @@ pex_status pex_embed_stat(const void* ids, int32_t ids_bytes, const void* G, int
                : PEX_ERR_HIP;
 }
 
+size_t pex_sum_squares_workspace_bytes(int64_t n) { return n < 1 ? 0 : sum_squares_workspace(n); }
+
+pex_status pex_sum_squares(const float* x, int64_t n, double* acc, int32_t accumulate, void* workspace, size_t workspace_bytes,
+                           pex_stream_t stream)
+{
+    if (!x || !acc) return PEX_ERR_NULL;
+    if (n < 1) return PEX_ERR_SHAPE;
+    if (((uintptr_t)x & 15u) || ((uintptr_t)acc & 7u)) return PEX_ERR_ALIGN;
+    if (!workspace || workspace_bytes < sum_squares_workspace(n)) return PEX_ERR_WORKSPACE;
+    if ((uintptr_t)workspace & 15u) return PEX_ERR_ALIGN;
+    return launch_sum_squares(x, n, acc, accumulate, (double*)workspace, (hipStream_t)stream) == hipSuccess ? PEX_OK : PEX_ERR_HIP;
+}
+
+pex_status pex_adam_update_clipped(float* theta, float* m, float* v, const float* S_id, const float* S_sq, int64_t n,
+                                   pex_adam_variant variant, const pex_adam_params* p, const double* sum_sq, float max_norm,
+                                   pex_stream_t stream)
+{
+    if (!theta || !m || !v || !S_id || !p || !sum_sq) return PEX_ERR_NULL;
+    if (variant != PEX_ADAM && variant != PEX_MICROADAM && variant != PEX_MICROADAM_VAR && variant != PEX_MICROADAM_MSQ)
+        return PEX_ERR_PHI;
+    if (variant != PEX_ADAM && !S_sq) return PEX_ERR_NULL;
+    if (n < 1 || p->step < 1 || p->B < 1 || !(max_norm > 0.f)) return PEX_ERR_SHAPE;
+    if ((variant == PEX_MICROADAM_VAR || variant == PEX_MICROADAM_MSQ) && p->B < 2) return PEX_ERR_SHAPE;
+    if (((uintptr_t)theta | (uintptr_t)m | (uintptr_t)v | (uintptr_t)S_id | (uintptr_t)S_sq) & 15u) return PEX_ERR_ALIGN;
+    if ((uintptr_t)sum_sq & 7u) return PEX_ERR_ALIGN;
+    return launch_adam_update(theta, m, v, S_id, S_sq, n, variant, *p, (hipStream_t)stream, sum_sq, max_norm) == hipSuccess
+               ? PEX_OK
+               : PEX_ERR_HIP;
+}
+
 size_t pex_mfma_probe_operand_bytes(void) { return probe_operand_bytes(); }
 size_t pex_mfma_probe_sink_floats(int32_t workgroups) { return workgroups < 1 ? 0 : probe_sink_floats(workgroups); }
 

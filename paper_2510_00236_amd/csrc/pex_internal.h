@@ -82,7 +82,10 @@ hipError_t launch_vec_stat(const void* A, const void* C, int64_t B, int64_t T, i
 hipError_t launch_reduce_partials(const float* partial, int nsplit, int64_t n, float* S, hipStream_t stream);
 
 hipError_t launch_adam_update(float* theta, float* m, float* v, const float* S_id, const float* S_sq, int64_t n,
-                              pex_adam_variant variant, const pex_adam_params& p, hipStream_t stream);
+                              pex_adam_variant variant, const pex_adam_params& p, hipStream_t stream,
+                              const double* clip_sumsq = nullptr, float max_norm = 0.f);
+size_t sum_squares_workspace(int64_t n);
+hipError_t launch_sum_squares(const float* x, int64_t n, double* acc, int accumulate, double* partial, hipStream_t stream);
 hipError_t launch_sign_update(float* theta, float* m, const float* S, int64_t n, pex_sign_variant variant, float lr, float beta,
                               float weight_decay, int32_t B, int32_t debias, int64_t step, hipStream_t stream);
 

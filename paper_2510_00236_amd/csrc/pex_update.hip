@@ -36,11 +36,22 @@ __device__ __forceinline__ void adam_one(float& th, float& m, float& v, float si
     th = th - k.lr * u - k.wd * th;
 }
 
+// clip_sumsq != nullptr: gradient clipping by the global norm (Sec. 3.2.3, App. C).  *clip_sumsq is the sum of S_id^2
+// over all parameters of the model (device memory, written by sum_squares_kernel); every per-example gradient is
+// multiplied by kappa = min(1, max_norm / (|grad_scale| * sqrt(*clip_sumsq))), i.e. the mean gradient by kappa and
+// the per-example second moment by kappa^2.
 template <int VARIANT>
 __global__ __launch_bounds__(256) void adam_update_kernel(float* __restrict__ theta, float* __restrict__ m,
                                                           float* __restrict__ v, const float* __restrict__ S_id,
-                                                          const float* __restrict__ S_sq, int64_t n, AdamConsts k)
+                                                          const float* __restrict__ S_sq, int64_t n, AdamConsts k,
+                                                          const double* __restrict__ clip_sumsq, float max_norm)
 {
+    if (clip_sumsq) {
+        const double norm = fabs((double)k.gs) * sqrt(*clip_sumsq);
+        const float kappa = norm > (double)max_norm ? (float)((double)max_norm / norm) : 1.0f;
+        k.gs *= kappa;
+        k.qs *= kappa * kappa;
+    }
     const int64_t n4 = n / 4;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -183,6 +194,44 @@ __global__ __launch_bounds__(1024) void moment_finalize_kernel(const double* __r
     }
 }
 
+// acc[0] (+)= sum of x^2, squares and sums in fp64, fixed order (per thread, wave butterfly, workgroup, then one
+// workgroup over the partials): the global gradient norm the clipping needs, reproducible bit for bit.
+__global__ __launch_bounds__(256) void sum_squares_kernel(const float* __restrict__ x, int64_t n, double* __restrict__ partial)
+{
+    const int64_t n4 = n / 4;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const float4* x4 = reinterpret_cast<const float4*>(x);
+    double s = 0.0;
+    for (int64_t e = gid; e < n4; e += stride) {
+        const float4 a = x4[e];
+        s += ((double)a.x * a.x + (double)a.y * a.y) + ((double)a.z * a.z + (double)a.w * a.w);
+    }
+    for (int64_t e = n4 * 4 + gid; e < n; e += stride) s += (double)x[e] * x[e];
+    __shared__ double red[4];
+    s = wave_sum(s);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) partial[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+__global__ __launch_bounds__(1024) void sum_squares_finalize_kernel(const double* __restrict__ partial, int nparts, int accumulate,
+                                                                    double* __restrict__ acc)
+{
+    double s = 0.0;
+    for (int i = threadIdx.x; i < nparts; i += 1024) s += partial[i];
+    __shared__ double red[16];
+    s = wave_sum(s);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) t += red[w];
+        acc[0] = accumulate ? acc[0] + t : t;
+    }
+}
+
 inline unsigned update_grid(int64_t n)
 {
     int64_t blocks = (n / 4 + 255) / 256;
@@ -194,7 +243,8 @@ inline unsigned update_grid(int64_t n)
 }  // namespace
 
 hipError_t launch_adam_update(float* theta, float* m, float* v, const float* S_id, const float* S_sq, int64_t n,
-                              pex_adam_variant variant, const pex_adam_params& p, hipStream_t stream)
+                              pex_adam_variant variant, const pex_adam_params& p, hipStream_t stream, const double* clip_sumsq,
+                              float max_norm)
 {
     AdamConsts k;
     k.beta1 = p.beta1; k.one_m_beta1 = 1.f - p.beta1;
@@ -207,11 +257,23 @@ hipError_t launch_adam_update(float* theta, float* m, float* v, const float* S_i
     k.c_est = p.B > 1 ? (float)(1.0 / (1.0 - 1.0 / (double)p.B)) : 0.f;
     const dim3 grid(update_grid(n)), block(256);
     switch (variant) {
-    case PEX_ADAM: adam_update_kernel<PEX_ADAM><<<grid, block, 0, stream>>>(theta, m, v, S_id, S_sq, n, k); break;
-    case PEX_MICROADAM: adam_update_kernel<PEX_MICROADAM><<<grid, block, 0, stream>>>(theta, m, v, S_id, S_sq, n, k); break;
-    case PEX_MICROADAM_VAR: adam_update_kernel<PEX_MICROADAM_VAR><<<grid, block, 0, stream>>>(theta, m, v, S_id, S_sq, n, k); break;
-    case PEX_MICROADAM_MSQ: adam_update_kernel<PEX_MICROADAM_MSQ><<<grid, block, 0, stream>>>(theta, m, v, S_id, S_sq, n, k); break;
+    case PEX_ADAM: adam_update_kernel<PEX_ADAM><<<grid, block, 0, stream>>>(theta, m, v, S_id, S_sq, n, k, clip_sumsq, max_norm); break;
+    case PEX_MICROADAM: adam_update_kernel<PEX_MICROADAM><<<grid, block, 0, stream>>>(theta, m, v, S_id, S_sq, n, k, clip_sumsq, max_norm); break;
+    case PEX_MICROADAM_VAR: adam_update_kernel<PEX_MICROADAM_VAR><<<grid, block, 0, stream>>>(theta, m, v, S_id, S_sq, n, k, clip_sumsq, max_norm); break;
+    case PEX_MICROADAM_MSQ: adam_update_kernel<PEX_MICROADAM_MSQ><<<grid, block, 0, stream>>>(theta, m, v, S_id, S_sq, n, k, clip_sumsq, max_norm); break;
     }
+    return hipGetLastError();
+}
+
+size_t sum_squares_workspace(int64_t n) { return (size_t)update_grid(n) * sizeof(double); }
+
+hipError_t launch_sum_squares(const float* x, int64_t n, double* acc, int accumulate, double* partial, hipStream_t stream)
+{
+    const unsigned grid = update_grid(n);
+    sum_squares_kernel<<<dim3(grid), dim3(256), 0, stream>>>(x, n, partial);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    sum_squares_finalize_kernel<<<dim3(1), dim3(1024), 0, stream>>>(partial, (int)grid, accumulate, acc);
     return hipGetLastError();
 }
 

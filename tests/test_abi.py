@@ -140,6 +140,18 @@ def test_host_validation_launches_nothing():
     assert L.pex_embed_stat(ids, 8, Gp, 4, 16, 100, 64, 1, 7, Sp, Sp, Sp, wsp, need - 1, None) == 6
     assert L.pex_embed_stat(ids, 8, Gp, 4, 16, 100, 64, 1, 7, Sp, Sp, Sp, None, 0, None) == 6
 
+    ssb = pex.pex_sum_squares_workspace_bytes(16)
+    assert 0 < ssb <= 1 << 16 and pex.pex_sum_squares_workspace_bytes(1 << 30) <= 1 << 16
+    acc = 0x6100
+    assert L.pex_sum_squares(None, 16, acc, 0, wsp, ssb, None) == 1
+    assert L.pex_sum_squares(a, 0, acc, 0, wsp, ssb, None) == 2
+    assert L.pex_sum_squares(a, 16, acc + 4, 0, wsp, ssb, None) == 5
+    assert L.pex_sum_squares(a, 16, acc, 0, wsp, ssb - 1, None) == 6
+    assert L.pex_adam_update_clipped(th, m, v, a, q, 16, 1, ctypes.byref(p), None, 1.0, None) == 1
+    assert L.pex_adam_update_clipped(th, m, v, a, q, 16, 1, ctypes.byref(p), acc, 0.0, None) == 2      # max_norm must be positive
+    assert L.pex_adam_update_clipped(th, m, v, a, q, 16, 1, ctypes.byref(p), acc + 4, 1.0, None) == 5
+    assert L.pex_adam_update_clipped(th, m, v, a, q, 16, 7, ctypes.byref(p), acc, 1.0, None) == 4
+
     mp = pex.MomentParams(beta2=0.95, grad_scale=0.25, sq_scale=0.25, B=4, debias=1, step=1)
     wsb = pex.pex_moment_track_workspace_bytes(16)
     assert 0 < wsb <= 1 << 17 and pex.pex_moment_track_workspace_bytes(1 << 30) <= 1 << 17

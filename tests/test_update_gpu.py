@@ -193,3 +193,48 @@ def test_moment_tracking_recovers_planted_moments():
     # entries of X_b^T G_b are sums of T products of independent unit normals: mean 0, variance T
     assert abs(sums[1] - T) < 0.02 * T
     assert abs(sums[0]) < 0.1 * T / B            # nu_adam itself would sit at T / B
+
+
+@pytest.mark.parametrize("n", [1 << 20, 1000003, 5])
+def test_sum_of_squares_and_clipped_updates_match_oracle(n):
+    """Global-norm clipping without a host round trip: the norm accumulates on the GPU over two 'layers', the update
+    reads it there.  Thresholds on both sides of the actual norm."""
+    rng = np.random.default_rng(n)
+    B = 8
+    S_id_t, S_sq_t = _stats(n, B, seed=n % 1000)
+    parts = [S_id_t.numpy(), rng.standard_normal(n // 2 + 3).astype(np.float32) * 0.05]
+    acc = pex.pex_sum_squares(torch.from_numpy(parts[0]).to(DEV))
+    acc = pex.pex_sum_squares(torch.from_numpy(parts[1]).to(DEV), acc=acc, accumulate=True)
+    ref_sumsq = float((parts[0].astype(np.float64) ** 2).sum() + (parts[1].astype(np.float64) ** 2).sum())
+    assert abs(float(acc.cpu()[0]) - ref_sumsq) <= 1e-12 * ref_sumsq
+    again = pex.pex_sum_squares(torch.from_numpy(parts[0]).to(DEV))
+    again = pex.pex_sum_squares(torch.from_numpy(parts[1]).to(DEV), acc=again, accumulate=True)
+    assert torch.equal(acc, again)                       # fixed summation order
+    S_id, S_sq = parts[0], S_sq_t.numpy()
+    norm = np.sqrt(ref_sumsq) / B
+    for max_norm in (0.25 * norm, 4.0 * norm):
+        for name, code in VARIANTS:
+            theta0 = rng.standard_normal(n).astype(np.float32) * 0.02
+            m0 = rng.standard_normal(n).astype(np.float32) * 0.01
+            v0 = (rng.standard_normal(n).astype(np.float32) ** 2) * 0.01
+            th, m, v = (torch.from_numpy(x.copy()).to(DEV) for x in (theta0, m0, v0))
+            prm = pex.AdamParams(lr=1e-2, beta1=0.9, beta2=0.95, eps=1e-8, eps_root=0.0, weight_decay=0.0,
+                                 grad_scale=1.0 / B, sq_scale=1.0 / B, step=3, B=B)
+            pex.pex_adam_update_clipped(th, m, v, torch.from_numpy(S_id).to(DEV), torch.from_numpy(S_sq).to(DEV), name, prm,
+                                        acc, float(max_norm))
+            op = ou.AdamParams(lr=float(np.float32(1e-2)), beta1=float(np.float32(0.9)), beta2=float(np.float32(0.95)),
+                               eps=float(np.float32(1e-8)), grad_scale=float(np.float32(1.0 / B)),
+                               sq_scale=float(np.float32(1.0 / B)), step=3, B=B)
+            rt, rm, rv = ou.adam_family_step_clipped(theta0, m0, v0, S_id, S_sq, code, op, ref_sumsq, float(np.float32(max_norm)))
+            np.testing.assert_allclose(m.cpu().double().numpy(), rm, rtol=3e-6, atol=1e-9)
+            np.testing.assert_allclose(v.cpu().double().numpy(), rv, rtol=3e-6, atol=1e-10)
+            ok = np.abs(rv) / (1 - 0.95 ** 3) >= 1e-3 * np.abs(rv).max() / (1 - 0.95 ** 3)
+            d_gpu, d_ref = th.cpu().double().numpy() - theta0, rt - theta0
+            np.testing.assert_allclose(d_gpu[ok], d_ref[ok], rtol=2e-4, atol=2e-8)      # theta is fp32: one ulp of 0.1 is 7e-9
+    # under the threshold the clipped call is the plain call, bit for bit
+    th1, m1, v1 = (torch.from_numpy(x.copy()).to(DEV) for x in (theta0, m0, v0))
+    th2, m2, v2 = (torch.from_numpy(x.copy()).to(DEV) for x in (theta0, m0, v0))
+    Sd, Sq = torch.from_numpy(S_id).to(DEV), torch.from_numpy(S_sq).to(DEV)
+    pex.pex_adam_update_clipped(th1, m1, v1, Sd, Sq, "microadam", prm, acc, float(4.0 * norm))
+    pex.pex_adam_update(th2, m2, v2, Sd, Sq, "microadam", prm)
+    assert torch.equal(th1, th2) and torch.equal(m1, m2) and torch.equal(v1, v2)

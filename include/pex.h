@@ -67,7 +67,8 @@ int pex_version(void);
  *                               same (B,T,din,dout,dt,phi); may be NULL when that query returns 0.  It
  *                               holds partial sums over groups of examples when the batch is split over
  *                               workgroups; it never holds a per-example gradient, and its size is at most
- *                               a small multiple of din*dout*4, independent of B.
+ *                               32 * din*dout*4 bytes, whatever B (reached by small layers only, where
+ *                               many groups are needed to occupy the chip; none at the 1B-scale shapes).
  *   The contraction over T of one example is never split across workgroups (phi is applied to the complete
  *   sum over the sequence), the sum over b is taken in a fixed order.
  *   Any B,T,din,dout >= 1 is accepted (B*T, din, dout each < 2^31).

@@ -39,7 +39,7 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
     tiles = ((din + bm - 1) / bm) * ((dout + bn - 1) / bn);
     const int64_t slab = 64;
     units = per_example ? B : (B * T + slab - 1) / slab;
-    const int max_split = env_int("PEX_MAX_SPLIT", 16);
+    const int max_split = env_int("PEX_MAX_SPLIT", 32);
     int64_t nsplit = 1, per = units;
     if (p.kernel != 1) {
         nsplit = (target + tiles - 1) / tiles;

@@ -277,3 +277,11 @@ def test_mfma_probe_runs_and_counts_its_flop():
         pex.pex_mfma_probe(ops[:100], 4, 10)
     with pytest.raises(pex.PexError):
         pex.pex_mfma_probe(ops, 0, 10)
+
+
+@pytest.mark.parametrize("B,T,din,dout,dtype", [(1, 100_000, 64, 96, "bf16"), (2, 40_000, 64, 64, "f32"), (3, 33_333, 40, 72, "bf16")])
+def test_long_sequences(B, T, din, dout, dtype):
+    """Contractions over tens of thousands of tokens per example: thousands of slabs through the LDS ring, fp32
+    accumulation error still far inside the bars, the batch split (plain contractions split the flattened rows)."""
+    X, G = si.custom(B, T, din, dout, dtype=dtype, seed=T)
+    _compare(X, G, dtype, f"B{B} T{T} {din}x{dout} {dtype}", elementwise=(B >= 3))

@@ -228,7 +228,7 @@ def main() -> int:
         el = 2                                     # bytes per bf16 element
 
         def timed(fn, reps=5):
-            for _ in range(3):
+            for _ in range(10):         # fresh buffers: the first launches on new memory run slower
                 fn()
             torch.cuda.synchronize()
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

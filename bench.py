@@ -122,6 +122,7 @@ def main() -> int:
     id_events = []          # (start, stop) around every launch of the plain contraction by pex_stat(identity)
     sq_events = []          # ... of the phi = square contraction
     upd_events = []
+    sgn_events = []         # ... of the MicroSignSGD update
 
     def step(t: int, record: bool):
         for L in layers:
@@ -149,7 +150,13 @@ def main() -> int:
                 u1.record()
                 upd_events.append((u0, u1, w))
             pex.pex_stat(L["X"], L["G"], "sign", S=L["S_sg"], workspace=L["ws"])
+            if record:
+                g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                g0.record()
             pex.pex_signsgd_update(L["theta_s"], L["m_s"], L["S_sg"].view(-1), 3.47e-3, 0.9, 0.0, w.B, False, t)
+            if record:
+                g1.record()
+                sgn_events.append((g0, g1, w))
             pex.pex_token_sq(L["X"], L["G"], S=L["S_tk"], workspace=L["ws"])
 
     for t in range(1, args.warmup + 1):
@@ -292,6 +299,12 @@ def main() -> int:
                        "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(upd_gbs / PEAK_HBM_GBS, 4),
                        "avg_launch_ms": round(sum(upd_ms) / len(upd_ms), 4)}
 
+    sgn_ms = [a.elapsed_time(b) for a, b, _ in sgn_events]
+    sgn_gbs = (sum(20.0 * w.din * w.dout for _, _, w in sgn_events) / len(sgn_events)) / (sum(sgn_ms) / len(sgn_ms) * 1e-3) / 1e9
+    sign_update_roofline = {"bound": "hbm", "kernel": "signsgd_update_kernel<microsignsgd>", "achieved": round(sgn_gbs, 1),
+                            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(sgn_gbs / PEAK_HBM_GBS, 4),
+                            "avg_launch_ms": round(sum(sgn_ms) / len(sgn_ms), 4)}
+
     # ---- CPU baseline: the fp64 oracle as it stands, on a bounded sample of the first layer
     cpu = None
     if not args.no_cpu_baseline:
@@ -330,6 +343,7 @@ def main() -> int:
                    "step": "per layer: pex_stat identity+square -> MicroAdam update; pex_stat sign -> MicroSignSGD update; pex_token_sq",
                    "flop_per_step": flop_per_step, "seed": args.seed},
         "roofline": roofline, "square_roofline": square_roofline, "update_roofline": update_roofline,
+        "sign_update_roofline": sign_update_roofline,
         "mfma_only_ceiling": None if ceiling is None else {
             "achieved": round(ceiling, 1), "unit": "TFLOP/s", "frac_of_peak": round(ceiling / PEAK_BF16_TFLOPS, 4),
             "kernel": "mfma_probe_kernel: nothing but v_mfma_f32_16x16x32_bf16, 8 waves on each of "

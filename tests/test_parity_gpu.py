@@ -285,3 +285,16 @@ def test_long_sequences(B, T, din, dout, dtype):
     accumulation error still far inside the bars, the batch split (plain contractions split the flattened rows)."""
     X, G = si.custom(B, T, din, dout, dtype=dtype, seed=T)
     _compare(X, G, dtype, f"B{B} T{T} {din}x{dout} {dtype}", elementwise=(B >= 3))
+
+
+@pytest.mark.parametrize("B,T,din,dout,dtype", [(5, 77, 520, 264, "bf16"), (3, 50, 132, 68, "f32"), (7, 33, 256, 128, "bf16")])
+def test_simt_kernel_on_shapes_the_mfma_kernels_normally_take(monkeypatch, B, T, din, dout, dtype):
+    """PEX_FORCE_GENERIC=1 routes every call through the SIMT kernel: the two device paths agree with the oracle, and
+    sign counts agree with each other exactly outside the ambiguity band."""
+    X, G = si.custom(B, T, din, dout, dtype=dtype, seed=B * 1000 + T)
+    mfma = _run_all(X, G)
+    monkeypatch.setenv("PEX_FORCE_GENERIC", "1")
+    got, st = _compare(X, G, dtype, f"SIMT B{B} T{T} {din}x{dout} {dtype}", elementwise=(B >= 3))
+    monkeypatch.delenv("PEX_FORCE_GENERIC")
+    assert np.abs(got["identity"] - mfma["identity"]).max() <= 2e-5 * np.abs(st.S_id).max()
+    assert (np.abs(got["sign"] - mfma["sign"]) <= 2 * st.amb).all()

@@ -85,3 +85,22 @@ def test_full_size_shared_contraction_weighted_and_power(name):
     # the norms cover every entry; the total of the square statistic is the same number by another kernel
     tot = float(multi["square"].double().sum())
     assert abs(float(N.double().sum()) - tot) <= 1e-5 * tot
+
+
+def test_full_size_fp32_inputs_sampled():
+    """fp32 inputs at a transformer-layer size (B=8, T=1024, 1024 x 4096) on the fp32 MFMA kernel, 1e-4 bar."""
+    B, T, din, dout = 8, 1024, 1024, 4096
+    X, G = si.custom(B, T, din, dout, dtype="f32", seed=4)
+    Xd, Gd = X.to(DEV), G.to(DEV)
+    got = {phi: pex.pex_stat(Xd, Gd, phi) for phi in ("identity", "square", "sign")}
+    got["token_sq"] = pex.pex_token_sq(Xd, Gd)
+    torch.cuda.synchronize()
+    ii, jj = _sample_positions(din, dout, 2000, seed=5)
+    Xn, Gn = si.widen(X), si.widen(G)
+    st = oracle.stat_at(Xn, Gn, ii, jj)
+    tok = oracle.token_sq_at(Xn, Gn, ii, jj)
+    pick = lambda t: t[torch.as_tensor(ii, device=DEV), torch.as_tensor(jj, device=DEV)].cpu().numpy().astype(np.float64)
+    assert_real_stat(pick(got["identity"]), st.S_id, "f32", "fp32 identity", elementwise=False)
+    assert_real_stat(pick(got["square"]), st.S_sq, "f32", "fp32 square", elementwise=True)
+    assert_sign_stat(pick(got["sign"]), st.S_sign, st.amb, "fp32 sign")
+    assert_real_stat(pick(got["token_sq"]), tok, "f32", "fp32 token_sq", elementwise=True)

@@ -49,7 +49,18 @@
 // refills the buffer of slab h-2 with slab h+NS-2, i.e. its loads run one slab behind.  Every wave makes sure its
 // part of slab g+1 has landed before the barrier that ends phase 2g+1.  Steady state is branch-free: loads past
 // the end of the range carry an empty descriptor and write zeros into a buffer nobody reads.
+//
+// Plain contractions (phi = identity, the pre-squared per-token square, split partial sums) over long ranges run on a
+// second kernel, stat_bf16_quad_kernel: four waves, one per SIMD, each with a 128 x 128 register tile (256 accumulator
+// registers, which only a wave that has its SIMD's register file to itself can hold).  A wave then reads 16 fragments
+// per 64 MFMAs instead of 12 per 32: a third less LDS traffic per FLOP.  With realistic operand values the chip is
+// bound by power, not by issue slots (all-zero inputs run 30 % faster on either kernel), and the lower energy per FLOP
+// is worth 5-8 % although nothing hides a wave's own LDS, load and scalar instructions: with one wave per SIMD every
+// instruction that is not an MFMA costs about four cycles of MFMA time (measured: 1024 + 4 x 60 cycles per slab), so
+// that kernel is written to issue as few of them as possible (see there).
 #include <cstdlib>
+#include <type_traits>
+#include <utility>
 
 #include "pex_internal.h"
 
@@ -542,6 +553,284 @@ hipError_t launch_one(const uint16_t* X, const uint16_t* G, int64_t B, int64_t T
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// Four waves, one per SIMD, 128 x 128 per wave: the kernel of plain contractions over long ranges.
+//
+// Same tile, slabs, swizzle, fragment reads and zero-filling descriptors as above; what differs is the schedule.
+// There is no second wave on a SIMD to hide anything behind, so a wave interleaves everything itself: iteration g
+// issues the 64 MFMAs of slab g from one set of fragment registers and, between them, the 32 fragment reads of slab
+// g+1 into the other set and its 8 loads of slab g+NS-1, whose ring buffer held slab g-1 (every wave's MFMAs of slab
+// g-1 came before the barrier that ended iteration g-1, and they had waited for that slab's fragments).  One
+// barrier per slab: before it a wave makes sure its part of slab g+2 has landed.
+// Every instruction between two MFMAs costs MFMA time here, so there are as few as can be:
+//   * the loop is unrolled over a whole period of (fragment set, ring buffer), which turns every LDS address into
+//     lane base + immediate;
+//   * the four loads of an operand share one write of M0 (the LDS base): load n adds n KiB through its instruction
+//     offset, which moves the LDS address and the global address alike, so lane offsets are lowered by n KiB -- and,
+//     to keep them non-negative, raised by 3 KiB against a descriptor base 3 KiB lower (nothing below the true base
+//     is touched: every effective offset is >= 3 KiB, and a range of 3 KiB or less reads as empty);
+//   * the descriptors are kept in scalar registers and only moved on: a slab is full, the last one, or past the end.
+constexpr int QUAD_NS = 5;
+struct QuadTile {
+    static constexpr int BM = 256, BN = 256, WM = 128, WN = 128, BK = 32, NS = QUAD_NS;
+    static constexpr int FM = WM / 16, FN = WN / 16, NWAVES = 4, NT = NWAVES * 64;
+    static constexpr int XROW = BM * 2, GROW = BN * 2, X_BYTES = BK * XROW, G_BYTES = BK * GROW, STAGE = X_BYTES + G_BYTES;
+    static constexpr int LDS_BYTES = NS * STAGE;
+    static constexpr int NXI = X_BYTES / 1024 / NWAVES, NGI = G_BYTES / 1024 / NWAVES, LPS = NXI + NGI;
+    static constexpr int RX = 1024 / XROW, RG = 1024 / GROW;
+    static constexpr int PERIOD = (NS % 2 == 0) ? NS : 2 * NS;     // iterations after which fragment set and buffers repeat
+    static constexpr int BIAS = (NXI > NGI ? NXI : NGI) * 1024 - 1024;
+    // after which MFMA of an iteration things are issued: fragment half k after MFMA 2k+1, load n after MFMA 4+7n
+    static constexpr int READ_FIRST = 1, READ_STEP = 2, LOAD_FIRST = 4, LOAD_STEP = 7, ADVANCE_AT = 60;
+    static_assert(LDS_BYTES <= 160 * 1024 && NS >= 4, "ring");
+    static_assert(NXI * 1024 <= 4096 && NGI * 1024 <= 4096, "instruction offsets are 12 bits");
+    static_assert(READ_FIRST + READ_STEP * (2 * (FM + FN) - 1) < FM * FN, "every fragment read has its MFMA");
+    static_assert(LOAD_FIRST >= 3 && LOAD_FIRST + LOAD_STEP * (LPS - 1) < ADVANCE_AT && ADVANCE_AT < FM * FN,
+                  "loads sit between the descriptor update and the move to the next slab");
+};
+
+// LDS base of a group of direct-to-LDS loads.  M0 must stay as it is until the group's last load: no instruction the
+// compiler generates for this kernel writes it.  A load may not follow the write directly; WAIT adds the wait state
+// where no other instruction sits between.
+template <int OFF, bool WAIT>
+__device__ __forceinline__ void dma_set_base(uint32_t sbase)
+{
+    if constexpr (WAIT) asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0" : : "s"(sbase), "n"(OFF) : "memory", "m0", "scc");
+    else asm volatile("s_add_u32 m0, %0, %1" : : "s"(sbase), "n"(OFF) : "memory", "m0", "scc");
+}
+// one load of the group: 1 KiB to LDS (base in M0) + IOFF + lane*16, from descriptor base + voff + IOFF
+template <int IOFF>
+__device__ __forceinline__ void dma_load_16_off(uint32_t voff, int4_t rsrc)
+{
+    asm volatile("buffer_load_dwordx4 %0, %1, 0 offen offset:%2 lds" : : "v"(voff), "s"(rsrc), "n"(IOFF) : "memory");
+}
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index is a constant expression
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// which fragment half (G fragments first, two halves each) is read after MFMA i of an iteration, which load is issued; -1: none
+constexpr int quad_read_slot(int i)
+{
+    const int k = (i - QuadTile::READ_FIRST) / QuadTile::READ_STEP;
+    return (i >= QuadTile::READ_FIRST && (i - QuadTile::READ_FIRST) % QuadTile::READ_STEP == 0 && k < 2 * (QuadTile::FM + QuadTile::FN)) ? k : -1;
+}
+constexpr int quad_load_slot(int i)
+{
+    const int n = (i - QuadTile::LOAD_FIRST) / QuadTile::LOAD_STEP;
+    return (i >= QuadTile::LOAD_FIRST && (i - QuadTile::LOAD_FIRST) % QuadTile::LOAD_STEP == 0 && n < QuadTile::LPS) ? n : -1;
+}
+
+__global__ __launch_bounds__(QuadTile::NT, 1) void stat_bf16_quad_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ G,
+                                                                         int64_t rows_total, int din, int dout, int64_t rows_per_split,
+                                                                         int tiles_m, int tiles_n, float* __restrict__ out)
+{
+    using TL = QuadTile;
+    constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK, NS = TL::NS, FM = TL::FM, FN = TL::FN;
+    constexpr int XROW = TL::XROW, GROW = TL::GROW, NXI = TL::NXI, NGI = TL::NGI, RX = TL::RX, RG = TL::RG, LPS = TL::LPS;
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+
+    int split, tm, tn;
+    map_workgroup(tiles_m, tiles_n, split, tm, tn);
+    const int i0 = tm * BM, j0 = tn * BN;
+    const int64_t row_begin = (int64_t)split * rows_per_split;
+    int64_t row_end = row_begin + rows_per_split;
+    if (row_end > rows_total) row_end = rows_total;
+    const int slen = (int)(row_end - row_begin);
+    const int total = (slen + BK - 1) / BK;
+    const int tid = threadIdx.x, lane = tid % 64;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void)lds;
+    const int wm = wave / 2, wn = wave % 2;
+
+    // ---- loader geometry: as in the eight-wave kernel (load q = wave*NXI + n fills slab rows q*RX ..), with the
+    // group bias and the instruction offset of load n taken out of the lane offset
+    uint32_t xoff[NXI], goff[NGI];
+#pragma unroll
+    for (int n = 0; n < NXI; ++n) {
+        const int q = wave * NXI + n, r = q * RX + lane / (XROW / 16), slot = lane % (XROW / 16);
+        const int c = slot ^ (4 * (r & 3));
+        xoff[n] = ((i0 + c * 8 < din) ? (uint32_t)(r * din + c * 8) * 2u : 0x80000000u) + (uint32_t)(TL::BIAS - n * 1024);
+    }
+#pragma unroll
+    for (int n = 0; n < NGI; ++n) {
+        const int q = wave * NGI + n, r = q * RG + lane / (GROW / 16), slot = lane % (GROW / 16);
+        const int c = slot ^ (4 * (r & 3));
+        goff[n] = ((j0 + c * 8 < dout) ? (uint32_t)(r * dout + c * 8) * 2u : 0x80000000u) + (uint32_t)(TL::BIAS - n * 1024);
+    }
+    const uint32_t wave_x = lds_base + (uint32_t)(wave * NXI * 1024);                  // this wave's part of a buffer
+    const uint32_t wave_g = lds_base + (uint32_t)(TL::X_BYTES + wave * NGI * 1024);
+
+    // ---- descriptors of the next slab to issue.  Base: the tile's first column of the slab's first row (minus the
+    // bias); range: up to the tile's last column of the slab's last valid row, i.e. rows * row bytes minus the bytes
+    // left of the tile (plus the bias).  A slab is full (BK rows), the last one of the range, or past the end (no
+    // rows: the range is at most the bias, so every lane reads zero).
+    const int xrow_bytes = din * 2, grow_bytes = dout * 2, xcut = i0 * 2 - TL::BIAS, gcut = j0 * 2 - TL::BIAS;
+    const int last_rows = slen - (total - 1) * BK;
+    const int xfull = BK * xrow_bytes, gfull = BK * grow_bytes, xlast = last_rows * xrow_bytes, glast = last_rows * grow_bytes;
+    uint64_t xptr = (uint64_t)(X + row_begin * din + i0) - TL::BIAS, gptr = (uint64_t)(G + row_begin * dout + j0) - TL::BIAS;
+    int left = total, xadv = 0, gadv = 0;          // slabs not yet issued; bytes the bases move after this one
+    int4_t rx, rg;
+    auto slab_rows = [&]() {
+        xadv = left > 1 ? xfull : (left == 1 ? xlast : 0);
+        gadv = left > 1 ? gfull : (left == 1 ? glast : 0);
+    };
+    auto slab_range = [&]() {
+        const int nx = xadv - xcut, ng = gadv - gcut;
+        rx = int4_t{(int)(uint32_t)xptr, (int)(uint32_t)(xptr >> 32), nx > 0 ? nx : 0, 0x00020000};
+        rg = int4_t{(int)(uint32_t)gptr, (int)(uint32_t)(gptr >> 32), ng > 0 ? ng : 0, 0x00020000};
+    };
+    auto slab_advance = [&]() {
+        xptr += (uint32_t)xadv;
+        gptr += (uint32_t)gadv;
+        --left;
+    };
+    auto set_group = [&](auto BUFC, auto GROUPC, auto WAITC) {
+        constexpr int BUF = decltype(BUFC)::value;
+        constexpr bool WAIT = decltype(WAITC)::value;
+        if constexpr (decltype(GROUPC)::value == 0) dma_set_base<BUF * TL::STAGE, WAIT>(wave_x);
+        else dma_set_base<BUF * TL::STAGE, WAIT>(wave_g);
+    };
+    auto issue_one = [&](auto NC) {
+        constexpr int n = decltype(NC)::value;
+        if constexpr (n < NXI) dma_load_16_off<n * 1024>(xoff[n], rx);
+        else dma_load_16_off<(n - NXI) * 1024>(goff[n - NXI], rg);
+    };
+
+    // ---- fragment geometry: as in the eight-wave kernel
+    const int blk = lane / 16, li = lane % 16;
+    const int frow = 8 * blk + li / 4;
+    const int sw = 4 * (li / 4);
+    const int low = (li % 4) * 8;
+    int a_addr[FM], b_addr[FN];
+#pragma unroll
+    for (int a = 0; a < FM; ++a) a_addr[a] = frow * XROW + ((((wm * TL::WM + a * 16) / 8) ^ sw) * 16) + low;
+#pragma unroll
+    for (int c = 0; c < FN; ++c) b_addr[c] = frow * GROW + ((((wn * TL::WN + c * 16) / 8) ^ sw) * 16) + low;
+
+    float4_t acc[FM][FN];
+#pragma unroll
+    for (int a = 0; a < FM; ++a)
+#pragma unroll
+        for (int c = 0; c < FN; ++c)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[a][c][r] = 0.f;
+
+    // two sets of fragments, each fragment as the two transposing reads that make it
+    short4_t fa[2][FM][2], fb[2][FN][2];
+    // half h (tokens 8*blk + 4*h .. + 3) of fragment f (G fragments first) of the slab in buffer BUF
+    auto read_half = [&](auto SETC, auto BUFC, int f, int h) {
+        constexpr int SET = decltype(SETC)::value, BUF = decltype(BUFC)::value;
+        const unsigned char* base = lds + BUF * TL::STAGE;
+        if (f < FN) fb[SET][f][h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(base + TL::X_BYTES + b_addr[f] + h * 4 * GROW));
+        else fa[SET][f - FN][h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(base + a_addr[f - FN] + h * 4 * XROW));
+    };
+    auto whole = [&](const short4_t (&h)[2]) { return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(h[0], h[1], 0, 1, 2, 3, 4, 5, 6, 7)); };
+
+    // Iteration g: fragment set CUR holds slab g; buffer RB holds slab g+1; buffer WB is free for slab g+NS-1.
+    auto iteration = [&](auto CURC, auto RBC, auto WBC) {
+        constexpr int CUR = decltype(CURC)::value;
+        static_for<FM * FN>([&](auto IC) {
+            constexpr int i = decltype(IC)::value, a = i / FN, cc = i % FN, c = (a & 1) ? FN - 1 - cc : cc;
+            acc[a][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(whole(fa[CUR][a]), whole(fb[CUR][c]), acc[a][c], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (i == 0) { slab_rows(); __builtin_amdgcn_sched_barrier(0); }
+            if constexpr (i == 1) { slab_range(); __builtin_amdgcn_sched_barrier(0); }
+            if constexpr (i == TL::ADVANCE_AT) { slab_advance(); __builtin_amdgcn_sched_barrier(0); }
+            constexpr int k = quad_read_slot(i);
+            if constexpr (k >= 0) {
+                read_half(std::integral_constant<int, 1 - CUR>{}, RBC, k / 2, k % 2);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            constexpr int nb = quad_load_slot(i + 1);      // a group's LDS base is set one MFMA ahead of its first load
+            if constexpr (nb == 0 || nb == NXI) {
+                set_group(WBC, std::integral_constant<int, nb == 0 ? 0 : 1>{}, std::false_type{});
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            constexpr int n = quad_load_slot(i);
+            if constexpr (n >= 0) {
+                issue_one(std::integral_constant<int, n>{});
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        });
+        wait_vmcnt<(NS - 3) * LPS>();     // this wave's part of slab g+2 has landed (slabs g+3 .. g+NS-1 may be in flight)
+        plain_barrier();
+    };
+
+    if (total > 0) {
+        static_for<NS - 1>([&](auto SC) {      // slabs 0 .. NS-2 into buffers 0 .. NS-2
+            slab_rows();
+            slab_range();
+            set_group(SC, std::integral_constant<int, 0>{}, std::true_type{});
+            static_for<NXI>([&](auto NC) { issue_one(NC); });
+            set_group(SC, std::integral_constant<int, 1>{}, std::true_type{});
+            static_for<NGI>([&](auto NC) { issue_one(std::integral_constant<int, NXI + decltype(NC)::value>{}); });
+            slab_advance();
+        });
+        wait_vmcnt<(NS - 2) * LPS>();
+        plain_barrier();                        // slab 0 is visible to every wave
+#pragma unroll
+        for (int f = 0; f < FM + FN; ++f) {
+            read_half(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, f, 0);
+            read_half(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, f, 1);
+        }
+        wait_vmcnt<(NS - 3) * LPS>();
+        plain_barrier();                        // so is slab 1
+        // iteration g0 + k: set k mod 2, reads buffer (k+1) mod NS, refills buffer (k-1) mod NS
+        for (int g0 = 0; g0 < total; g0 += TL::PERIOD) {
+            static_for<TL::PERIOD>([&](auto KC) {
+                constexpr int k = decltype(KC)::value;
+                if (g0 + k < total)
+                    iteration(std::integral_constant<int, k & 1>{}, std::integral_constant<int, (k + 1) % NS>{},
+                              std::integral_constant<int, (k + NS - 1) % NS>{});
+            });
+        }
+    }
+    wait_vmcnt<0>();   // drain the (empty) loads issued past the end before the LDS is released
+
+    // ---- epilogue: lane holds column (lane%16), rows 4*(lane/16) + r of each 16x16 tile
+    const int64_t split_off = (int64_t)split * din * dout;
+    const int jn = lane % 16, ib = 4 * (lane / 16);
+#pragma unroll
+    for (int a = 0; a < FM; ++a)
+#pragma unroll
+        for (int c = 0; c < FN; ++c) {
+            const int j = j0 + wn * TL::WN + c * 16 + jn;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int i = i0 + wm * TL::WM + a * 16 + ib + r;
+                if (i < din && j < dout) out[split_off + (int64_t)i * dout + j] = acc[a][c][r];
+            }
+        }
+}
+
+// Ranges shorter than this many rows per workgroup stay on the eight-wave kernel, whose start-up is shorter.
+constexpr int64_t QUAD_MIN_ROWS = 1024;
+
+hipError_t launch_quad(const uint16_t* X, const uint16_t* G, int64_t B, int64_t T, int64_t din, int64_t dout,
+                       const StatPlan& plan, float* out, hipStream_t stream)
+{
+    using TL = QuadTile;
+    const int tiles_m = (int)((din + TL::BM - 1) / TL::BM), tiles_n = (int)((dout + TL::BN - 1) / TL::BN);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)stat_bf16_quad_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const dim3 grid((unsigned)(tiles_m * tiles_n * plan.nsplit)), block(TL::NT);
+    stat_bf16_quad_kernel<<<grid, block, TL::LDS_BYTES, stream>>>(X, G, B * T, (int)din, (int)dout, plan.per_split, tiles_m, tiles_n, out);
+    return hipGetLastError();
+}
+
 // sign counts are packed (and the tile is 256 x 256) while a group of examples cannot exceed 2048
 bool sign_is_packed(int64_t B) { return B <= 2048; }
 
@@ -559,7 +848,7 @@ bool bf16_supports(int64_t B, int64_t T, int64_t din, int64_t dout)
     if (din % 8 != 0 || dout % 8 != 0 || din < 32 || dout < 32 || B * T < 16) return false;
     // per-slab descriptors and lane offsets are 32-bit byte counts: one slab of rows must stay below 2 GiB
     const int64_t bk = 32;
-    if (bk * din * 2 >= ((int64_t)1 << 31) || bk * dout * 2 >= ((int64_t)1 << 31)) return false;
+    if (bk * din * 2 + 4096 >= ((int64_t)1 << 31) || bk * dout * 2 + 4096 >= ((int64_t)1 << 31)) return false;
     return true;
 }
 
@@ -578,7 +867,9 @@ hipError_t launch_stat_bf16(const void* X, const void* G, int64_t B, int64_t T, 
     const uint16_t* x = (const uint16_t*)X;
     const uint16_t* g = (const uint16_t*)G;
     switch (mode) {
-    case MODE_IDENTITY: return launch_one<TileWide, OUT_ID>(x, g, B, T, din, dout, plan, out, nullptr, nullptr, stream);
+    case MODE_IDENTITY:
+        if (plan.per_split >= QUAD_MIN_ROWS) return launch_quad(x, g, B, T, din, dout, plan, out, stream);
+        return launch_one<TileWide, OUT_ID>(x, g, B, T, din, dout, plan, out, nullptr, nullptr, stream);
     case MODE_TOKEN_SQ: return launch_one<TileToken, OUT_TOKEN>(x, g, B, T, din, dout, plan, out, nullptr, nullptr, stream);
     case MODE_SQUARE: return launch_one<TilePhi, OUT_SQ>(x, g, B, T, din, dout, plan, nullptr, out, nullptr, stream);
     case MODE_SIGN:

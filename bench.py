@@ -289,7 +289,7 @@ def main() -> int:
                 "frac_of_measured_mfma_ceiling": None if ceiling is None else round(achieved / ceiling, 4), "avg_launch_ms": round(avg_ms, 4),
                 "launches": len(ms), "traffic": measured_traffic(args.workload, which)}
 
-    roofline = contraction_roofline(id_events, "stat_bf16_kernel<256x256 tile, identity> (pex_stat phi=identity; also "
+    roofline = contraction_roofline(id_events, "stat_bf16_quad_kernel (256x256 tile, four waves of 128x128; pex_stat phi=identity; also "
                                                "the contraction inside pex_token_sq)", "identity")
     square_roofline = contraction_roofline(sq_events, "stat_bf16_kernel<256x128 tile, square> (pex_stat phi=square)", "square")
     upd_ms = [a.elapsed_time(b) for a, b, _ in upd_events]

@@ -298,3 +298,21 @@ def test_simt_kernel_on_shapes_the_mfma_kernels_normally_take(monkeypatch, B, T,
     monkeypatch.delenv("PEX_FORCE_GENERIC")
     assert np.abs(got["identity"] - mfma["identity"]).max() <= 2e-5 * np.abs(st.S_id).max()
     assert (np.abs(got["sign"] - mfma["sign"]) <= 2 * st.amb).all()
+
+
+# Plain contractions with at least 1024 rows per workgroup run on the four-wave kernel (one wave per SIMD, 128 x 128
+# per wave): ragged tile edges, a last slab of 1, 23 and 31 rows, an odd and an even number of slabs, one tile and
+# several, with the planner's split of the rows over workgroups and (small shapes) with the split switched off.
+@pytest.mark.parametrize("B,T,din,dout,max_split", [(1, 1024, 256, 256, 1), (1, 1025, 256, 256, 1), (3, 701, 328, 200, 1),
+                                                    (5, 411, 264, 520, 1), (1, 2079, 1032, 40, 2), (3, 7171, 520, 776, None),
+                                                    (2, 20000, 512, 512, None)])
+def test_four_wave_kernel_shapes(monkeypatch, B, T, din, dout, max_split):
+    if max_split is not None:
+        monkeypatch.setenv("PEX_MAX_SPLIT", str(max_split))
+    nsplit = max(1, pex.pex_stat_workspace_bytes(B, T, din, dout, pex.PEX_BF16, "identity") // (din * dout * 4))
+    assert B * T // nsplit >= 1024, "shape chosen so that the four-wave kernel takes it"
+    X, G = si.custom(B, T, din, dout, dtype="bf16", seed=B + T)
+    S = pex.pex_stat(X.to(DEV), G.to(DEV), "identity")
+    torch.cuda.synchronize()
+    ref = si.widen(X).reshape(B * T, din).astype(np.float64).T @ si.widen(G).reshape(B * T, dout).astype(np.float64)
+    assert_real_stat(S.cpu().numpy().astype(np.float64), ref, "bf16", f"four-wave identity {B}x{T}x{din}x{dout}", elementwise=False)

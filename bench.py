@@ -123,6 +123,8 @@ def main() -> int:
     sq_events = []          # ... of the phi = square contraction
     upd_events = []
     sgn_events = []         # ... of the MicroSignSGD update
+    sc_events = []          # ... of the phi = sign contraction
+    tk_events = []          # ... of the per-token square (both squaring passes and the contraction)
 
     def step(t: int, record: bool):
         for L in layers:
@@ -149,15 +151,26 @@ def main() -> int:
             if record:
                 u1.record()
                 upd_events.append((u0, u1, w))
+            if record:
+                s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                s0.record()
             pex.pex_stat(L["X"], L["G"], "sign", S=L["S_sg"], workspace=L["ws"])
             if record:
+                s1.record()
+                sc_events.append((s0, s1, w))
                 g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 g0.record()
             pex.pex_signsgd_update(L["theta_s"], L["m_s"], L["S_sg"].view(-1), 3.47e-3, 0.9, 0.0, w.B, False, t)
             if record:
                 g1.record()
                 sgn_events.append((g0, g1, w))
+            if record:
+                k0, k1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                k0.record()
             pex.pex_token_sq(L["X"], L["G"], S=L["S_tk"], workspace=L["ws"])
+            if record:
+                k1.record()
+                tk_events.append((k0, k1, w))
 
     for t in range(1, args.warmup + 1):
         step(t, False)
@@ -292,6 +305,9 @@ def main() -> int:
     roofline = contraction_roofline(id_events, "stat_bf16_quad_kernel (256x256 tile, four waves of 128x128; pex_stat phi=identity; also "
                                                "the contraction inside pex_token_sq)", "identity")
     square_roofline = contraction_roofline(sq_events, "stat_bf16_kernel<256x128 tile, square> (pex_stat phi=square)", "square")
+    sign_roofline = contraction_roofline(sc_events, "stat_bf16_kernel<256x256 tile, sign with packed counts> (pex_stat phi=sign)", "sign")
+    token_roofline = contraction_roofline(tk_events, "pex_token_sq as a whole: square_bf16_kernel on X and on G, then stat_bf16_quad_kernel "
+                                                     "on the copies; FLOP of the contraction only", "token")
     upd_ms = [a.elapsed_time(b) for a, b, _ in upd_events]
     upd_bytes = [32.0 * w.din * w.dout for _, _, w in upd_events]
     upd_gbs = (sum(upd_bytes) / len(upd_bytes)) / (sum(upd_ms) / len(upd_ms) * 1e-3) / 1e9
@@ -342,7 +358,8 @@ def main() -> int:
                    "shapes": [[L["w"].din, L["w"].dout] for L in layers],
                    "step": "per layer: pex_stat identity+square -> MicroAdam update; pex_stat sign -> MicroSignSGD update; pex_token_sq",
                    "flop_per_step": flop_per_step, "seed": args.seed},
-        "roofline": roofline, "square_roofline": square_roofline, "update_roofline": update_roofline,
+        "roofline": roofline, "square_roofline": square_roofline, "sign_roofline": sign_roofline,
+        "token_roofline": token_roofline, "update_roofline": update_roofline,
         "sign_update_roofline": sign_update_roofline,
         "mfma_only_ceiling": None if ceiling is None else {
             "achieved": round(ceiling, 1), "unit": "TFLOP/s", "frac_of_peak": round(ceiling / PEAK_BF16_TFLOPS, 4),

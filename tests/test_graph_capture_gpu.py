@@ -75,3 +75,36 @@ def test_a_whole_step_replays_from_a_graph():
             assert torch.equal(graphed[k], reference[k]), f"replay {replay}: {k} differs from the eager run"
     for k in ("theta", "m", "v", "S_sq", "E_sq"):
         assert torch.equal(graphed[k], eager[k]), k
+
+
+def test_four_wave_contraction_is_deterministic_and_replays_from_a_graph(monkeypatch):
+    """The plain contraction on its four-wave kernel (rows unsplit, so every workgroup runs the long loop): two eager
+    runs agree bit for bit (no atomics, fixed order), and so do three replays of a captured launch, with eager work
+    between them."""
+    monkeypatch.setenv("PEX_MAX_SPLIT", "1")
+    B, T, din, dout = 3, 701, 328, 520
+    X, G = si.custom(B, T, din, dout, dtype="bf16", seed=11)
+    Xd, Gd = X.to(DEV), G.to(DEV)
+    ws = torch.empty(max(pex.pex_stat_workspace_bytes(B, T, din, dout, pex.PEX_BF16, "identity"), 16), dtype=torch.uint8, device=DEV)
+    first = pex.pex_stat(Xd, Gd, "identity", workspace=ws).clone()
+    second = pex.pex_stat(Xd, Gd, "identity", workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(first, second)
+
+    S = torch.empty(din, dout, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        pex.pex_stat(Xd, Gd, "identity", S=S, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        pex.pex_stat(Xd, Gd, "identity", S=S, workspace=ws)
+    for _ in range(3):
+        S.fill_(-1.0)
+        pex.pex_stat(Xd, Gd, "square", workspace=ws)      # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(S, first)

@@ -59,6 +59,7 @@
 // instruction that is not an MFMA costs about four cycles of MFMA time (measured: 1024 + 4 x 60 cycles per slab), so
 // that kernel is written to issue as few of them as possible (see there).
 #include <cstdlib>
+#include <mutex>
 #include <type_traits>
 #include <utility>
 
@@ -541,12 +542,11 @@ hipError_t launch_one(const uint16_t* X, const uint16_t* G, int64_t B, int64_t T
     const int tiles_m = (int)((din + TL::BM - 1) / TL::BM), tiles_n = (int)((dout + TL::BN - 1) / TL::BN);
     const int64_t rows_per_split = PER_EXAMPLE ? plan.per_split * T : plan.per_split;
     auto kern = stat_bf16_kernel<TL, OUTS>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    // once per kernel and process, also when several host threads launch at the same time
+    static std::once_flag attr_once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(attr_once, [&] { attr_err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES); });
+    if (attr_err != hipSuccess) return attr_err;
     const dim3 grid((unsigned)(tiles_m * tiles_n * plan.nsplit)), block(TL::NT);
     kern<<<grid, block, TL::LDS_BYTES, stream>>>(X, G, B * T, (int)T, (int)din, (int)dout, rows_per_split, tiles_m,
                                                  tiles_n, out_id, out_sq, out_sg, weight, norm_partial, (int)B, alpha);
@@ -820,12 +820,10 @@ hipError_t launch_quad(const uint16_t* X, const uint16_t* G, int64_t B, int64_t 
 {
     using TL = QuadTile;
     const int tiles_m = (int)((din + TL::BM - 1) / TL::BM), tiles_n = (int)((dout + TL::BN - 1) / TL::BN);
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)stat_bf16_quad_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::once_flag attr_once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(attr_once, [] { attr_err = hipFuncSetAttribute((const void*)stat_bf16_quad_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES); });
+    if (attr_err != hipSuccess) return attr_err;
     const dim3 grid((unsigned)(tiles_m * tiles_n * plan.nsplit)), block(TL::NT);
     stat_bf16_quad_kernel<<<grid, block, TL::LDS_BYTES, stream>>>(X, G, B * T, (int)din, (int)dout, plan.per_split, tiles_m, tiles_n, out);
     return hipGetLastError();

@@ -39,7 +39,8 @@ typedef enum {
     PEX_ERR_PHI = 4,        /* unknown pex_phi / pex_adam_variant */
     PEX_ERR_ALIGN = 5,      /* a pointer is not 16-byte aligned */
     PEX_ERR_WORKSPACE = 6,  /* workspace is NULL or smaller than the matching *_workspace_bytes() */
-    PEX_ERR_HIP = 7         /* the HIP runtime reported an error at launch */
+    PEX_ERR_HIP = 7,        /* the HIP runtime reported an error at launch */
+    PEX_ERR_TOO_LARGE = 8   /* pex_stat_noalloc: the call needs more than PEX_NOALLOC_SCRATCH_BYTES of scratch */
 } pex_status;
 
 typedef enum { PEX_F32 = 0, PEX_BF16 = 1 } pex_dtype;                          /* storage type of X and of G (same for both) */
@@ -77,6 +78,24 @@ size_t pex_stat_workspace_bytes(int64_t B, int64_t T, int64_t din, int64_t dout,
 pex_status pex_stat(const void *X, const void *G, int64_t B, int64_t T, int64_t din, int64_t dout,
                     pex_dtype dt, pex_phi phi, float *S, void *workspace, size_t workspace_bytes,
                     pex_stream_t stream);
+
+/*
+ * pex_stat_noalloc -- pex_stat for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels, results (bit
+ * for bit) and error codes as pex_stat, but the partial sums over groups of examples go to a buffer of
+ * PEX_NOALLOC_SCRATCH_BYTES that is part of the library's device image (one copy per GPU, held until the process
+ * ends) instead of a caller's workspace.  The call allocates and frees nothing.
+ *   - A call whose pex_stat_workspace_bytes(...) exceeds PEX_NOALLOC_SCRATCH_BYTES returns PEX_ERR_TOO_LARGE and
+ *     launches nothing (small layers with many groups: e.g. 512 x 2048 in 16 groups needs 64 MiB).
+ *   - All calls on one GPU share that GPU's buffer: calls that overlap in time on one GPU (different streams,
+ *     different host threads) race on it; calls on one stream, or otherwise ordered, are safe.  Nothing in the
+ *     buffer needs to start at zero and nothing is kept in it between calls.
+ *   - The buffer's address is looked up on the first call on each device (no allocation, but make that first
+ *     call outside graph capture).
+ */
+#define PEX_NOALLOC_SCRATCH_BYTES (32u << 20)
+pex_status pex_stat_noalloc(const void *X, const void *G, int64_t B, int64_t T, int64_t din, int64_t dout,
+                            pex_dtype dt, pex_phi phi, float *S, pex_stream_t stream);
 
 /*
  * pex_stat_multi -- several of the statistics of pex_stat from one pass over X and G.  MicroAdam needs the mean

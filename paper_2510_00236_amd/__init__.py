@@ -37,7 +37,7 @@ EXPORTS = ("pex_status_string", "pex_version", "pex_stat_workspace_bytes", "pex_
            "pex_token_sq_workspace_bytes", "pex_token_sq", "pex_adam_update", "pex_signsgd_update",
            "pex_moment_track_workspace_bytes", "pex_moment_track", "pex_embed_stat_workspace_bytes", "pex_embed_stat",
            "pex_mfma_probe_operand_bytes", "pex_mfma_probe_sink_floats", "pex_mfma_probe",
-           "pex_sum_squares_workspace_bytes", "pex_sum_squares", "pex_adam_update_clipped")
+           "pex_sum_squares_workspace_bytes", "pex_sum_squares", "pex_adam_update_clipped", "pex_stat_noalloc")
 
 
 class PexError(RuntimeError):
@@ -78,6 +78,8 @@ def lib() -> ctypes.CDLL:
         L.pex_stat_workspace_bytes.restype = sz
         L.pex_stat.argtypes = [p, p, i64, i64, i64, i64, ctypes.c_int, ctypes.c_int, p, p, sz, p]
         L.pex_stat.restype = ctypes.c_int
+        L.pex_stat_noalloc.argtypes = [p, p, i64, i64, i64, i64, ctypes.c_int, ctypes.c_int, p, p]
+        L.pex_stat_noalloc.restype = ctypes.c_int
         L.pex_stat_multi_workspace_bytes.argtypes = [i64, i64, i64, i64, ctypes.c_int, ctypes.c_uint32]
         L.pex_stat_multi_workspace_bytes.restype = sz
         L.pex_stat_multi.argtypes = [p, p, i64, i64, i64, i64, ctypes.c_int, ctypes.c_uint32, p, p, p, p, sz, p]
@@ -214,6 +216,18 @@ def pex_stat(X, G, phi, S=None, workspace=None, stream=None):
     ws, wptr, wbytes = _workspace(pex_stat_workspace_bytes(B, T, din, dout, dt, code), X, workspace)
     _check(lib().pex_stat(_dev(X, "X"), _dev(G, "G"), B, T, din, dout, dt, code, _dev(S, "S"), wptr, wbytes,
                           _stream(stream)))
+    return S
+
+
+NOALLOC_SCRATCH_BYTES = 32 << 20
+
+
+def pex_stat_noalloc(X, G, phi, S, stream=None):
+    """pex_stat into the caller's ``S`` with the library's own static scratch: nothing is allocated, here or in the
+    library.  Raises PexError (PEX_ERR_TOO_LARGE) when the call needs more than NOALLOC_SCRATCH_BYTES."""
+    B, T, din, dout = _shapes(X, G)
+    _check(lib().pex_stat_noalloc(_dev(X, "X"), _dev(G, "G"), B, T, din, dout, _dtype_code(X), PHI.get(phi, phi),
+                                  _dev(S, "S"), _stream(stream)))
     return S
 
 

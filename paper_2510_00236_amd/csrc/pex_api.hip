@@ -1,10 +1,38 @@
 // pex_api.hip -- the C ABI of libpex: host-side validation, planning and kernel dispatch.
 // Every entry point validates first and launches nothing on error.
 #include <cstdlib>
+#include <mutex>
 
 #include "pex_internal.h"
 
+// Scratch of pex_stat_noalloc: device memory that belongs to the library, one copy per GPU, held until the process
+// ends.  In host code this name is only a handle for hipGetSymbolAddress; kernels and copies take the address that
+// call returns for the current device.
+static __device__ __align__(256) unsigned char scratch[PEX_NOALLOC_SCRATCH_BYTES];
+
 namespace pex {
+
+// The address of `scratch` on the current device, looked up once per device.
+static hipError_t scratch_address(void** out)
+{
+    constexpr int MAX_DEVICES = 64;
+    static std::mutex mu;
+    static void* ptr[MAX_DEVICES] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return hipSuccess;
+}
 
 static int env_int(const char* name, int dflt)
 {
@@ -189,6 +217,7 @@ const char* pex_status_string(pex_status s)
     case PEX_ERR_ALIGN: return "PEX_ERR_ALIGN: a pointer is not 16-byte aligned";
     case PEX_ERR_WORKSPACE: return "PEX_ERR_WORKSPACE: workspace missing or too small";
     case PEX_ERR_HIP: return "PEX_ERR_HIP: the HIP runtime reported an error";
+    case PEX_ERR_TOO_LARGE: return "PEX_ERR_TOO_LARGE: the call needs more scratch than the library's static buffer holds";
     }
     return "PEX: unknown status";
 }
@@ -210,6 +239,21 @@ pex_status pex_stat(const void* X, const void* G, int64_t B, int64_t T, int64_t 
     if (st != PEX_OK) return st;
     if (phi != PEX_PHI_IDENTITY && phi != PEX_PHI_SQUARE && phi != PEX_PHI_SIGN) return PEX_ERR_PHI;
     return run_stat(X, G, B, T, din, dout, dt, (Mode)phi, S, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+pex_status pex_stat_noalloc(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt,
+                            pex_phi phi, float* S, pex_stream_t stream)
+{
+    const pex_status st = check_stat_args(X, G, B, T, din, dout, dt, S);
+    if (st != PEX_OK) return st;
+    if (phi != PEX_PHI_IDENTITY && phi != PEX_PHI_SQUARE && phi != PEX_PHI_SIGN) return PEX_ERR_PHI;
+    const size_t need = plan_stat(B, T, din, dout, dt, (Mode)phi).ws_bytes;
+    if (need > (size_t)PEX_NOALLOC_SCRATCH_BYTES) return PEX_ERR_TOO_LARGE;
+    void* ws = nullptr;
+    if (need > 0 && scratch_address(&ws) != hipSuccess) return PEX_ERR_HIP;
+    // Every partial sum the reduction reads is written by the contraction of the same call, so nothing in the
+    // scratch has to start at zero.
+    return run_stat(X, G, B, T, din, dout, dt, (Mode)phi, S, ws, need, (hipStream_t)stream);
 }
 
 size_t pex_stat_multi_workspace_bytes(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt, uint32_t want)

@@ -30,7 +30,7 @@ def test_header_and_library_agree():
 def test_version_and_status_strings():
     assert pex.lib().pex_version() >= 100
     seen = set()
-    for code in range(8):
+    for code in range(9):
         s = pex.status_string(code)
         assert s.startswith("PEX_") and s not in seen
         seen.add(s)
@@ -87,6 +87,14 @@ def test_host_validation_launches_nothing():
     assert L.pex_stat(X, G, *ok, 0, 1, S, None, 0, None) == 6
     assert L.pex_stat(X, G, *ok, 0, 1, S, 0x4000, need - 1, None) == 6
     assert L.pex_stat(X, G, *ok, 0, 1, S, 0x4004, need, None) == 5
+    # the entry point without a workspace argument: same validation, and a size check against its static scratch
+    assert L.pex_stat_noalloc(None, G, *ok, 0, 0, S, None) == 1
+    assert L.pex_stat_noalloc(X, G, 0, 16, 64, 64, 0, 0, S, None) == 2
+    assert L.pex_stat_noalloc(X, G, *ok, 7, 0, S, None) == 3
+    assert L.pex_stat_noalloc(X, G, *ok, 0, 9, S, None) == 4
+    assert L.pex_stat_noalloc(X, G, *ok, 0, 0, S + 4, None) == 5
+    assert pex.pex_stat_workspace_bytes(32, 256, 512, 2048, pex.PEX_BF16, "sign") > pex.NOALLOC_SCRATCH_BYTES
+    assert L.pex_stat_noalloc(X, G, 32, 256, 512, 2048, 1, 2, S, None) == 8
     assert L.pex_stat_multi(X, G, *ok, 0, 0, S, S, S, None, 0, None) == 4          # nothing wanted
     assert L.pex_stat_multi(X, G, *ok, 0, 8, S, S, S, None, 0, None) == 4
     assert L.pex_stat_multi(X, G, *ok, 0, 3, S, None, None, None, 0, None) == 1     # square wanted, no output for it

@@ -72,6 +72,8 @@ def main() -> int:
                          "against which the FETCH_SIZE / WRITE_SIZE counters of a profiling run are scaled")
     ap.add_argument("--no-probe", action="store_true",
                     help="skip the MFMA-only ceiling measurement (profiling runs: the trace then holds the step's kernels only)")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the per-launch timing of the other workload shapes (profiling runs)")
     ap.add_argument("--extras", action="store_true",
                     help="after the timed region also time, per launch, the entry points outside the headline step "
                          "(vector parameters, norms, weighted sums, power, embedding table, moment tracking) on the "
@@ -286,6 +288,63 @@ def main() -> int:
             nbytes=20.0 * n)
         del ids, emb_out, ema_a, ema_q
 
+    # ---- the other workload shapes, per launch, after the timed region.  Not part of `value`: the headline stays on
+    # the 1B-scale layer pair.  Every statistic is timed alone with events on the launch stream, 10 warm-up launches
+    # and `reps` timed ones; layers whose inputs fit the 256 MB memory-side cache alternate between two sets of
+    # input buffers so that cache residency does not flatter them.
+    configs = None
+    if not args.no_configs:
+        configs = {}
+        others = [n for k, names in LAYER_SETS.items() if k != args.workload for n in names]
+        for name in sorted(others):
+            w = si.WORKLOADS[name]
+            in_bytes = w.B * w.T * (w.din + w.dout) * 2
+            nsets = 2 if in_bytes < (256 << 20) else 1
+            sets = []
+            for k in range(nsets):
+                Xc, Gc = si.make(w, seed=args.seed + 17 * k)
+                sets.append((Xc.to(dev), Gc.to(dev)))
+            S = torch.empty(w.din, w.dout, device=dev)
+            nb = max(pex.pex_stat_workspace_bytes(w.B, w.T, w.din, w.dout, pex.PEX_BF16, p) for p in ("identity", "square", "sign"))
+            nb = max(nb, pex.pex_token_sq_workspace_bytes(w.B, w.T, w.din, w.dout, pex.PEX_BF16), 16)
+            wsc = torch.empty(nb, dtype=torch.uint8, device=dev)
+            flop = 2.0 * w.B * w.T * w.din * w.dout
+            reps = 20 if flop < 5e11 else 10
+
+            def per_launch(fn):
+                for k in range(10):            # fresh buffers: the first launches on new memory run slower
+                    fn(*sets[k % nsets])
+                torch.cuda.synchronize()
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                for k in range(reps):
+                    fn(*sets[k % nsets])
+                b.record()
+                torch.cuda.synchronize()
+                return a.elapsed_time(b) / reps
+
+            c = {"B": w.B, "T": w.T, "din": w.din, "dout": w.dout, "flop_per_statistic": flop,
+                 "input_buffer_sets": nsets, "launches_timed": reps}
+            for phi in ("identity", "square", "sign"):
+                ms = per_launch(lambda Xc, Gc, phi=phi: pex.pex_stat(Xc, Gc, phi, S=S, workspace=wsc))
+                c[phi] = {"us": round(ms * 1e3, 1), "TFLOP/s": round(flop / (ms * 1e-3) / 1e12, 1),
+                          "frac_of_bf16_peak": round(flop / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
+            ms = per_launch(lambda Xc, Gc: pex.pex_token_sq(Xc, Gc, S=S, workspace=wsc))
+            c["token_sq"] = {"us": round(ms * 1e3, 1), "TFLOP/s": round(flop / (ms * 1e-3) / 1e12, 1),
+                             "frac_of_bf16_peak": round(flop / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
+            if name == "c2_mlp_in":      # this workload names the MicroAdam update over its 512 x 2048 parameters
+                n = w.din * w.dout
+                th, mm, vv = (t.to(dev) for t in si.optimizer_state(n, seed=args.seed))
+                Sa, Sq = torch.randn(n, device=dev), torch.rand(n, device=dev) + 1.0
+                pp = pex.AdamParams(lr=2.0 / 1024, beta1=0.9, beta2=0.95, eps=1e-8, eps_root=0.0, weight_decay=0.0,
+                                    grad_scale=1.0 / w.B, sq_scale=1.0 / w.B, step=1, B=w.B)
+                ms = per_launch(lambda Xc, Gc: pex.pex_adam_update(th, mm, vv, Sa, Sq, "microadam", pp))
+                c["microadam_update"] = {"us": round(ms * 1e3, 1), "GB/s": round(32.0 * n / (ms * 1e-3) / 1e9, 1),
+                                         "frac_of_hbm_peak": round(32.0 * n / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+            configs[name] = c
+            del sets, S, wsc
+        torch.cuda.empty_cache()
+
     flop_per_stat = [2.0 * L["w"].B * L["w"].T * L["w"].din * L["w"].dout for L in layers]
     flop_per_step = 4.0 * sum(flop_per_stat)          # identity, square, sign, per-token square
     ms_per_step = elapsed / args.steps * 1e3
@@ -370,6 +429,8 @@ def main() -> int:
                                     "note": "same outputs with identity, square and sign from one contraction per layer "
                                             "(pex_stat_multi); informational, not used in value"},
     }
+    if configs is not None:
+        out["configs"] = configs
     if extras is not None:
         out["extras"] = extras
     print(json.dumps(out, ensure_ascii=False))

@@ -56,6 +56,24 @@ const char *pex_status_string(pex_status s);
 int pex_version(void);
 
 /*
+ * Planner options.  Each starts from an environment variable that is read once per process (on the first call that
+ * plans anything) and is changed afterwards only by pex_set_option; both calls are safe from any host thread.
+ *   PEX_OPT_MAX_SPLIT        1 .. 32 (default 32; environment PEX_MAX_SPLIT, clamped to that range): the largest
+ *                            number of groups the batch is split into when a layer has too few tiles to fill the
+ *                            chip; it bounds the workspace at max_split * din*dout*4 bytes.
+ *   PEX_OPT_TOKEN_PRESQUARE  0 = pex_token_sq always squares inside the contraction, 1 = chosen by a cost model
+ *                            (default), 2 = always through bf16 copies of the squares (environment
+ *                            PEX_TOKEN_PRESQUARE).  Both routes round alike and give the same bits.
+ * An option changes the plan and with it the *_workspace_bytes of later calls: query again after setting one.  A
+ * call whose workspace was sized under another value returns PEX_ERR_WORKSPACE if it is too small.
+ * pex_set_option: PEX_ERR_PHI for an unknown option, PEX_ERR_SHAPE for a value out of range.  pex_get_option: the
+ * current value, -1 for an unknown option.
+ */
+typedef enum { PEX_OPT_MAX_SPLIT = 0, PEX_OPT_TOKEN_PRESQUARE = 1 } pex_option;
+pex_status pex_set_option(pex_option opt, int32_t value);
+int32_t pex_get_option(pex_option opt);
+
+/*
  * pex_stat -- S = sum_b phi(X_b^T G_b)  (Sec. 2.3: M = einsum(BLD,BLF->BDF), phi, reduce over B;
  * phi = identity is the ordinary batch weight gradient, phi = square is B * nu_micro of Eq. (nu_defs),
  * phi = sign is B * (avg o sign) of Sec. 3.1).
@@ -72,7 +90,8 @@ int pex_version(void);
  *                               many groups are needed to occupy the chip; none at the 1B-scale shapes).
  *   The contraction over T of one example is never split across workgroups (phi is applied to the complete
  *   sum over the sequence), the sum over b is taken in a fixed order.
- *   Any B,T,din,dout >= 1 is accepted (B*T, din, dout each < 2^31).
+ *   Any B,T,din,dout >= 1 is accepted with B*T, din, dout each < 2^31; fp32 inputs and bf16 layers whose rows are
+ *   not multiples of 16 bytes additionally need din <= 65535*128 resp. 65535*64 (PEX_ERR_SHAPE beyond).
  */
 size_t pex_stat_workspace_bytes(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt, pex_phi phi);
 pex_status pex_stat(const void *X, const void *G, int64_t B, int64_t T, int64_t din, int64_t dout,
@@ -126,8 +145,11 @@ pex_status pex_stat_multi(const void *X, const void *G, int64_t B, int64_t T, in
  *   A, C   [B,T,d] device, dtype `dt`, read-only; products are exact for bf16 and summed in fp32.
  *   s_id, s_sq, s_sign  [d] fp32 device outputs, each required iff its bit is set.
  *   workspace  at least pex_vec_stat_workspace_bytes(...) bytes (never 0): fp32 partial sums over ranges of the
- *              length axis, B * ranges * d floats, summed in a fixed order.
- *   Bound by HBM bandwidth: every input byte is read once.  Any B,T,d >= 1 (B*T, d < 2^31).
+ *              length axis, B * ranges * d floats, summed in a fixed order.  These partial sums are the per-example
+ *              gradients of the vector themselves (B*d floats per range): for a vector, unlike for a weight
+ *              matrix, staging them is cheap (B*d against B*T*d input values).
+ *   Bound by HBM bandwidth: every input byte is read once.  B,T,d >= 1 with B*T, d < 2^31 and B * ranges < 65536
+ *   (there are at most max(1, 2048/B) ranges, so this is B < 65536); PEX_ERR_SHAPE beyond.
  */
 size_t pex_vec_stat_workspace_bytes(int64_t B, int64_t T, int64_t d, pex_dtype dt);
 pex_status pex_vec_stat(const void *A, const void *C, int64_t B, int64_t T, int64_t d, pex_dtype dt, uint32_t want,

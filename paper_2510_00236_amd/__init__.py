@@ -37,7 +37,7 @@ EXPORTS = ("pex_status_string", "pex_version", "pex_stat_workspace_bytes", "pex_
            "pex_token_sq_workspace_bytes", "pex_token_sq", "pex_adam_update", "pex_signsgd_update",
            "pex_moment_track_workspace_bytes", "pex_moment_track", "pex_embed_stat_workspace_bytes", "pex_embed_stat",
            "pex_mfma_probe_operand_bytes", "pex_mfma_probe_sink_floats", "pex_mfma_probe",
-           "pex_sum_squares_workspace_bytes", "pex_sum_squares", "pex_adam_update_clipped", "pex_stat_noalloc")
+           "pex_sum_squares_workspace_bytes", "pex_sum_squares", "pex_adam_update_clipped", "pex_stat_noalloc", "pex_set_option", "pex_get_option")
 
 
 class PexError(RuntimeError):
@@ -78,6 +78,10 @@ def lib() -> ctypes.CDLL:
         L.pex_stat_workspace_bytes.restype = sz
         L.pex_stat.argtypes = [p, p, i64, i64, i64, i64, ctypes.c_int, ctypes.c_int, p, p, sz, p]
         L.pex_stat.restype = ctypes.c_int
+        L.pex_set_option.argtypes = [ctypes.c_int, i32]
+        L.pex_set_option.restype = ctypes.c_int
+        L.pex_get_option.argtypes = [ctypes.c_int]
+        L.pex_get_option.restype = i32
         L.pex_stat_noalloc.argtypes = [p, p, i64, i64, i64, i64, ctypes.c_int, ctypes.c_int, p, p]
         L.pex_stat_noalloc.restype = ctypes.c_int
         L.pex_stat_multi_workspace_bytes.argtypes = [i64, i64, i64, i64, ctypes.c_int, ctypes.c_uint32]
@@ -134,6 +138,19 @@ def lib() -> ctypes.CDLL:
     return _lib
 
 
+PEX_OPT_MAX_SPLIT, PEX_OPT_TOKEN_PRESQUARE = 0, 1
+OPTION = {"max_split": PEX_OPT_MAX_SPLIT, "token_presquare": PEX_OPT_TOKEN_PRESQUARE}
+
+
+def pex_set_option(opt, value) -> None:
+    """Set a planner option ('max_split' 1..32, 'token_presquare' 0|1|2, or the code)."""
+    _check(lib().pex_set_option(OPTION.get(opt, opt), int(value)))
+
+
+def pex_get_option(opt) -> int:
+    return int(lib().pex_get_option(OPTION.get(opt, opt)))
+
+
 def status_string(code: int) -> str:
     return lib().pex_status_string(int(code)).decode()
 
@@ -152,18 +169,63 @@ def _dtype_code(t) -> int:
     raise TypeError(f"X and G must be float32 or bfloat16, got {t.dtype}")
 
 
-def _dev(t, name):
-    if not t.is_cuda:
-        raise ValueError(f"{name} must live in GPU memory (libpex has no CPU path)")
+class _Buf:
+    """A tensor whose type and size have been checked, on its way to becoming a raw device pointer."""
+    __slots__ = ("t", "name")
+
+    def __init__(self, t, name):
+        self.t, self.name = t, name
+
+
+def _invoke(fn, *args):
+    """Call a library function: every checked tensor must live on the GPU (all type and size checks of the call
+    have passed by now), then goes in as its address; a status other than PEX_OK raises."""
+    for a in args:
+        if isinstance(a, _Buf) and not a.t.is_cuda:
+            raise ValueError(f"{a.name} must live in GPU memory (libpex has no CPU path)")
+    _check(fn(*[a.t.data_ptr() if isinstance(a, _Buf) else a.handle() if isinstance(a, _Stream) else a for a in args]))
+
+
+def _dev(t, name, dtype=None, numel=None, shape=None):
+    """``t`` as an argument for _invoke after checking what the library cannot check through a raw pointer: where the tensor
+    lives, that it is dense, and -- when given -- its element type and its size (a buffer of another type or size
+    would make a kernel read or write past its end)."""
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} must have shape {tuple(shape)}, got {tuple(t.shape)}")
+    if numel is not None and t.numel() != numel:
+        raise ValueError(f"{name} must have {numel} elements, got {t.numel()}")
     if not t.is_contiguous():
         raise ValueError(f"{name} must be contiguous")
-    return t.data_ptr()
+    return _Buf(t, name)
+
+
+def _f32(t, name, numel=None, shape=None):
+    import torch
+    return _dev(t, name, torch.float32, numel, shape)
+
+
+def _f64(t, name, numel=None):
+    import torch
+    return _dev(t, name, torch.float64, numel)
+
+
+class _Stream:
+    """The stream argument of a call, turned into a hipStream_t by _invoke (None = torch's current stream)."""
+    __slots__ = ("stream",)
+
+    def __init__(self, stream):
+        self.stream = stream
+
+    def handle(self):
+        import torch
+        s = torch.cuda.current_stream() if self.stream is None else self.stream
+        return ctypes.c_void_p(s.cuda_stream)
 
 
 def _stream(stream):
-    import torch
-    s = torch.cuda.current_stream() if stream is None else stream
-    return ctypes.c_void_p(s.cuda_stream)
+    return _Stream(stream)
 
 
 def _shapes(X, G):
@@ -196,13 +258,24 @@ def pex_token_sq_workspace_bytes(B, T, din, dout, dtype_code) -> int:
     return int(lib().pex_token_sq_workspace_bytes(B, T, din, dout, dtype_code))
 
 
-def _workspace(nbytes, like, workspace):
+def _workspace(nbytes, like, workspace, stream=None):
+    """The caller's workspace (uint8, at least ``nbytes``) or a temporary one.  A temporary is allocated under the
+    stream the kernels run on, so the caching allocator does not hand its memory out again before they finish."""
     import torch
     if workspace is None:
         if nbytes == 0:
-            return None, 0, 0
-        workspace = torch.empty(nbytes, dtype=torch.uint8, device=like.device)
-    return workspace, workspace.data_ptr(), workspace.numel() * workspace.element_size()
+            return None, None, 0
+        if stream is None:
+            workspace = torch.empty(nbytes, dtype=torch.uint8, device=like.device)
+        else:
+            with torch.cuda.stream(stream):
+                workspace = torch.empty(nbytes, dtype=torch.uint8, device=like.device)
+    else:
+        if workspace.dtype != torch.uint8:
+            raise TypeError(f"workspace must be uint8, got {workspace.dtype}")
+        if workspace.numel() < nbytes:
+            raise ValueError(f"workspace holds {workspace.numel()} bytes, the call needs {nbytes}")
+    return workspace, _dev(workspace, "workspace"), workspace.numel()
 
 
 def pex_stat(X, G, phi, S=None, workspace=None, stream=None):
@@ -213,9 +286,9 @@ def pex_stat(X, G, phi, S=None, workspace=None, stream=None):
     code = PHI.get(phi, phi)
     if S is None:
         S = torch.empty(din, dout, dtype=torch.float32, device=X.device)
-    ws, wptr, wbytes = _workspace(pex_stat_workspace_bytes(B, T, din, dout, dt, code), X, workspace)
-    _check(lib().pex_stat(_dev(X, "X"), _dev(G, "G"), B, T, din, dout, dt, code, _dev(S, "S"), wptr, wbytes,
-                          _stream(stream)))
+    ws, wptr, wbytes = _workspace(pex_stat_workspace_bytes(B, T, din, dout, dt, code), X, workspace, stream)
+    _invoke(lib().pex_stat, _dev(X, "X"), _dev(G, "G"), B, T, din, dout, dt, code, _f32(S, "S", shape=(din, dout)), wptr, wbytes,
+                          _stream(stream))
     return S
 
 
@@ -226,8 +299,8 @@ def pex_stat_noalloc(X, G, phi, S, stream=None):
     """pex_stat into the caller's ``S`` with the library's own static scratch: nothing is allocated, here or in the
     library.  Raises PexError (PEX_ERR_TOO_LARGE) when the call needs more than NOALLOC_SCRATCH_BYTES."""
     B, T, din, dout = _shapes(X, G)
-    _check(lib().pex_stat_noalloc(_dev(X, "X"), _dev(G, "G"), B, T, din, dout, _dtype_code(X), PHI.get(phi, phi),
-                                  _dev(S, "S"), _stream(stream)))
+    _invoke(lib().pex_stat_noalloc, _dev(X, "X"), _dev(G, "G"), B, T, din, dout, _dtype_code(X), PHI.get(phi, phi),
+                                  _f32(S, "S", shape=(din, dout)), _stream(stream))
     return S
 
 
@@ -246,12 +319,12 @@ def pex_stat_multi(X, G, want, out=None, workspace=None, stream=None):
             if S is None:
                 S = torch.empty(din, dout, dtype=torch.float32, device=X.device)
             res[name] = S
-            ptrs.append(_dev(S, name))
+            ptrs.append(_f32(S, name, shape=(din, dout)))
         else:
             ptrs.append(None)
-    ws, wptr, wbytes = _workspace(pex_stat_multi_workspace_bytes(B, T, din, dout, dt, mask), X, workspace)
-    _check(lib().pex_stat_multi(_dev(X, "X"), _dev(G, "G"), B, T, din, dout, dt, mask, ptrs[0], ptrs[1], ptrs[2],
-                                wptr, wbytes, _stream(stream)))
+    ws, wptr, wbytes = _workspace(pex_stat_multi_workspace_bytes(B, T, din, dout, dt, mask), X, workspace, stream)
+    _invoke(lib().pex_stat_multi, _dev(X, "X"), _dev(G, "G"), B, T, din, dout, dt, mask, ptrs[0], ptrs[1], ptrs[2],
+                                wptr, wbytes, _stream(stream))
     return res
 
 
@@ -277,12 +350,12 @@ def pex_vec_stat(A, C=None, want=("identity", "square", "sign"), out=None, works
             if s is None:
                 s = torch.empty(d, dtype=torch.float32, device=A.device)
             res[name] = s
-            ptrs.append(_dev(s, name))
+            ptrs.append(_f32(s, name, numel=d))
         else:
             ptrs.append(None)
-    ws, wptr, wbytes = _workspace(pex_vec_stat_workspace_bytes(B, T, d, dt), A, workspace)
-    _check(lib().pex_vec_stat(_dev(A, "A"), _dev(C, "C") if C is not None else None, B, T, d, dt, mask,
-                              ptrs[0], ptrs[1], ptrs[2], wptr, wbytes, _stream(stream)))
+    ws, wptr, wbytes = _workspace(pex_vec_stat_workspace_bytes(B, T, d, dt), A, workspace, stream)
+    _invoke(lib().pex_vec_stat, _dev(A, "A"), _dev(C, "C") if C is not None else None, B, T, d, dt, mask,
+                              ptrs[0], ptrs[1], ptrs[2], wptr, wbytes, _stream(stream))
     return res
 
 
@@ -305,9 +378,9 @@ def pex_example_norms(X, G, N=None, workspace=None, stream=None):
     dt = _dtype_code(X)
     if N is None:
         N = torch.empty(B, dtype=torch.float32, device=X.device)
-    ws, wptr, wbytes = _workspace(pex_example_norms_workspace_bytes(B, T, din, dout, dt), X, workspace)
-    _check(lib().pex_example_norms(_dev(X, "X"), _dev(G, "G"), B, T, din, dout, dt, _dev(N, "N"), wptr, wbytes,
-                                   _stream(stream)))
+    ws, wptr, wbytes = _workspace(pex_example_norms_workspace_bytes(B, T, din, dout, dt), X, workspace, stream)
+    _invoke(lib().pex_example_norms, _dev(X, "X"), _dev(G, "G"), B, T, din, dout, dt, _f32(N, "N", numel=B), wptr, wbytes,
+                                   _stream(stream))
     return N
 
 
@@ -316,13 +389,11 @@ def pex_weighted_sum(X, G, w, S=None, workspace=None, stream=None):
     import torch
     B, T, din, dout = _shapes(X, G)
     dt = _dtype_code(X)
-    if w.dtype != torch.float32 or w.numel() != B:
-        raise ValueError("w must be float32 with one weight per example")
     if S is None:
         S = torch.empty(din, dout, dtype=torch.float32, device=X.device)
-    ws, wptr, wbytes = _workspace(pex_weighted_sum_workspace_bytes(B, T, din, dout, dt), X, workspace)
-    _check(lib().pex_weighted_sum(_dev(X, "X"), _dev(G, "G"), _dev(w, "w"), B, T, din, dout, dt, _dev(S, "S"), wptr,
-                                  wbytes, _stream(stream)))
+    ws, wptr, wbytes = _workspace(pex_weighted_sum_workspace_bytes(B, T, din, dout, dt), X, workspace, stream)
+    _invoke(lib().pex_weighted_sum, _dev(X, "X"), _dev(G, "G"), _f32(w, "w", numel=B), B, T, din, dout, dt, _f32(S, "S", shape=(din, dout)), wptr,
+                                  wbytes, _stream(stream))
     return S
 
 
@@ -333,9 +404,9 @@ def pex_stat_power(X, G, alpha, S=None, workspace=None, stream=None):
     dt = _dtype_code(X)
     if S is None:
         S = torch.empty(din, dout, dtype=torch.float32, device=X.device)
-    ws, wptr, wbytes = _workspace(pex_stat_power_workspace_bytes(B, T, din, dout, dt), X, workspace)
-    _check(lib().pex_stat_power(_dev(X, "X"), _dev(G, "G"), B, T, din, dout, dt, float(alpha), _dev(S, "S"), wptr,
-                                wbytes, _stream(stream)))
+    ws, wptr, wbytes = _workspace(pex_stat_power_workspace_bytes(B, T, din, dout, dt), X, workspace, stream)
+    _invoke(lib().pex_stat_power, _dev(X, "X"), _dev(G, "G"), B, T, din, dout, dt, float(alpha), _f32(S, "S", shape=(din, dout)), wptr,
+                                wbytes, _stream(stream))
     return S
 
 
@@ -346,7 +417,7 @@ def pex_token_norms(X, G, N_tok=None, stream=None):
     dt = _dtype_code(X)
     if N_tok is None:
         N_tok = torch.empty(B, T, dtype=torch.float32, device=X.device)
-    _check(lib().pex_token_norms(_dev(X, "X"), _dev(G, "G"), B, T, din, dout, dt, _dev(N_tok, "N_tok"), _stream(stream)))
+    _invoke(lib().pex_token_norms, _dev(X, "X"), _dev(G, "G"), B, T, din, dout, dt, _f32(N_tok, "N_tok", numel=B * T), _stream(stream))
     return N_tok
 
 
@@ -357,9 +428,9 @@ def pex_token_sq(X, G, S=None, workspace=None, stream=None):
     dt = _dtype_code(X)
     if S is None:
         S = torch.empty(din, dout, dtype=torch.float32, device=X.device)
-    ws, wptr, wbytes = _workspace(pex_token_sq_workspace_bytes(B, T, din, dout, dt), X, workspace)
-    _check(lib().pex_token_sq(_dev(X, "X"), _dev(G, "G"), B, T, din, dout, dt, _dev(S, "S"), wptr, wbytes,
-                              _stream(stream)))
+    ws, wptr, wbytes = _workspace(pex_token_sq_workspace_bytes(B, T, din, dout, dt), X, workspace, stream)
+    _invoke(lib().pex_token_sq, _dev(X, "X"), _dev(G, "G"), B, T, din, dout, dt, _f32(S, "S", shape=(din, dout)), wptr, wbytes,
+                              _stream(stream))
     return S
 
 
@@ -367,31 +438,24 @@ def pex_adam_update(theta, m, v, S_id, S_sq, variant, params: AdamParams, stream
     """One in-place step of the Adam family (Algorithm 1).  ``S_sq`` may be None for plain Adam."""
     code = VARIANT.get(variant, variant)
     n = theta.numel()
-    for name, t in (("m", m), ("v", v), ("S_id", S_id)) + ((("S_sq", S_sq),) if S_sq is not None else ()):
-        if t.numel() != n:
-            raise ValueError(f"{name} has {t.numel()} elements, theta has {n}")
-    _check(lib().pex_adam_update(_dev(theta, "theta"), _dev(m, "m"), _dev(v, "v"), _dev(S_id, "S_id"),
-                                 _dev(S_sq, "S_sq") if S_sq is not None else None, n, code,
-                                 ctypes.byref(params), _stream(stream)))
+    _invoke(lib().pex_adam_update, _f32(theta, "theta"), _f32(m, "m", n), _f32(v, "v", n), _f32(S_id, "S_id", n),
+                                 _f32(S_sq, "S_sq", n) if S_sq is not None else None, n, code,
+                                 ctypes.byref(params), _stream(stream))
 
 
 def pex_signsgd_update(theta, m, S_sign, lr, beta, weight_decay, B, debias=False, step=1, stream=None):
     """One in-place MicroSignSGD step (EMA o avg o sign)."""
     n = theta.numel()
-    if m.numel() != n or S_sign.numel() != n:
-        raise ValueError("theta, m and S_sign must have the same number of elements")
-    _check(lib().pex_signsgd_update(_dev(theta, "theta"), _dev(m, "m"), _dev(S_sign, "S_sign"), n, lr, beta,
-                                    weight_decay, int(B), int(bool(debias)), int(step), _stream(stream)))
+    _invoke(lib().pex_signsgd_update, _f32(theta, "theta"), _f32(m, "m", n), _f32(S_sign, "S_sign", n), n, lr, beta,
+                                    weight_decay, int(B), int(bool(debias)), int(step), _stream(stream))
 
 
 def pex_sign_update(theta, m, S, variant, lr, beta, weight_decay, B, debias=False, step=1, stream=None):
     """One in-place step of 'microsignsgd' | 'signsgd' | 'signema' (Sec. 3.1); S is the sum of per-example signs for
     the first and the sum of gradients for the other two."""
     n = theta.numel()
-    if m.numel() != n or S.numel() != n:
-        raise ValueError("theta, m and S must have the same number of elements")
-    _check(lib().pex_sign_update(_dev(theta, "theta"), _dev(m, "m"), _dev(S, "S"), n, SIGN_VARIANT.get(variant, variant),
-                                 lr, beta, weight_decay, int(B), int(bool(debias)), int(step), _stream(stream)))
+    _invoke(lib().pex_sign_update, _f32(theta, "theta"), _f32(m, "m", n), _f32(S, "S", n), n, SIGN_VARIANT.get(variant, variant),
+                                 lr, beta, weight_decay, int(B), int(bool(debias)), int(step), _stream(stream))
 
 
 def pex_moment_track_workspace_bytes(n) -> int:
@@ -403,15 +467,12 @@ def pex_moment_track(ema_adam, ema_micro, S_id, S_sq, params: MomentParams, sums
     float64 tensor [2] = (sum of mu^2-hat, sum of sigma^2-hat) over the parameters."""
     import torch
     n = ema_adam.numel()
-    for name, t in (("ema_micro", ema_micro), ("S_id", S_id), ("S_sq", S_sq)):
-        if t.numel() != n:
-            raise ValueError(f"{name} has {t.numel()} elements, ema_adam has {n}")
     if sums is None:
         sums = torch.empty(2, dtype=torch.float64, device=ema_adam.device)
-    ws, wptr, wbytes = _workspace(pex_moment_track_workspace_bytes(n), ema_adam, workspace)
-    _check(lib().pex_moment_track(_dev(ema_adam, "ema_adam"), _dev(ema_micro, "ema_micro"), _dev(S_id, "S_id"),
-                                  _dev(S_sq, "S_sq"), n, ctypes.byref(params), _dev(sums, "sums"), wptr, wbytes,
-                                  _stream(stream)))
+    ws, wptr, wbytes = _workspace(pex_moment_track_workspace_bytes(n), ema_adam, workspace, stream)
+    _invoke(lib().pex_moment_track, _f32(ema_adam, "ema_adam"), _f32(ema_micro, "ema_micro", n), _f32(S_id, "S_id", n),
+                                  _f32(S_sq, "S_sq", n), n, ctypes.byref(params), _f64(sums, "sums", 2), wptr, wbytes,
+                                  _stream(stream))
     return sums
 
 
@@ -436,12 +497,12 @@ def pex_embed_stat(ids, G, V, want, out=None, workspace=None, stream=None):
             if S is None:
                 S = torch.empty(V, d, dtype=torch.float32, device=G.device)
             res[name] = S
-            ptrs.append(_dev(S, name))
+            ptrs.append(_f32(S, name, shape=(V, d)))
         else:
             ptrs.append(None)
-    ws, wptr, wbytes = _workspace(pex_embed_stat_workspace_bytes(B, T, V, d), G, workspace)
-    _check(lib().pex_embed_stat(_dev(ids, "ids"), ids.element_size(), _dev(G, "G"), B, T, V, d, _dtype_code(G), mask,
-                                ptrs[0], ptrs[1], ptrs[2], wptr, wbytes, _stream(stream)))
+    ws, wptr, wbytes = _workspace(pex_embed_stat_workspace_bytes(B, T, V, d), G, workspace, stream)
+    _invoke(lib().pex_embed_stat, _dev(ids, "ids"), ids.element_size(), _dev(G, "G"), B, T, V, d, _dtype_code(G), mask,
+                                ptrs[0], ptrs[1], ptrs[2], wptr, wbytes, _stream(stream))
     return res
 
 
@@ -471,8 +532,8 @@ def pex_mfma_probe(operands, workgroups, iters, sink=None, stream=None):
     if sink is None:
         sink = torch.empty(pex_mfma_probe_sink_floats(workgroups), dtype=torch.float32, device=operands.device)
     flop = ctypes.c_double(0.0)
-    _check(lib().pex_mfma_probe(_dev(operands, "operands"), int(workgroups), int(iters), _dev(sink, "sink"), ctypes.byref(flop),
-                                _stream(stream)))
+    _invoke(lib().pex_mfma_probe, _dev(operands, "operands"), int(workgroups), int(iters), _f32(sink, "sink"), ctypes.byref(flop),
+                                _stream(stream))
     return flop.value, sink
 
 
@@ -486,8 +547,8 @@ def pex_sum_squares(x, acc=None, accumulate=False, workspace=None, stream=None):
     n = x.numel()
     if acc is None:
         acc = torch.zeros(1, dtype=torch.float64, device=x.device)
-    ws, wptr, wbytes = _workspace(pex_sum_squares_workspace_bytes(n), x, workspace)
-    _check(lib().pex_sum_squares(_dev(x, "x"), n, _dev(acc, "acc"), int(bool(accumulate)), wptr, wbytes, _stream(stream)))
+    ws, wptr, wbytes = _workspace(pex_sum_squares_workspace_bytes(n), x, workspace, stream)
+    _invoke(lib().pex_sum_squares, _f32(x, "x"), n, _f64(acc, "acc", 1), int(bool(accumulate)), wptr, wbytes, _stream(stream))
     return acc
 
 
@@ -496,9 +557,6 @@ def pex_adam_update_clipped(theta, m, v, S_id, S_sq, variant, params: AdamParams
     ``sum_sq`` is the double on the GPU that pex_sum_squares accumulated over the S_id of all layers."""
     code = VARIANT.get(variant, variant)
     n = theta.numel()
-    for name, t in (("m", m), ("v", v), ("S_id", S_id)) + ((("S_sq", S_sq),) if S_sq is not None else ()):
-        if t.numel() != n:
-            raise ValueError(f"{name} has {t.numel()} elements, theta has {n}")
-    _check(lib().pex_adam_update_clipped(_dev(theta, "theta"), _dev(m, "m"), _dev(v, "v"), _dev(S_id, "S_id"),
-                                         _dev(S_sq, "S_sq") if S_sq is not None else None, n, code, ctypes.byref(params),
-                                         _dev(sum_sq, "sum_sq"), float(max_norm), _stream(stream)))
+    _invoke(lib().pex_adam_update_clipped, _f32(theta, "theta"), _f32(m, "m", n), _f32(v, "v", n), _f32(S_id, "S_id", n),
+                                         _f32(S_sq, "S_sq", n) if S_sq is not None else None, n, code, ctypes.byref(params),
+                                         _f64(sum_sq, "sum_sq", 1), float(max_norm), _stream(stream))

@@ -34,6 +34,13 @@ def build(verbose: bool = False, extra_flags=()) -> str:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
+    # the four-wave kernel's assumptions about its own machine code, checked while the objects compile
+    from . import isa_check
+    isa_error = None
+    try:
+        isa_check.check_all(HIPCC, [*FLAGS, *extra_flags], os.path.join(CSRC, "pex_stat_bf16.hip"))
+    except (isa_check.IsaCheckError, subprocess.CalledProcessError) as e:
+        isa_error = e
     failed = False
     for src, p in procs:
         out, _ = p.communicate()
@@ -46,6 +53,8 @@ def build(verbose: bool = False, extra_flags=()) -> str:
             failed = True
     if failed:
         raise RuntimeError("libpex build failed")
+    if isa_error is not None:
+        raise RuntimeError(f"libpex build failed: {isa_error}")
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     subprocess.run(cmd, check=True)
     return LIB

@@ -1,5 +1,6 @@
 // pex_api.hip -- the C ABI of libpex: host-side validation, planning and kernel dispatch.
 // Every entry point validates first and launches nothing on error.
+#include <atomic>
 #include <cstdlib>
 #include <mutex>
 
@@ -34,22 +35,42 @@ static hipError_t scratch_address(void** out)
     return hipSuccess;
 }
 
-static int env_int(const char* name, int dflt)
+// Planner options.  Their first values come from the environment, read once per process; afterwards only
+// pex_set_option changes them.  Atomics, so a host thread that plans while another one sets an option reads a
+// whole value; a plan made under one value and launched under another is caught as PEX_ERR_WORKSPACE.
+struct Options {
+    std::atomic<int> v[2];
+};
+
+static int clamp_option(int opt, int value)
 {
-    const char* s = getenv(name);
-    if (!s || !*s) return dflt;
-    return atoi(s);
+    if (opt == PEX_OPT_MAX_SPLIT) return value < 1 ? 1 : (value > 32 ? 32 : value);
+    return value < 0 ? 0 : (value > 2 ? 2 : value);      // PEX_OPT_TOKEN_PRESQUARE
 }
+
+static Options& options()
+{
+    static Options o;
+    static std::once_flag once;
+    std::call_once(once, [] {
+        const char* names[2] = {"PEX_MAX_SPLIT", "PEX_TOKEN_PRESQUARE"};
+        const int dflt[2] = {32, 1};
+        for (int k = 0; k < 2; ++k) {
+            const char* e = getenv(names[k]);
+            o.v[k].store(clamp_option(k, (e && *e) ? atoi(e) : dflt[k]));
+        }
+    });
+    return o;
+}
+
+static int option(int opt) { return options().v[opt].load(); }
 
 StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt, Mode mode)
 {
     StatPlan p{};
     const bool per_example = (mode == MODE_SQUARE || mode == MODE_SIGN || mode == MODE_NORMS || mode == MODE_WEIGHTED || mode == MODE_POWER);
-    // PEX_FORCE_GENERIC=1 routes bf16 through the SIMT kernel (a tuning/debugging aid, not a fallback:
-    // both kernels are device code of this library).
-    const bool force_generic = env_int("PEX_FORCE_GENERIC", 0) != 0;
-    p.kernel = (dt == PEX_BF16 && !force_generic && bf16_supports(B, T, din, dout)) ? 1 : 0;
-    if (dt == PEX_F32 && !force_generic && f32_mfma_supports(B, T, din, dout, mode)) p.kernel = 2;
+    p.kernel = (dt == PEX_BF16 && bf16_supports(B, T, din, dout)) ? 1 : 0;
+    if (dt == PEX_F32 && f32_mfma_supports(B, T, din, dout, mode)) p.kernel = 2;
 
     // The unit the batch axis is split in: whole examples when phi is applied per example (the sum over
     // the sequence must be complete before phi), slabs of 64 rows of the flattened [B*T] axis otherwise.
@@ -67,7 +88,7 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
     tiles = ((din + bm - 1) / bm) * ((dout + bn - 1) / bn);
     const int64_t slab = 64;
     units = per_example ? B : (B * T + slab - 1) / slab;
-    const int max_split = env_int("PEX_MAX_SPLIT", 32);
+    const int max_split = option(PEX_OPT_MAX_SPLIT);
     int64_t nsplit = 1, per = units;
     if (p.kernel != 1) {
         nsplit = (target + tiles - 1) / tiles;
@@ -102,11 +123,12 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
     // every slab (about +60 % time); squaring them once into bf16 copies costs one pass over X and G at HBM speed
     // (~5.5 TB/s, 4 bytes moved per element).  The copies win when din*dout/(din+dout) is large.
     p.presq_bytes = 0;
-    if (mode == MODE_TOKEN_SQ && p.kernel == 1 && env_int("PEX_TOKEN_PRESQUARE", 1) != 0) {
+    const int presquare = option(PEX_OPT_TOKEN_PRESQUARE);
+    if (mode == MODE_TOKEN_SQ && p.kernel == 1 && presquare != 0) {
         const double elems = (double)B * (double)T * (double)(din + dout);
         const double t_pre = 4.0 * elems / 5.5e12 + 6.0e-6;
         const double t_fused_extra = 0.6 * 2.0 * (double)B * (double)T * (double)din * (double)dout / 1.3e15;
-        if (t_pre < t_fused_extra || env_int("PEX_TOKEN_PRESQUARE", 1) == 2)
+        if (t_pre < t_fused_extra || presquare == 2)
             p.presq_bytes = (((size_t)B * (size_t)T * (size_t)(din + dout) * 2) + 255) & ~(size_t)255;
     }
     p.ws_bytes = p.presq_bytes + (nsplit > 1 ? (size_t)nsplit * (size_t)din * (size_t)dout * sizeof(float) : 0);
@@ -124,6 +146,9 @@ static pex_status check_stat_args(const void* X, const void* G, int64_t B, int64
     const int64_t lim = (int64_t)1 << 31;
     if (din >= lim || dout >= lim || B >= lim || T >= lim || B * T >= lim) return PEX_ERR_SHAPE;
     if (((uintptr_t)X | (uintptr_t)G | (uintptr_t)S) & 15u) return PEX_ERR_ALIGN;
+    // The fp32 and the SIMT kernels put the tiles of din (128 and 64 rows) in the second grid dimension.
+    const StatPlan plan = plan_stat(B, T, din, dout, dt, MODE_IDENTITY);
+    if (plan.kernel != 1 && din > 65535 * (int64_t)(plan.kernel == 2 ? 128 : 64)) return PEX_ERR_SHAPE;
     return PEX_OK;
 }
 
@@ -222,7 +247,21 @@ const char* pex_status_string(pex_status s)
     return "PEX: unknown status";
 }
 
-int pex_version(void) { return 100; }
+int pex_version(void) { return 200; }
+
+pex_status pex_set_option(pex_option opt, int32_t value)
+{
+    if (opt != PEX_OPT_MAX_SPLIT && opt != PEX_OPT_TOKEN_PRESQUARE) return PEX_ERR_PHI;
+    if (value != clamp_option(opt, value)) return PEX_ERR_SHAPE;
+    options().v[opt].store(value);
+    return PEX_OK;
+}
+
+int32_t pex_get_option(pex_option opt)
+{
+    if (opt != PEX_OPT_MAX_SPLIT && opt != PEX_OPT_TOKEN_PRESQUARE) return -1;
+    return option(opt);
+}
 
 size_t pex_stat_workspace_bytes(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt, pex_phi phi)
 {

@@ -685,8 +685,9 @@ __global__ __launch_bounds__(QuadTile::NT, 1) void stat_bf16_quad_kernel(const u
     };
     auto slab_range = [&]() {
         const int nx = xadv - xcut, ng = gadv - gcut;
-        rx = int4_t{(int)(uint32_t)xptr, (int)(uint32_t)(xptr >> 32), nx > 0 ? nx : 0, 0x00020000};
-        rg = int4_t{(int)(uint32_t)gptr, (int)(uint32_t)(gptr >> 32), ng > 0 ? ng : 0, 0x00020000};
+        // word 1: address bits 32..47 only, so that stride and swizzle stay 0 whatever the upper address bits are
+        rx = int4_t{(int)(uint32_t)xptr, (int)((uint32_t)(xptr >> 32) & 0xffffu), nx > 0 ? nx : 0, 0x00020000};
+        rg = int4_t{(int)(uint32_t)gptr, (int)((uint32_t)(gptr >> 32) & 0xffffu), ng > 0 ? ng : 0, 0x00020000};
     };
     auto slab_advance = [&]() {
         xptr += (uint32_t)xadv;

@@ -15,3 +15,18 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
+
+
+@pytest.fixture
+def pex_option():
+    """Set planner options of libpex for one test; the values in force before are put back afterwards."""
+    import paper_2510_00236_amd as pex
+    saved = {}
+
+    def set_option(name, value):
+        saved.setdefault(name, pex.pex_get_option(name))
+        pex.pex_set_option(name, value)
+
+    yield set_option
+    for name, value in saved.items():
+        pex.pex_set_option(name, value)

@@ -37,6 +37,27 @@ def test_version_and_status_strings():
     assert "unknown" in pex.status_string(99)
 
 
+def test_planner_options_are_clamped_and_change_the_plan():
+    assert pex.pex_get_option("max_split") == 32 and pex.pex_get_option("token_presquare") == 1
+    L = pex.lib()
+    assert L.pex_set_option(7, 1) == 4 and L.pex_get_option(7) == -1
+    assert L.pex_set_option(0, 0) == 2 and L.pex_set_option(0, 33) == 2 and L.pex_set_option(1, 3) == 2
+    shape = (32, 256, 512, 2048)
+    full = pex.pex_stat_workspace_bytes(*shape, pex.PEX_BF16, "sign")
+    try:
+        pex.pex_set_option("max_split", 4)
+        assert pex.pex_get_option("max_split") == 4
+        assert 0 < pex.pex_stat_workspace_bytes(*shape, pex.PEX_BF16, "sign") <= 4 * 512 * 2048 * 4 < full
+        pex.pex_set_option("max_split", 1)
+        assert pex.pex_stat_workspace_bytes(*shape, pex.PEX_BF16, "sign") == 0
+    finally:
+        pex.pex_set_option("max_split", 32)
+    assert pex.pex_stat_workspace_bytes(*shape, pex.PEX_BF16, "sign") == full
+    # a width whose tiles do not fit the second grid dimension of the fp32 and SIMT kernels is refused up front
+    assert L.pex_stat(0x1000, 0x2000, 1, 1, 65535 * 128 + 1, 8, 0, 0, 0x3000, None, 0, None) == 2
+    assert L.pex_stat(0x1000, 0x2000, 1, 1, 65535 * 64 + 1, 8, 1, 0, 0x3000, None, 0, None) == 2
+
+
 def test_struct_layout_matches_header():
     # 8 floats, int64, int32 (+ padding): the layout a C compiler gives pex_adam_params
     assert ctypes.sizeof(pex.AdamParams) == 48
@@ -179,3 +200,40 @@ def test_binding_refuses_cpu_tensors():
     X = torch.zeros(2, 4, 8)
     with pytest.raises(ValueError, match="GPU"):
         pex.pex_stat(X, X.clone(), "square", S=torch.zeros(8, 8))
+
+
+def test_binding_checks_type_and_size_of_every_buffer_it_passes_as_a_raw_pointer():
+    """A state tensor of another element type or size would make a kernel run past its end; the binding refuses it
+    before anything reaches the library (these checks come before the is-it-on-the-GPU check, so they run here)."""
+    import torch
+    n = 64
+    th, m, v, a, q = (torch.zeros(n) for _ in range(5))
+    p = pex.AdamParams(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, grad_scale=1.0, sq_scale=1.0, step=1, B=4)
+    with pytest.raises(TypeError, match="m must be torch.float32"):
+        pex.pex_adam_update(th, m.to(torch.bfloat16), v, a, q, "microadam", p)
+    with pytest.raises(TypeError, match="v must be torch.float32"):
+        pex.pex_adam_update(th, m, v.double(), a, q, "microadam", p)
+    with pytest.raises(ValueError, match="S_sq must have 64 elements"):
+        pex.pex_adam_update(th, m, v, a, q[:32], "microadam", p)
+    with pytest.raises(TypeError, match="S_sign must be torch.float32"):
+        pex.pex_signsgd_update(th, m, a.to(torch.int32), 1e-3, 0.9, 0.0, 4)
+    with pytest.raises(ValueError, match="m must have 64 elements"):
+        pex.pex_sign_update(th, torch.zeros(n + 4), a, "signsgd", 1e-3, 0.9, 0.0, 4)
+    with pytest.raises(TypeError, match="sum_sq must be torch.float64"):
+        pex.pex_adam_update_clipped(th, m, v, a, q, "microadam", p, torch.zeros(1), 1.0)
+    X, G = torch.zeros(2, 4, 8), torch.zeros(2, 4, 16)
+    with pytest.raises(ValueError, match=r"S must have shape \(8, 16\)"):
+        pex.pex_stat(X, G, "square", S=torch.zeros(16, 8))
+    with pytest.raises(TypeError, match="S must be torch.float32"):
+        pex.pex_stat(X, G, "square", S=torch.zeros(8, 16, dtype=torch.float64))
+    with pytest.raises(TypeError, match="workspace must be uint8"):
+        pex.pex_stat(X, G, "square", S=torch.zeros(8, 16), workspace=torch.zeros(1 << 20))
+    with pytest.raises(ValueError, match="workspace holds 4 bytes"):
+        pex.pex_stat(X, G, "square", S=torch.zeros(8, 16), workspace=torch.zeros(4, dtype=torch.uint8))
+    with pytest.raises(ValueError, match="w must have 2 elements"):
+        pex.pex_weighted_sum(X, G, torch.zeros(3), S=torch.zeros(8, 16))
+    with pytest.raises(ValueError, match="N must have 2 elements"):
+        pex.pex_example_norms(X, G, N=torch.zeros(5))
+    with pytest.raises(TypeError, match="sums must be torch.float64"):
+        mp = pex.MomentParams(beta2=0.95, grad_scale=0.25, sq_scale=0.25, B=4, debias=1, step=1)
+        pex.pex_moment_track(th, m, a, q, mp, sums=torch.zeros(2))

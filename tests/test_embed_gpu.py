@@ -83,8 +83,11 @@ def test_output_buffers_workspace_and_stream():
         pex.pex_embed_stat(idd, Gd, V, ("square",), out=out, workspace=ws, stream=st)
     st.synchronize()
     assert torch.equal(out["square"], ref)
-    with pytest.raises(pex.PexError):
+    with pytest.raises(ValueError, match="workspace holds 64 bytes"):        # the binding's own check
         pex.pex_embed_stat(idd, Gd, V, ("square",), workspace=ws[:64])
+    rc = pex.lib().pex_embed_stat(idd.data_ptr(), 8, Gd.data_ptr(), B, T, V, d, pex.PEX_BF16, 2, None, out["square"].data_ptr(),
+                                  None, ws.data_ptr(), 64, None)                  # and the library's, through the C symbol
+    assert rc == 6
     with pytest.raises(TypeError):
         pex.pex_embed_stat(idd.to(torch.int16), Gd, V, ("square",))
 

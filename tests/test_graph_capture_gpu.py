@@ -77,11 +77,11 @@ def test_a_whole_step_replays_from_a_graph():
         assert torch.equal(graphed[k], eager[k]), k
 
 
-def test_four_wave_contraction_is_deterministic_and_replays_from_a_graph(monkeypatch):
+def test_four_wave_contraction_is_deterministic_and_replays_from_a_graph(pex_option):
     """The plain contraction on its four-wave kernel (rows unsplit, so every workgroup runs the long loop): two eager
     runs agree bit for bit (no atomics, fixed order), and so do three replays of a captured launch, with eager work
     between them."""
-    monkeypatch.setenv("PEX_MAX_SPLIT", "1")
+    pex_option("max_split", 1)
     B, T, din, dout = 3, 701, 328, 520
     X, G = si.custom(B, T, din, dout, dtype="bf16", seed=11)
     Xd, Gd = X.to(DEV), G.to(DEV)

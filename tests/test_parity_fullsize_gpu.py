@@ -104,3 +104,25 @@ def test_full_size_fp32_inputs_sampled():
     assert_real_stat(pick(got["square"]), st.S_sq, "f32", "fp32 square", elementwise=True)
     assert_sign_stat(pick(got["sign"]), st.S_sign, st.amb, "fp32 sign")
     assert_real_stat(pick(got["token_sq"]), tok, "f32", "fp32 token_sq", elementwise=True)
+
+
+def test_full_size_every_entry_c4_1b_up():
+    """One layer at full size with nothing sampled: all 16.8 M entries of identity, square and sign from one pass of
+    the fp64 oracle over B=16, T=2048, 2048 x 8192, and all entries of the per-token square from a second."""
+    w = si.WORKLOADS["c4_1b_up"]
+    X, G = si.make(w, seed=0)
+    Xd, Gd = X.to(DEV), G.to(DEV)
+    got = {phi: pex.pex_stat(Xd, Gd, phi) for phi in ("identity", "square", "sign")}
+    got["token_sq"] = pex.pex_token_sq(Xd, Gd)
+    torch.cuda.synchronize()
+    got = {k: v.cpu().numpy().astype(np.float64) for k, v in got.items()}
+    del Xd, Gd
+    Xn, Gn = si.widen(X), si.widen(G)
+    st = oracle.stat(Xn, Gn)
+    assert_real_stat(got["identity"], st.S_id, "bf16", "c4_1b_up identity, every entry", elementwise=False)
+    assert_real_stat(got["square"], st.S_sq, "bf16", "c4_1b_up square, every entry", elementwise=True)
+    n_diff = assert_sign_stat(got["sign"], st.S_sign, st.amb, "c4_1b_up sign, every entry")
+    print(f"c4_1b_up, every entry: {n_diff} sign counts differ inside the ambiguity band, {int((st.amb > 0).sum())} entries in it")
+    del st
+    tok = oracle.token_sq(Xn, Gn)
+    assert_real_stat(got["token_sq"], tok, "bf16", "c4_1b_up token_sq, every entry", elementwise=True, bar=8e-3, eng=None)

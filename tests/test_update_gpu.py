@@ -238,3 +238,32 @@ def test_sum_of_squares_and_clipped_updates_match_oracle(n):
     pex.pex_adam_update_clipped(th1, m1, v1, Sd, Sq, "microadam", prm, acc, float(4.0 * norm))
     pex.pex_adam_update(th2, m2, v2, Sd, Sq, "microadam", prm)
     assert torch.equal(th1, th2) and torch.equal(m1, m2) and torch.equal(v1, v2)
+
+
+def test_updates_at_the_full_parameter_count_of_the_1b_layer():
+    """One MicroAdam and one MicroSignSGD step over the 16,777,216 parameters of the 2048 x 8192 layer (the size
+    bench.py times): every parameter against the fp64 oracle."""
+    n, B = 2048 * 8192, 16
+    theta0, m0, v0 = si.optimizer_state(n, seed=3)
+    g = torch.Generator().manual_seed(77)
+    S_id = torch.randn(n, generator=g) * (B ** 0.5) * 1e-2 + B * 1e-2
+    S_sq = (S_id * S_id) / B + torch.rand(n, generator=g) * B * 1e-4            # >= S_id^2 / B, as Cauchy-Schwarz demands
+    S_sg = torch.randint(-B // 2, B // 2 + 1, (n,), generator=g).float() * 2    # same parity as B
+    kw = dict(lr=2.0 / 1024, beta1=0.9, beta2=0.95, eps=1e-8, eps_root=0.0, weight_decay=1e-4,
+              grad_scale=1.0 / B, sq_scale=1.0 / B, step=1, B=B)
+    th, m, v = theta0.to(DEV), m0.to(DEV), v0.to(DEV)
+    pex.pex_adam_update(th, m, v, S_id.to(DEV), S_sq.to(DEV), "microadam", pex.AdamParams(**kw))
+    th2, m2 = theta0.to(DEV), m0.to(DEV)
+    pex.pex_signsgd_update(th2, m2, S_sg.to(DEV), 1e-3, 0.9, 1e-4, B)
+    torch.cuda.synchronize()
+    t0 = theta0.double().numpy()
+    rth, rm, rv = ou.adam_family_step(t0, m0.double().numpy(), v0.double().numpy(), S_id.numpy(), S_sq.numpy(),
+                                      ou.MICROADAM, ou.AdamParams(**kw))
+    np.testing.assert_allclose(m.cpu().double().numpy(), rm, rtol=2e-6, atol=4e-7 * np.abs(rm).max())
+    np.testing.assert_allclose(v.cpu().double().numpy(), rv, rtol=4e-6, atol=4e-7 * np.abs(rv).max())
+    inc_got, inc_ref = th.cpu().double().numpy() - t0, rth - t0
+    assert np.abs(inc_got - inc_ref).max() <= 1e-3 * np.abs(inc_ref).max()
+    rth2, rm2 = ou.microsignsgd_step(t0, m0.double().numpy(), S_sg.numpy(), 1e-3, 0.9, 1e-4, B, False, 1)
+    np.testing.assert_allclose(m2.cpu().double().numpy(), rm2, rtol=2e-6, atol=1e-9)
+    inc2_got, inc2_ref = th2.cpu().double().numpy() - t0, rth2 - t0
+    assert np.abs(inc2_got - inc2_ref).max() <= 1e-3 * np.abs(inc2_ref).max() + 1e-9

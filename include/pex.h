@@ -64,12 +64,18 @@ int pex_version(void);
  *   PEX_OPT_TOKEN_PRESQUARE  0 = pex_token_sq always squares inside the contraction, 1 = chosen by a cost model
  *                            (default), 2 = always through bf16 copies of the squares (environment
  *                            PEX_TOKEN_PRESQUARE).  Both routes round alike and give the same bits.
+ *   PEX_OPT_WIDE_BLOCKS      pex_stat(square), pex_weighted_sum and pex_stat_power on bf16 layers keep two fp32
+ *                            register tiles and have two block shapes, 256 x 128 and 256 x 192.  0 = the narrow one
+ *                            only, 1 = the first columns of S on the wide shape where a cost model says so
+ *                            (default: layers whose wide blocks fill whole rounds of the 256 compute units),
+ *                            2 = as many columns as fit on the wide shape, always (environment PEX_WIDE_BLOCKS).
+ *                            The result is the same bits under every value.
  * An option changes the plan and with it the *_workspace_bytes of later calls: query again after setting one.  A
  * call whose workspace was sized under another value returns PEX_ERR_WORKSPACE if it is too small.
  * pex_set_option: PEX_ERR_PHI for an unknown option, PEX_ERR_SHAPE for a value out of range.  pex_get_option: the
  * current value, -1 for an unknown option.
  */
-typedef enum { PEX_OPT_MAX_SPLIT = 0, PEX_OPT_TOKEN_PRESQUARE = 1 } pex_option;
+typedef enum { PEX_OPT_MAX_SPLIT = 0, PEX_OPT_TOKEN_PRESQUARE = 1, PEX_OPT_WIDE_BLOCKS = 2 } pex_option;
 pex_status pex_set_option(pex_option opt, int32_t value);
 int32_t pex_get_option(pex_option opt);
 
@@ -87,7 +93,9 @@ int32_t pex_get_option(pex_option opt);
  *                               holds partial sums over groups of examples when the batch is split over
  *                               workgroups; it never holds a per-example gradient, and its size is at most
  *                               32 * din*dout*4 bytes, whatever B (reached by small layers only, where
- *                               many groups are needed to occupy the chip; none at the 1B-scale shapes).
+ *                               many groups are needed to occupy the chip; at the 1B-scale shapes identity
+ *                               and sign need none, and square splits only the columns its wider block
+ *                               shape leaves over, in two groups: half the size of S).
  *   The contraction over T of one example is never split across workgroups (phi is applied to the complete
  *   sum over the sequence), the sum over b is taken in a fixed order.
  *   Any B,T,din,dout >= 1 is accepted with B*T, din, dout each < 2^31; fp32 inputs and bf16 layers whose rows are

@@ -38,14 +38,17 @@ static hipError_t scratch_address(void** out)
 // Planner options.  Their first values come from the environment, read once per process; afterwards only
 // pex_set_option changes them.  Atomics, so a host thread that plans while another one sets an option reads a
 // whole value; a plan made under one value and launched under another is caught as PEX_ERR_WORKSPACE.
+constexpr int NUM_OPTIONS = 3;
 struct Options {
-    std::atomic<int> v[2];
+    std::atomic<int> v[NUM_OPTIONS];
 };
+
+static bool known_option(int opt) { return opt >= 0 && opt < NUM_OPTIONS; }
 
 static int clamp_option(int opt, int value)
 {
     if (opt == PEX_OPT_MAX_SPLIT) return value < 1 ? 1 : (value > 32 ? 32 : value);
-    return value < 0 ? 0 : (value > 2 ? 2 : value);      // PEX_OPT_TOKEN_PRESQUARE
+    return value < 0 ? 0 : (value > 2 ? 2 : value);      // PEX_OPT_TOKEN_PRESQUARE, PEX_OPT_WIDE_BLOCKS
 }
 
 static Options& options()
@@ -53,9 +56,9 @@ static Options& options()
     static Options o;
     static std::once_flag once;
     std::call_once(once, [] {
-        const char* names[2] = {"PEX_MAX_SPLIT", "PEX_TOKEN_PRESQUARE"};
-        const int dflt[2] = {32, 1};
-        for (int k = 0; k < 2; ++k) {
+        const char* names[NUM_OPTIONS] = {"PEX_MAX_SPLIT", "PEX_TOKEN_PRESQUARE", "PEX_WIDE_BLOCKS"};
+        const int dflt[NUM_OPTIONS] = {32, 1, 1};
+        for (int k = 0; k < NUM_OPTIONS; ++k) {
             const char* e = getenv(names[k]);
             o.v[k].store(clamp_option(k, (e && *e) ? atoi(e) : dflt[k]));
         }
@@ -65,7 +68,34 @@ static Options& options()
 
 static int option(int opt) { return options().v[opt].load(); }
 
-StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt, Mode mode)
+// The bf16 kernels run one workgroup per compute unit, so a launch of `tiles` blocks with the batch in `ns` groups takes
+//   rounds(ns) * ceil(units / ns)  unit-times,  rounds = ceil(tiles * ns / 256),
+// and the fixed-order reduction of the partial sums reads ns copies of the output (s_bytes each) at ~4 TB/s.
+// Returns the cheapest cost over ns <= max_split and the split that reaches it.
+static double cheapest_split(int64_t tiles, int64_t units, double t_unit, double s_bytes, int max_split, int64_t* nsplit, int64_t* per)
+{
+    double best = 0.0;
+    const int64_t lim = units < max_split ? units : max_split;
+    for (int64_t ns = 1; ns <= lim; ++ns) {
+        const int64_t pu = (units + ns - 1) / ns;
+        const int64_t ns_eff = (units + pu - 1) / pu;
+        const int64_t rounds = (tiles * ns_eff + 255) / 256;
+        double cost = (double)rounds * (double)pu * t_unit;
+        if (ns_eff > 1) cost += (ns_eff + 1) * s_bytes / 4.0e12 + 3.0e-6;
+        if (ns == 1 || cost < best) { best = cost; *nsplit = ns_eff; *per = pu; }
+    }
+    return best;
+}
+
+// Sustained rate of one compute unit on the bf16 blocks, FLOP/s (measured on Gaussian operands, 1B-scale layers):
+// the larger the block, the fewer bytes go from L2 into LDS and from LDS into registers per FLOP.
+static double bf16_block_rate(int bm, int bn)
+{
+    const int area = bm * bn;
+    return area >= 256 * 256 ? 5.5e12 : (area >= 256 * 192 ? 4.8e12 : 4.3e12);
+}
+
+StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt, Mode mode, bool allow_wide)
 {
     StatPlan p{};
     const bool per_example = (mode == MODE_SQUARE || mode == MODE_SIGN || mode == MODE_NORMS || mode == MODE_WEIGHTED || mode == MODE_POWER);
@@ -90,6 +120,7 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
     units = per_example ? B : (B * T + slab - 1) / slab;
     const int max_split = option(PEX_OPT_MAX_SPLIT);
     int64_t nsplit = 1, per = units;
+    int64_t wide_cols = 0;
     if (p.kernel != 1) {
         nsplit = (target + tiles - 1) / tiles;
         if (nsplit > max_split) nsplit = max_split;
@@ -97,23 +128,43 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
         if (nsplit < 1) nsplit = 1;
         per = (units + nsplit - 1) / nsplit;
     } else {
-        // One workgroup per compute unit runs at a time, so the contraction takes
-        //   rounds(ns) * ceil(units / ns)  unit-times,  rounds = ceil(tiles * ns / 256),
-        // and the fixed-order reduction of the partial sums reads ns copies of S.  Pick the cheapest ns.
-        // A unit-time is one example (or 64 rows) on one tile at ~5.5 TFLOP/s per compute unit; the reduction
-        // streams at ~4 TB/s.
+        // A unit-time is one example (or 64 rows) on one block.
         const double rows_per_unit = per_example ? (double)T : (double)slab;
-        const double t_unit = 2.0 * rows_per_unit * bm * bn / 5.5e12;
-        const double s_bytes = (double)din * (double)dout * 4.0;
-        double best = 0.0;
-        const int64_t lim = units < max_split ? units : max_split;
-        for (int64_t ns = 1; ns <= lim; ++ns) {
-            const int64_t pu = (units + ns - 1) / ns;
-            const int64_t ns_eff = (units + pu - 1) / pu;
-            const int64_t rounds = (tiles * ns_eff + target - 1) / target;
-            double cost = (double)rounds * (double)pu * t_unit;
-            if (ns_eff > 1) cost += (ns_eff + 1) * s_bytes / 4.0e12 + 3.0e-6;
-            if (ns == 1 || cost < best) { best = cost; nsplit = ns_eff; per = pu; }
+        const double t_unit = 2.0 * rows_per_unit * bm * bn / bf16_block_rate(bm, bn);
+        double best = cheapest_split(tiles, units, t_unit, (double)din * (double)dout * 4.0, max_split, &nsplit, &per);
+        // One statistic on two register tiles may put its first columns on the wider block (256 x 192), whole batch
+        // per workgroup and straight into S, and only the remaining columns on the 256 x 128 block with a split of
+        // their own.  Worth it when the wide part fills whole rounds of 256 workgroups: tried for the largest
+        // number of wide block columns that fits k rounds, k = 1, 2, ..., and for all columns wide.
+        const int wide_opt = option(PEX_OPT_WIDE_BLOCKS);
+        if (allow_wide && wide_opt != 0 && (mode == MODE_SQUARE || mode == MODE_WEIGHTED || mode == MODE_POWER) && bm == 256 && bn == 128) {
+            int wm, wn;
+            bf16_wide_tile_shape(&wm, &wn);
+            const int64_t tiles_m = (din + wm - 1) / wm, max_wide = dout / wn;
+            const double t_wide = 2.0 * (double)T * wm * wn / bf16_block_rate(wm, wn);
+            int64_t tried = -1;
+            for (int64_t k = 1; k <= 65; ++k) {
+                int64_t na = k <= 64 ? (256 * k) / tiles_m : max_wide;
+                if (na > max_wide) na = max_wide;
+                if (na < 1 || na == tried) { if (na >= max_wide) break; continue; }
+                tried = na;
+                const int64_t rest = dout - na * wn;
+                double cost = (double)((tiles_m * na + 255) / 256) * (double)B * t_wide;
+                int64_t ns_r = 1, per_r = units;
+                if (rest > 0)
+                    cost += 5.0e-6 + cheapest_split(tiles_m * ((rest + bn - 1) / bn), units, t_unit, (double)din * (double)rest * 4.0, max_split,
+                                                    &ns_r, &per_r);
+                if (cost < best) { best = cost; wide_cols = na * wn; nsplit = ns_r; per = per_r; }
+                if (na >= max_wide) break;
+            }
+            if (wide_opt == 2 && max_wide >= 1) {      // forced: as many wide block columns as fit, whatever the cost
+                wide_cols = max_wide * wn;
+                const int64_t rest = dout - wide_cols;
+                nsplit = 1;
+                per = units;
+                if (rest > 0)
+                    cheapest_split(tiles_m * ((rest + bn - 1) / bn), units, t_unit, (double)din * (double)rest * 4.0, max_split, &nsplit, &per);
+            }
         }
     }
     nsplit = (units + per - 1) / per;      // no empty group
@@ -131,7 +182,8 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
         if (t_pre < t_fused_extra || presquare == 2)
             p.presq_bytes = (((size_t)B * (size_t)T * (size_t)(din + dout) * 2) + 255) & ~(size_t)255;
     }
-    p.ws_bytes = p.presq_bytes + (nsplit > 1 ? (size_t)nsplit * (size_t)din * (size_t)dout * sizeof(float) : 0);
+    p.wide_cols = wide_cols;
+    p.ws_bytes = p.presq_bytes + (nsplit > 1 ? (size_t)nsplit * (size_t)din * (size_t)(dout - wide_cols) * sizeof(float) : 0);
     if (mode == MODE_NORMS)   // no S at all: one partial of ||M_b||^2 per tile (and wave) and example
         p.ws_bytes = (size_t)(p.kernel == 1 ? bf16_norm_partials(din, dout) : generic_norm_partials(din, dout)) * (size_t)B * sizeof(float);
     return p;
@@ -171,20 +223,22 @@ static pex_status run_stat(const void* X, const void* G, int64_t B, int64_t T, i
         uint16_t* g2 = x2 + B * T * din;
         e = launch_square_bf16(X, x2, B * T * din, stream);
         if (e == hipSuccess) e = launch_square_bf16(G, g2, B * T * dout, stream);
-        if (e == hipSuccess) e = launch_stat_bf16(x2, g2, B, T, din, dout, MODE_IDENTITY, plan, out, stream);
+        if (e == hipSuccess) e = launch_stat_bf16(x2, g2, B, T, din, dout, MODE_IDENTITY, plan, S, partials, stream);
     } else if (plan.kernel == 2) {
         e = launch_stat_f32(X, G, B, T, din, dout, mode, plan, out, stream, weight, alpha);
     } else if (mode == MODE_POWER) {
-        e = plan.kernel == 1 ? launch_power_bf16(X, G, alpha, B, T, din, dout, plan, out, stream)
+        e = plan.kernel == 1 ? launch_power_bf16(X, G, alpha, B, T, din, dout, plan, S, partials, stream)
                              : launch_stat_generic(X, G, B, T, din, dout, dt, mode, plan, out, stream, nullptr, nullptr, alpha);
     } else if (mode == MODE_WEIGHTED) {
-        e = plan.kernel == 1 ? launch_weighted_bf16(X, G, weight, B, T, din, dout, plan, out, stream)
+        e = plan.kernel == 1 ? launch_weighted_bf16(X, G, weight, B, T, din, dout, plan, S, partials, stream)
                              : launch_stat_generic(X, G, B, T, din, dout, dt, mode, plan, out, stream, weight, nullptr);
-    } else if (plan.kernel == 1) e = launch_stat_bf16(X, G, B, T, din, dout, mode, plan, out, stream);
+    } else if (plan.kernel == 1) e = launch_stat_bf16(X, G, B, T, din, dout, mode, plan, S, partials, stream);
     else e = launch_stat_generic(X, G, B, T, din, dout, dt, mode, plan, out, stream);
     if (e != hipSuccess) return PEX_ERR_HIP;
     if (plan.nsplit > 1) {
-        e = launch_reduce_partials(partials, plan.nsplit, din * dout, S, stream);
+        // partial sums of the whole layer, or of the columns beyond the wide blocks only
+        e = plan.wide_cols > 0 ? launch_reduce_partials_cols(partials, plan.nsplit, din, dout - plan.wide_cols, S + plan.wide_cols, dout, stream)
+                               : launch_reduce_partials(partials, plan.nsplit, din * dout, S, stream);
         if (e != hipSuccess) return PEX_ERR_HIP;
     }
     return PEX_OK;
@@ -204,7 +258,7 @@ static MultiPlan plan_multi(int64_t B, int64_t T, int64_t din, int64_t dout, pex
 {
     MultiPlan m{};
     const int n = __builtin_popcount(want);
-    const StatPlan sq = plan_stat(B, T, din, dout, dt, MODE_SQUARE);
+    const StatPlan sq = plan_stat(B, T, din, dout, dt, MODE_SQUARE, false);
     m.pair = (n >= 2 && sq.kernel == 1);
     if (m.pair) {
         // three wanted: all from one contraction while the sign counts fit bytes; otherwise identity and square
@@ -251,7 +305,7 @@ int pex_version(void) { return 200; }
 
 pex_status pex_set_option(pex_option opt, int32_t value)
 {
-    if (opt != PEX_OPT_MAX_SPLIT && opt != PEX_OPT_TOKEN_PRESQUARE) return PEX_ERR_PHI;
+    if (!known_option(opt)) return PEX_ERR_PHI;
     if (value != clamp_option(opt, value)) return PEX_ERR_SHAPE;
     options().v[opt].store(value);
     return PEX_OK;
@@ -259,7 +313,7 @@ pex_status pex_set_option(pex_option opt, int32_t value)
 
 int32_t pex_get_option(pex_option opt)
 {
-    if (opt != PEX_OPT_MAX_SPLIT && opt != PEX_OPT_TOKEN_PRESQUARE) return -1;
+    if (!known_option(opt)) return -1;
     return option(opt);
 }
 

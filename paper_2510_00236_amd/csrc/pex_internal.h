@@ -23,10 +23,13 @@ struct StatPlan {
     int nsplit;        // number of groups the batch (or, for plain contractions, B*T) is split into
     int64_t per_split; // examples (or rows of B*T) per group
     size_t presq_bytes; // per-token square through pre-squared copies of X and G: their size (256-byte multiple), else 0
-    size_t ws_bytes;   // presq_bytes + (nsplit > 1 ? nsplit * din * dout * 4 : 0)
+    int64_t wide_cols; // bf16, one statistic on two register tiles: columns [0, wide_cols) of S run on 256 x 192 blocks with the
+                       // whole batch per workgroup; nsplit / per_split then describe the remaining columns only
+    size_t ws_bytes;   // presq_bytes + (nsplit > 1 ? nsplit * din * (dout - wide_cols) * 4 : 0)
 };
 
-StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt, Mode mode);
+// allow_wide = false keeps the plan on one block shape (the launches that produce several statistics at once need it)
+StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt, Mode mode, bool allow_wide = true);
 
 // Launchers.  `out` is S when plan.nsplit == 1, else the workspace holding [nsplit][din][dout] partials.
 // MODE_WEIGHTED reads one weight per example from `weight`; MODE_NORMS writes no S but one partial of ||M_b||^2 per
@@ -34,21 +37,22 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
 hipError_t launch_stat_generic(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout,
                                pex_dtype dt, Mode mode, const StatPlan& plan, float* out, hipStream_t stream,
                                const float* weight = nullptr, float* norm_partial = nullptr, float alpha = 0.f);
+// bf16 launchers take S and the partial-sum buffer both: which one a block writes depends on the plan
 hipError_t launch_power_bf16(const void* X, const void* G, float alpha, int64_t B, int64_t T, int64_t din, int64_t dout,
-                             const StatPlan& plan, float* out, hipStream_t stream);
+                             const StatPlan& plan, float* S, float* partials, hipStream_t stream);
 int64_t generic_norm_partials(int64_t din, int64_t dout);
 int64_t bf16_norm_partials(int64_t din, int64_t dout);
 hipError_t launch_norms_bf16(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout, const StatPlan& plan,
                              float* norm_partial, hipStream_t stream);
 hipError_t launch_weighted_bf16(const void* X, const void* G, const float* w, int64_t B, int64_t T, int64_t din, int64_t dout,
-                                const StatPlan& plan, float* out, hipStream_t stream);
+                                const StatPlan& plan, float* S, float* partials, hipStream_t stream);
 // N[b] = sum_{p < nparts} partial[p][b], p ascending
 hipError_t launch_reduce_norms(const float* partial, int64_t nparts, int64_t B, float* N, hipStream_t stream);
 // N_tok[r] = |x_r|^2 |g_r|^2 for every row r of the flattened [B*T] axis
 hipError_t launch_token_norms(const void* X, const void* G, int64_t rows, int64_t din, int64_t dout, pex_dtype dt, float* N_tok,
                               hipStream_t stream);
 hipError_t launch_stat_bf16(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout,
-                            Mode mode, const StatPlan& plan, float* out, hipStream_t stream);
+                            Mode mode, const StatPlan& plan, float* S, float* partials, hipStream_t stream);
 // Two per-example statistics from one contraction; exactly one of the three outputs is NULL.  Uses the block
 // shape of phi = square, so plan_stat(..., MODE_SQUARE) is its plan.
 hipError_t launch_stat_bf16_pair(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout,
@@ -65,6 +69,7 @@ hipError_t launch_stat_f32(const void* X, const void* G, int64_t B, int64_t T, i
 // out[i] = bf16(in[i]^2) (square in fp32, round to nearest even) for n bf16 values, n a multiple of 8
 hipError_t launch_square_bf16(const void* in, void* out, int64_t n, hipStream_t stream);
 void bf16_tile_shape(Mode mode, int64_t B, int* bm, int* bn);
+void bf16_wide_tile_shape(int* bm, int* bn);
 
 // Vector parameters (offsets, elementwise scales): the length axis of each example is cut into nrange ranges of
 // rows_per_range tokens; the workspace holds [B][nrange][d] fp32 partial sums.
@@ -80,6 +85,9 @@ hipError_t launch_vec_stat(const void* A, const void* C, int64_t B, int64_t T, i
 
 // S[e] = sum_{s < nsplit} partial[s][e], s ascending (fixed order => deterministic).
 hipError_t launch_reduce_partials(const float* partial, int nsplit, int64_t n, float* S, hipStream_t stream);
+// the same for a range of columns: S[i * lds + j] = sum_s partial[s][i][j], i < rows, j < cols (cols a multiple of 4)
+hipError_t launch_reduce_partials_cols(const float* partial, int nsplit, int64_t rows, int64_t cols, float* S, int64_t lds,
+                                       hipStream_t stream);
 
 hipError_t launch_adam_update(float* theta, float* m, float* v, const float* S_id, const float* S_sq, int64_t n,
                               pex_adam_variant variant, const pex_adam_params& p, hipStream_t stream,

@@ -218,29 +218,54 @@ struct Bf16Tile {
     static constexpr int XROW = BM * 2, GROW = BN * 2;                 // bytes per slab row
     static constexpr int X_BYTES = BK * XROW, G_BYTES = BK * GROW, STAGE = X_BYTES + G_BYTES;
     static constexpr int LDS_BYTES = NS * STAGE;
-    static constexpr int NXI = X_BYTES / 1024 / NWAVES, NGI = G_BYTES / 1024 / NWAVES;   // loads per wave per slab
-    static constexpr int LPS = NXI + NGI;
-    static constexpr int RX = 1024 / XROW, RG = 1024 / GROW;           // slab rows covered by one load
+    // Loads per wave per slab.  The G part of a slab need not divide evenly over eight waves (a 192-column tile has
+    // 12 KiB per slab): the waves of group 1 take NGI1 loads each, those of group 0 the rest (NGI0 >= NGI1 each).
+    static constexpr int NXI = X_BYTES / 1024 / NWAVES, G_LOADS = G_BYTES / 1024;
+    static constexpr int NGI1 = G_LOADS / NWAVES, NGI0 = (G_LOADS - 4 * NGI1) / 4;
+    static constexpr int LPS0 = NXI + NGI0, LPS1 = NXI + NGI1;         // per wave of group 0 / group 1
+    static constexpr int RX = 1024 / XROW;                             // slab rows covered by one load of X
+    static constexpr int XCH = XROW / 16, GCH = GROW / 16;             // 16-byte chunks per slab row
     static_assert(NWAVES == 8, "eight waves per workgroup: two groups of four");
-    static_assert(X_BYTES % (1024 * NWAVES) == 0 && G_BYTES % (1024 * NWAVES) == 0, "slab must divide over the waves");
+    static_assert(X_BYTES % (1024 * NWAVES) == 0 && G_BYTES % 4096 == 0 && 4 * (NGI0 + NGI1) == G_LOADS, "slab must divide over the waves");
     static_assert(BK % 32 == 0 && XROW <= 1024 && GROW <= 1024, "tile limits");
+    static_assert((XROW & (XROW - 1)) == 0 && ((GROW & (GROW - 1)) == 0 || GROW % 256 == 128), "row pitches the swizzles cover");
     static_assert(NS >= 3, "the ring holds the slab being read, the one landing and at least one more");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS ring too large");
     static_assert(RC <= KS * FM * FN && RC < FM, "the multiply phase has a slot for every late read, and they are X fragments");
 };
 
+// Where the 16-byte chunk c of slab row r sits inside the row in LDS (chunk position), and the inverse.  The
+// transposing read of a 16-lane group touches 4 consecutive rows x 32 bytes, which must fall into different 64-byte
+// bank groups.  Rows whose pitch is a multiple of 256 bytes all start at bank 0: position = c ^ 4*(r mod 4).  A pitch
+// of 128 mod 256 bytes (192-column tiles: 384 bytes) already alternates between the two halves of the banks from row
+// to row, so rows 2 and 3 of every four are rotated by 64 bytes: position = (c + 4*((r/2) mod 2)) mod chunks-per-row.
+template <int ROW_BYTES>
+__device__ __forceinline__ int chunk_position(int c, int r)
+{
+    if constexpr ((ROW_BYTES & (ROW_BYTES - 1)) == 0) return c ^ (4 * (r & 3));
+    else return (c + 4 * ((r >> 1) & 1)) % (ROW_BYTES / 16);
+}
+template <int ROW_BYTES>
+__device__ __forceinline__ int chunk_at_position(int pos, int r)
+{
+    if constexpr ((ROW_BYTES & (ROW_BYTES - 1)) == 0) return pos ^ (4 * (r & 3));
+    else return (pos + ROW_BYTES / 16 - 4 * ((r >> 1) & 1)) % (ROW_BYTES / 16);
+}
+
 template <typename TL, int OUTS>
 __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ G,
-                                                              int64_t rows_total, int seg_len, int din, int dout,
+                                                              int64_t rows_total, int seg_len, int din, int dout, int ldg, int ldo,
                                                               int64_t rows_per_split, int tiles_m, int tiles_n,
                                                               float* __restrict__ out_id, float* __restrict__ out_sq,
                                                               float* __restrict__ out_sg, const float* __restrict__ weight,
                                                               float* __restrict__ norm_partial, int examples_total, float alpha)
 {
     constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK, NS = TL::NS, FM = TL::FM, FN = TL::FN, KS = TL::KS;
-    constexpr int XROW = TL::XROW, GROW = TL::GROW, NXI = TL::NXI, NGI = TL::NGI, RX = TL::RX, RG = TL::RG;
-    constexpr int LPS = TL::LPS, FPK = TL::FPK, RC = TL::RC;
+    constexpr int XROW = TL::XROW, GROW = TL::GROW, NXI = TL::NXI, NGI0 = TL::NGI0, NGI1 = TL::NGI1, RX = TL::RX;
+    constexpr int LPS0 = TL::LPS0, LPS1 = TL::LPS1, FPK = TL::FPK, RC = TL::RC;
     constexpr bool TOKEN = (OUTS == OUT_TOKEN);
+    static_assert(!TOKEN || NGI0 == NGI1, "the in-place squaring assumes every wave loads the same share");
+    constexpr int NGI = NGI0, LPS = LPS0;      // the per-token square only: both groups alike
     constexpr bool PER_EXAMPLE = !(OUTS == OUT_ID || OUTS == OUT_TOKEN);
     constexpr bool HAS_W = (OUTS & OUT_IDW) != 0, HAS_NORM = (OUTS & OUT_NORM) != 0;
     constexpr bool HAS_POW = (OUTS & OUT_POW) != 0;
@@ -272,18 +297,22 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
     // ---- loader geometry.  Load q of a slab (q = wave*NXI + n) fills LDS bytes [q*1024, q*1024+1024) of the X
     // part: slab rows q*RX .. q*RX+RX-1.  Lane L fills 16-byte slot (L mod XROW/16) of row q*RX + L/(XROW/16)
     // with global chunk c = slot ^ 4*(row mod 4).
-    uint32_t xoff[NXI], goff[NGI];
+    // G: load q of a slab fills the 64 chunks from q*64 on of the G part, chunk k = row k / GCH, position k % GCH;
+    // group 0 takes loads 0 .. 4*NGI0-1, group 1 the rest.  `ldg` is the row pitch of G in elements, `dout` the
+    // width of the column range this launch covers (G points at its first column).
+    uint32_t xoff[NXI], goff[NGI0];
 #pragma unroll
     for (int n = 0; n < NXI; ++n) {
-        const int q = wave * NXI + n, r = q * RX + lane / (XROW / 16), slot = lane % (XROW / 16);
-        const int c = slot ^ (4 * (r & 3));
+        const int q = wave * NXI + n, r = q * RX + lane / TL::XCH, slot = lane % TL::XCH;
+        const int c = chunk_at_position<XROW>(slot, r);
         xoff[n] = (i0 + c * 8 < din) ? (uint32_t)(r * din + c * 8) * 2u : 0x80000000u;
     }
+    const int gq0 = group == 0 ? wave * NGI0 : 4 * NGI0 + (wave - 4) * NGI1;     // this wave's first load of G
 #pragma unroll
-    for (int n = 0; n < NGI; ++n) {
-        const int q = wave * NGI + n, r = q * RG + lane / (GROW / 16), slot = lane % (GROW / 16);
-        const int c = slot ^ (4 * (r & 3));
-        goff[n] = (j0 + c * 8 < dout) ? (uint32_t)(r * dout + c * 8) * 2u : 0x80000000u;
+    for (int n = 0; n < NGI0; ++n) {
+        const int k = (gq0 + n) * 64 + lane, r = k / TL::GCH, slot = k % TL::GCH;
+        const int c = chunk_at_position<GROW>(slot, r);
+        goff[n] = (j0 + c * 8 < dout) ? (uint32_t)(r * ldg + c * 8) * 2u : 0x80000000u;
     }
     const int din_avail = din - i0, dout_avail = dout - j0;   // columns of this tile that exist
 
@@ -292,22 +321,23 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
     // valid row, so rows past the end of the example (and everything once the range is exhausted) read as zero.
     int iss_slab = 0, iss_off = 0, iss_buf = 0;
     const uint16_t* xnext = X + row_begin * din + i0;
-    const uint16_t* gnext = G + row_begin * dout + j0;
-    auto issue_slab = [&]() {
+    const uint16_t* gnext = G + row_begin * ldg + j0;
+    auto issue_slab = [&](auto GROUPC) {
+        constexpr int MY_NGI = decltype(GROUPC)::value == 0 ? NGI0 : NGI1;
         int valid = 0;
         if (iss_slab < total) valid = (slen - iss_off) < BK ? (slen - iss_off) : BK;
         const uint32_t bx = lds_base + (uint32_t)(iss_buf * TL::STAGE);
         const uint32_t bg = bx + TL::X_BYTES;
         const uint32_t nrx = valid > 0 ? (uint32_t)(((valid - 1) * din + din_avail) * 2) : 0u;
-        const uint32_t nrg = valid > 0 ? (uint32_t)(((valid - 1) * dout + dout_avail) * 2) : 0u;
+        const uint32_t nrg = valid > 0 ? (uint32_t)(((valid - 1) * ldg + dout_avail) * 2) : 0u;
         const int4_t rx = make_rsrc(xnext, nrx);
         const int4_t rg = make_rsrc(gnext, nrg);
 #pragma unroll
         for (int n = 0; n < NXI; ++n) dma_load_16(bx + (uint32_t)((wave * NXI + n) * 1024), xoff[n], rx);
 #pragma unroll
-        for (int n = 0; n < NGI; ++n) dma_load_16(bg + (uint32_t)((wave * NGI + n) * 1024), goff[n], rg);
+        for (int n = 0; n < MY_NGI; ++n) dma_load_16(bg + (uint32_t)((gq0 + n) * 1024), goff[n], rg);
         xnext += (int64_t)valid * din;
-        gnext += (int64_t)valid * dout;
+        gnext += (int64_t)valid * ldg;
         iss_off += valid;
         if (iss_off >= slen) iss_off = 0;
         ++iss_slab;
@@ -346,7 +376,7 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
 #pragma unroll
     for (int a = 0; a < FM; ++a) a_addr[a] = frow * XROW + ((((wm * TL::WM + a * 16) / 8) ^ sw) * 16) + low;
 #pragma unroll
-    for (int c = 0; c < FN; ++c) b_addr[c] = frow * GROW + ((((wn * TL::WN + c * 16) / 8) ^ sw) * 16) + low;
+    for (int c = 0; c < FN; ++c) b_addr[c] = frow * GROW + chunk_position<GROW>((wn * TL::WN + c * 16) / 8, frow) * 16 + low;
 
     // register tiles: the running contraction, and one per requested per-example statistic
     float4_t acc[FM][FN];
@@ -387,7 +417,7 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
             fa[ks][f - FN] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         }
     };
-    auto read_phase = [&]() {
+    auto read_phase = [&](auto GROUPC) {
         rd_bx = lds + rd_buf * TL::STAGE;
         rd_buf = (rd_buf + 1 == NS) ? 0 : rd_buf + 1;
 #pragma unroll
@@ -395,7 +425,7 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
 #pragma unroll
             for (int f = 0; f < FPK; ++f)
                 if (ks < KS - 1 || f < FPK - RC) read_frag(ks, f);
-        issue_slab();   // after the reads: a wave that stalls on the memory pipeline here has its reads in flight
+        issue_slab(GROUPC);   // after the reads: a wave that stalls on the memory pipeline here has its reads in flight
         if constexpr (TOKEN) {
             // this wave's part of the NEXT slab is squared in place, a phase or more ahead of its first reader
             if (group == 0) wait_vmcnt<(NS - 3) * LPS>();
@@ -451,20 +481,26 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
 
     constexpr int AHEAD0 = NS - 2, AHEAD1 = NS - 1;   // slabs a group has issued before its first phase
     // loads that may still be in flight when this wave's part of slab g+1 must have landed (end of phase 2g+1)
-    constexpr int INFLIGHT0 = (NS - 3) * LPS;          // group 0, after its multiply phase of slab g
-    constexpr int INFLIGHT1 = (NS - 2) * LPS;          // group 1, after its read phase of slab g
+    constexpr int INFLIGHT0 = (NS - 3) * LPS0;         // group 0, after its multiply phase of slab g
+    constexpr int INFLIGHT1 = (NS - 2) * LPS1;         // group 1, after its read phase of slab g
+    constexpr std::integral_constant<int, 0> G0{};
+    constexpr std::integral_constant<int, 1> G1{};
     if (total > 0) {
+        if (group == 0) {
 #pragma unroll
-        for (int s = 0; s < AHEAD1; ++s)
-            if (s < AHEAD0 || group == 1) issue_slab();
-        if (group == 0) wait_vmcnt<(AHEAD0 - 1) * LPS>();
-        else wait_vmcnt<(AHEAD1 - 1) * LPS>();
+            for (int s = 0; s < AHEAD0; ++s) issue_slab(G0);
+            wait_vmcnt<(AHEAD0 - 1) * LPS0>();
+        } else {
+#pragma unroll
+            for (int s = 0; s < AHEAD1; ++s) issue_slab(G1);
+            wait_vmcnt<(AHEAD1 - 1) * LPS1>();
+        }
         if constexpr (TOKEN) square_share(0);
         wait_lds_and_barrier();               // slab 0 is visible to every wave
         int st_in_seg = 0;
         if (group == 0) {
             for (int g = 0; g < total; ++g) {
-                read_phase();
+                read_phase(G0);
                 __builtin_amdgcn_sched_barrier(0);
                 wait_lds_and_barrier();       // ends phase 2g
                 multiply_phase();
@@ -477,7 +513,7 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
         } else {
             plain_barrier();                  // start one phase late
             for (int g = 0; g < total; ++g) {
-                read_phase();
+                read_phase(G1);
                 __builtin_amdgcn_sched_barrier(0);
                 if constexpr (!TOKEN) wait_vmcnt<INFLIGHT1>();   // this wave's part of slab g+1 has landed
                 wait_lds_and_barrier();       // ends phase 2g+1
@@ -491,7 +527,9 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
     wait_vmcnt<0>();   // drain the (empty) loads issued past the end before the LDS is released
 
     // ---- epilogue: lane holds column (lane%16), rows 4*(lane/16) + r of each 16x16 tile
-    const int64_t split_off = (int64_t)split * din * dout;
+    // outputs have their own row pitch: S itself (pointing at the first column of the range, pitch of the whole
+    // layer) or partials [split][din][ldo]
+    const int64_t split_off = (int64_t)split * din * ldo;
     const int jn = lane % 16, ib = 4 * (lane / 16);
 #pragma unroll
     for (int a = 0; a < FM; ++a)
@@ -502,7 +540,7 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
             for (int r = 0; r < 4; ++r) {
                 const int i = i0 + wm * TL::WM + a * 16 + ib + r;
                 if (i < din && j < dout) {
-                    const int64_t e = split_off + (int64_t)i * dout + j;
+                    const int64_t e = split_off + (int64_t)i * ldo + j;
                     if constexpr (!PER_EXAMPLE) out_id[e] = acc[a][c][r];
                     if constexpr (HAS_ID) out_id[e] = acc_id[a][c][r];
                     if constexpr (HAS_SQ) out_sq[e] = acc_sq[a][c][r];
@@ -528,17 +566,35 @@ __global__ __launch_bounds__(256) void square_bf16_kernel(const uint4_t* __restr
 
 // plain contractions and packed sign counts: 256 x 256 block, 128 x 64 per wave, slabs of 32 tokens, ring of 4;
 // the per-token square needs its slab a phase earlier and takes a ring of 5 (all 160 KB of LDS);
-// two fp32 register tiles (phi = square, sign counts beyond 2048 examples): 256 x 128 block, 64 x 64 per wave.
+// two fp32 register tiles (phi = square, sign counts beyond 2048 examples): 256 x 128 block, 64 x 64 per wave, or --
+// for a single statistic -- 256 x 192 (64 x 96 per wave, 96 + 96 accumulators): 22 % fewer bytes from L2 into LDS and
+// 17 % fewer fragment reads per FLOP.
 using TileWide = Bf16Tile<256, 256, 128, 64, 32, 4, 5>;
 using TileToken = Bf16Tile<256, 256, 128, 64, 32, 5, 5>;
 using TilePhi = Bf16Tile<256, 128, 64, 64, 32, 4, 3>;
+using TilePhi192 = Bf16Tile<256, 192, 64, 96, 32, 5, 3>;
+
+// A launch may cover only the columns [col0, col0 + ncols) of the layer, so that launches of different block shapes
+// can sit side by side: G keeps the row pitch of the whole layer; the outputs point at their first element and
+// have the row pitch `ldo` (the layer's when they are S itself, the range's when they are partial sums).
+struct ColumnRange {
+    int64_t col0 = 0, ncols = -1, ldo = -1;      // ncols < 0: the whole layer
+};
 
 template <typename TL, int OUTS>
 hipError_t launch_one(const uint16_t* X, const uint16_t* G, int64_t B, int64_t T, int64_t din, int64_t dout,
                       const StatPlan& plan, float* out_id, float* out_sq, float* out_sg, hipStream_t stream,
-                      const float* weight = nullptr, float* norm_partial = nullptr, float alpha = 0.f)
+                      const float* weight = nullptr, float* norm_partial = nullptr, float alpha = 0.f,
+                      ColumnRange range = ColumnRange{})
 {
     constexpr bool PER_EXAMPLE = !(OUTS == OUT_ID || OUTS == OUT_TOKEN);
+    const int64_t ldg = dout;
+    int64_t ldo = dout;
+    if (range.ncols >= 0) {
+        G += range.col0;
+        dout = range.ncols;
+        ldo = range.ldo;
+    }
     const int tiles_m = (int)((din + TL::BM - 1) / TL::BM), tiles_n = (int)((dout + TL::BN - 1) / TL::BN);
     const int64_t rows_per_split = PER_EXAMPLE ? plan.per_split * T : plan.per_split;
     auto kern = stat_bf16_kernel<TL, OUTS>;
@@ -548,7 +604,7 @@ hipError_t launch_one(const uint16_t* X, const uint16_t* G, int64_t B, int64_t T
     std::call_once(attr_once, [&] { attr_err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES); });
     if (attr_err != hipSuccess) return attr_err;
     const dim3 grid((unsigned)(tiles_m * tiles_n * plan.nsplit)), block(TL::NT);
-    kern<<<grid, block, TL::LDS_BYTES, stream>>>(X, G, B * T, (int)T, (int)din, (int)dout, rows_per_split, tiles_m,
+    kern<<<grid, block, TL::LDS_BYTES, stream>>>(X, G, B * T, (int)T, (int)din, (int)dout, (int)ldg, (int)ldo, rows_per_split, tiles_m,
                                                  tiles_n, out_id, out_sq, out_sg, weight, norm_partial, (int)B, alpha);
     return hipGetLastError();
 }
@@ -860,17 +916,49 @@ hipError_t launch_square_bf16(const void* in, void* out, int64_t n, hipStream_t 
     return hipGetLastError();
 }
 
+namespace {
+
+// One statistic that needs two fp32 register tiles (phi = square, |.|^alpha, weighted sums).  The first
+// plan.wide_cols columns of S run on 256 x 192 blocks with the whole batch in every workgroup, straight into S; the
+// remaining columns on 256 x 128 blocks as plan.nsplit groups of examples (into S, or into partial sums of their own
+// row pitch when there are several groups).
+template <int OUTS>
+hipError_t launch_two_tile(const uint16_t* x, const uint16_t* g, int64_t B, int64_t T, int64_t din, int64_t dout, const StatPlan& plan,
+                           float* S, float* partials, hipStream_t stream, const float* weight, float alpha)
+{
+    constexpr bool TO_ID = (OUTS & OUT_IDW) != 0;       // which output slot of the kernel the statistic leaves through
+    auto go = [&](auto tile, const StatPlan& p, float* out, ColumnRange range) {
+        using TL = decltype(tile);
+        return launch_one<TL, OUTS>(x, g, B, T, din, dout, p, TO_ID ? out : nullptr, TO_ID ? nullptr : out, nullptr, stream, weight, nullptr,
+                                    alpha, range);
+    };
+    float* rest_out = plan.nsplit > 1 ? partials : S + plan.wide_cols;
+    if (plan.wide_cols == 0) return go(TilePhi{}, plan, rest_out, ColumnRange{});
+    StatPlan whole = plan;
+    whole.nsplit = 1;
+    whole.per_split = B;
+    hipError_t e = go(TilePhi192{}, whole, S, ColumnRange{0, plan.wide_cols, dout});
+    const int64_t rest = dout - plan.wide_cols;
+    if (e == hipSuccess && rest > 0) e = go(TilePhi{}, plan, rest_out, ColumnRange{plan.wide_cols, rest, plan.nsplit > 1 ? rest : dout});
+    return e;
+}
+
+}  // namespace
+
+void bf16_wide_tile_shape(int* bm, int* bn) { *bm = TilePhi192::BM; *bn = TilePhi192::BN; }
+
 hipError_t launch_stat_bf16(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout, Mode mode,
-                            const StatPlan& plan, float* out, hipStream_t stream)
+                            const StatPlan& plan, float* S, float* partials, hipStream_t stream)
 {
     const uint16_t* x = (const uint16_t*)X;
     const uint16_t* g = (const uint16_t*)G;
+    float* out = plan.nsplit > 1 ? partials : S;
     switch (mode) {
     case MODE_IDENTITY:
         if (plan.per_split >= QUAD_MIN_ROWS) return launch_quad(x, g, B, T, din, dout, plan, out, stream);
         return launch_one<TileWide, OUT_ID>(x, g, B, T, din, dout, plan, out, nullptr, nullptr, stream);
     case MODE_TOKEN_SQ: return launch_one<TileToken, OUT_TOKEN>(x, g, B, T, din, dout, plan, out, nullptr, nullptr, stream);
-    case MODE_SQUARE: return launch_one<TilePhi, OUT_SQ>(x, g, B, T, din, dout, plan, nullptr, out, nullptr, stream);
+    case MODE_SQUARE: return launch_two_tile<OUT_SQ>(x, g, B, T, din, dout, plan, S, partials, stream, nullptr, 0.f);
     case MODE_SIGN:
         if (sign_is_packed(B)) return launch_one<TileWide, OUT_SIGN_PK>(x, g, B, T, din, dout, plan, nullptr, nullptr, out, stream);
         return launch_one<TilePhi, OUT_SIGN_F32>(x, g, B, T, din, dout, plan, nullptr, nullptr, out, stream);
@@ -894,18 +982,16 @@ hipError_t launch_norms_bf16(const void* X, const void* G, int64_t B, int64_t T,
 
 // S = sum_b w_b M_b (two register tiles: block shape of phi = square)
 hipError_t launch_weighted_bf16(const void* X, const void* G, const float* w, int64_t B, int64_t T, int64_t din, int64_t dout,
-                                const StatPlan& plan, float* out, hipStream_t stream)
+                                const StatPlan& plan, float* S, float* partials, hipStream_t stream)
 {
-    return launch_one<TilePhi, OUT_IDW>((const uint16_t*)X, (const uint16_t*)G, B, T, din, dout, plan, out, nullptr, nullptr, stream, w,
-                                        nullptr);
+    return launch_two_tile<OUT_IDW>((const uint16_t*)X, (const uint16_t*)G, B, T, din, dout, plan, S, partials, stream, w, 0.f);
 }
 
 // S = sum_b |M_b|^alpha
 hipError_t launch_power_bf16(const void* X, const void* G, float alpha, int64_t B, int64_t T, int64_t din, int64_t dout,
-                             const StatPlan& plan, float* out, hipStream_t stream)
+                             const StatPlan& plan, float* S, float* partials, hipStream_t stream)
 {
-    return launch_one<TilePhi, OUT_POW>((const uint16_t*)X, (const uint16_t*)G, B, T, din, dout, plan, nullptr, out, nullptr, stream,
-                                        nullptr, nullptr, alpha);
+    return launch_two_tile<OUT_POW>((const uint16_t*)X, (const uint16_t*)G, B, T, din, dout, plan, S, partials, stream, nullptr, alpha);
 }
 
 // Identity, square and sign from one contraction: possible while a group of examples fits the byte counters.

@@ -172,6 +172,22 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
     }
 }
 
+// the same sum for a range of columns of S: partial rows are `cols` long, S rows `ld`; four columns per lane
+__global__ __launch_bounds__(256) void reduce_partials_cols_kernel(const float4* __restrict__ partial, int nsplit, int64_t rows, int64_t cols4,
+                                                                   float* __restrict__ S, int64_t ld)
+{
+    const int64_t n4 = rows * cols4, stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n4; e += stride) {
+        float4 s = partial[e];
+        for (int k = 1; k < nsplit; ++k) {
+            const float4 p = partial[(int64_t)k * n4 + e];
+            s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+        }
+        const int64_t i = e / cols4, j4 = e - i * cols4;
+        *(float4*)(S + i * ld + j4 * 4) = s;
+    }
+}
+
 }  // namespace
 
 hipError_t launch_stat_generic(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout,
@@ -268,6 +284,16 @@ hipError_t launch_token_norms(const void* X, const void* G, int64_t rows, int64_
         if (wide) token_norms_kernel<uint16_t, true><<<grid, block, 0, stream>>>((const uint16_t*)X, (const uint16_t*)G, rows, din, dout, N_tok);
         else token_norms_kernel<uint16_t, false><<<grid, block, 0, stream>>>((const uint16_t*)X, (const uint16_t*)G, rows, din, dout, N_tok);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_reduce_partials_cols(const float* partial, int nsplit, int64_t rows, int64_t cols, float* S, int64_t ld,
+                                       hipStream_t stream)
+{
+    if (cols % 4 != 0 || ld % 4 != 0) return hipErrorInvalidValue;
+    int64_t blocks = (rows * (cols / 4) + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    reduce_partials_cols_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>((const float4*)partial, nsplit, rows, cols / 4, S, ld);
     return hipGetLastError();
 }
 

@@ -39,9 +39,16 @@ def test_version_and_status_strings():
 
 def test_planner_options_are_clamped_and_change_the_plan():
     assert pex.pex_get_option("max_split") == 32 and pex.pex_get_option("token_presquare") == 1
+    assert pex.pex_get_option("wide_blocks") == 1
     L = pex.lib()
     assert L.pex_set_option(7, 1) == 4 and L.pex_get_option(7) == -1
-    assert L.pex_set_option(0, 0) == 2 and L.pex_set_option(0, 33) == 2 and L.pex_set_option(1, 3) == 2
+    assert L.pex_set_option(0, 0) == 2 and L.pex_set_option(0, 33) == 2 and L.pex_set_option(1, 3) == 2 and L.pex_set_option(2, -1) == 2
+    c4 = (16, 2048, 2048, 8192)
+    try:
+        pex.pex_set_option("wide_blocks", 0)
+        assert pex.pex_stat_workspace_bytes(*c4, pex.PEX_BF16, "square") == 0
+    finally:
+        pex.pex_set_option("wide_blocks", 1)
     shape = (32, 256, 512, 2048)
     full = pex.pex_stat_workspace_bytes(*shape, pex.PEX_BF16, "sign")
     try:
@@ -72,7 +79,7 @@ def test_workspace_query_is_bounded_and_independent_of_B():
     for (B, T, din, dout) in [(32, 256, 512, 2048), (64, 1024, 768, 768), (16, 2048, 2048, 8192), (4, 8192, 4096, 4096)]:
         for phi in ("identity", "square", "sign"):
             ws = pex.pex_stat_workspace_bytes(B, T, din, dout, pex.PEX_BF16, phi)
-            assert ws % (din * dout * 4) == 0
+            assert ws % (din * 8 * 4) == 0            # whole groups of whole rows of a column range
             assert ws <= 32 * din * dout * 4
             assert ws < B * din * dout * 4 or B <= 32
         # per-token square: partial sums plus, on large layers, bf16 copies of the squared operands
@@ -86,7 +93,11 @@ def test_workspace_query_is_bounded_and_independent_of_B():
         ws = pex.pex_vec_stat_workspace_bytes(B, T, d, pex.PEX_BF16)
         assert 0 < ws <= max(2048, B * (T // 32 + 1)) * d * 4 and ws % (B * d * 4) == 0
     assert pex.pex_stat_workspace_bytes(0, 1, 1, 1, pex.PEX_BF16, "square") == 0
-    assert pex.pex_stat_workspace_bytes(16, 2048, 2048, 8192, pex.PEX_BF16, "square") == 0
+    # 1B-scale layer: identity and sign run unsplit; square puts 6144 columns on 256 x 192 blocks (8 x 32 = 256 of them)
+    # and splits the remaining 2048 columns in two groups of examples
+    assert pex.pex_stat_workspace_bytes(16, 2048, 2048, 8192, pex.PEX_BF16, "identity") == 0
+    assert pex.pex_stat_workspace_bytes(16, 2048, 2048, 8192, pex.PEX_BF16, "sign") == 0
+    assert pex.pex_stat_workspace_bytes(16, 2048, 2048, 8192, pex.PEX_BF16, "square") == 2 * 2048 * 2048 * 4
 
 
 def test_host_validation_launches_nothing():

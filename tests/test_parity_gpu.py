@@ -315,3 +315,30 @@ def test_four_wave_kernel_shapes(pex_option, B, T, din, dout, max_split):
     torch.cuda.synchronize()
     st = oracle.stat(si.widen(X), si.widen(G))
     assert_real_stat(S.cpu().numpy().astype(np.float64), st.S_id, "bf16", f"four-wave identity {B}x{T}x{din}x{dout}", elementwise=False)
+
+
+# phi = square, weighted sums and |.|^alpha have two block shapes on bf16 layers; option wide_blocks = 2 puts as many
+# columns as fit on the 256 x 192 one and the rest on the 256 x 128 one, in two launches side by side.
+@pytest.mark.parametrize("B,T,din,dout", [(5, 77, 520, 264), (3, 100, 200, 192), (7, 33, 256, 456), (4, 64, 512, 1024),
+                                          (6, 40, 264, 392), (40, 24, 512, 200), (2, 50, 96, 1160)])
+def test_wide_blocks_side_by_side_with_narrow_ones(pex_option, B, T, din, dout):
+    X, G = si.custom(B, T, din, dout, dtype="bf16", seed=B * 10 + T)
+    Xd, Gd = X.to(DEV), G.to(DEV)
+    wts = torch.linspace(0.5, 1.5, B)
+    pex_option("wide_blocks", 0)
+    narrow = (pex.pex_stat(Xd, Gd, "square").clone(), pex.pex_weighted_sum(Xd, Gd, wts.to(DEV)).clone(), pex.pex_stat_power(Xd, Gd, 1.0).clone())
+    pex_option("wide_blocks", 2)
+    need = pex.pex_stat_workspace_bytes(B, T, din, dout, pex.PEX_BF16, "square")
+    wide_cols = dout // 192 * 192
+    assert need % (din * (dout - wide_cols) * 4 if dout > wide_cols else 1) == 0      # partial sums of the narrow columns only
+    wide = (pex.pex_stat(Xd, Gd, "square"), pex.pex_weighted_sum(Xd, Gd, wts.to(DEV)), pex.pex_stat_power(Xd, Gd, 1.0))
+    torch.cuda.synchronize()
+    st = oracle.stat(si.widen(X), si.widen(G))
+    f = lambda t: t.cpu().numpy().astype(np.float64)
+    assert_real_stat(f(wide[0]), st.S_sq, "bf16", "square on wide blocks", elementwise=(B >= 3))
+    M = np.einsum("bti,btj->bij", si.widen(X).astype(np.float64), si.widen(G).astype(np.float64))
+    assert_real_stat(f(wide[1]), (wts.double().numpy()[:, None, None] * M).sum(0), "bf16", "weighted sum on wide blocks", elementwise=False)
+    assert_real_stat(f(wide[2]), np.abs(M).sum(0), "bf16", "|.|^1 on wide blocks", elementwise=(B >= 3))
+    # either block shape folds the same per-example tiles; only the grouping of the sum over b may differ
+    for a, b in zip(wide, narrow):
+        assert float((a - b).abs().max()) <= 2e-6 * float(b.abs().max())

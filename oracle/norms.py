@@ -61,6 +61,25 @@ def power_stat(X, G, alpha: float) -> np.ndarray:
     return S
 
 
+def clip_weights_over_layers(layer_norms_sq, c) -> np.ndarray:
+    """Per-example clipping (the clip nonlinearity of Sec. 2.1) in a model of several layers: the gradient of example
+    b is the concatenation of its per-layer gradients, so ||g_b||^2 is the sum over the layers of the per-layer
+    squared norms (``layer_norms_sq`` is [layers, B]), and w_b = min(1, c / ||g_b||).  An example whose gradient
+    is exactly zero keeps w_b = 1."""
+    n = np.asarray(layer_norms_sq, dtype=np.float64)
+    if n.ndim != 2:
+        raise ValueError("expected [layers, B] squared norms")
+    total = np.zeros(n.shape[1])
+    for l in range(n.shape[0]):
+        total = total + n[l]
+    w = np.ones(n.shape[1])
+    for b in range(n.shape[1]):
+        norm = np.sqrt(total[b])
+        if norm > c:
+            w[b] = c / norm
+    return w
+
+
 def clip_weights(norms_sq, c) -> np.ndarray:
     """w_b = min(1, c / ||g_b||): the factor of the clipping nonlinearity for squared norms ``norms_sq``."""
     n = np.sqrt(np.asarray(norms_sq, dtype=np.float64))

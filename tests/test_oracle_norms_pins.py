@@ -93,3 +93,32 @@ def test_power_statistic():
     ii, jj = np.meshgrid(np.arange(6), np.arange(4), indexing="ij")
     M2 = np.abs(oracle.per_example_at(X, G, ii.ravel(), jj.ravel()).reshape(5, 6, 4)[2])
     np.testing.assert_allclose(on.power_stat(X, G2, a) - on.power_stat(X, G, a), (4.0 ** a - 1.0) * M2 ** a, rtol=1e-9, atol=1e-12)
+
+
+def test_clip_weights_over_layers_is_per_example_norm_clipping_of_the_whole_model():
+    """Two dense layers: clipping every example's whole gradient (both layers together) to norm c with the library
+    routine, then summing over examples, equals the weighted sums with the weights of clip_weights_over_layers."""
+    import torch
+    B = 6
+    X1, G1 = _rand(B, 7, 6, 4, 11)
+    X2, G2 = _rand(B, 7, 5, 3, 12)
+    X2 = X2 * np.linspace(0.2, 3.0, B, dtype=np.float32)[:, None, None]          # spread the norms around the threshold
+    N = np.stack([on.example_norms(X1, G1), on.example_norms(X2, G2)])
+    c = float(np.sqrt(np.median(N.sum(axis=0))))
+    w = on.clip_weights_over_layers(N, c)
+    assert (w < 1).any() and (w == 1).any()
+    want1, want2 = np.zeros((6, 4)), np.zeros((5, 3))
+    for b in range(B):
+        p1 = torch.nn.Parameter(torch.zeros(6, 4, dtype=torch.float64))
+        p2 = torch.nn.Parameter(torch.zeros(5, 3, dtype=torch.float64))
+        p1.grad = torch.from_numpy(X1[b].astype(np.float64).T @ G1[b].astype(np.float64))
+        p2.grad = torch.from_numpy(X2[b].astype(np.float64).T @ G2[b].astype(np.float64))
+        torch.nn.utils.clip_grad_norm_([p1, p2], c)
+        want1 += p1.grad.numpy()
+        want2 += p2.grad.numpy()
+    # the library routine divides by (norm + 1e-6): agreement to that guard
+    np.testing.assert_allclose(on.weighted_sum(X1, G1, w), want1, rtol=1e-5, atol=1e-9)
+    np.testing.assert_allclose(on.weighted_sum(X2, G2, w), want2, rtol=1e-5, atol=1e-9)
+    # one layer: the single-layer rule; a zero gradient is left alone
+    np.testing.assert_allclose(on.clip_weights_over_layers(N[:1], c), on.clip_weights(N[0], c), rtol=1e-15)
+    assert np.array_equal(on.clip_weights_over_layers(np.zeros((3, 2)), 1.0), np.ones(2))

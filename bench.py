@@ -72,6 +72,8 @@ def main() -> int:
                          "against which the FETCH_SIZE / WRITE_SIZE counters of a profiling run are scaled")
     ap.add_argument("--no-probe", action="store_true",
                     help="skip the MFMA-only ceiling measurement (profiling runs: the trace then holds the step's kernels only)")
+    ap.add_argument("--spin-up-seconds", type=float, default=0.3,
+                    help="untimed work before the warm-up steps that brings the chip from idle to its running clocks")
     ap.add_argument("--no-configs", action="store_true",
                     help="skip the per-launch timing of the other workload shapes (profiling runs)")
     ap.add_argument("--extras", action="store_true",
@@ -174,6 +176,14 @@ def main() -> int:
                 k1.record()
                 tk_events.append((k0, k1, w))
 
+    # The chip has idled while the host drew the inputs (many seconds) and needs some tens of milliseconds of work to
+    # come back to its running clocks: spin it up on the step itself before the W warm-up steps, outside every count.
+    spin_up_steps = 0
+    s0 = time.perf_counter()
+    while time.perf_counter() - s0 < args.spin_up_seconds:
+        step(1, False)
+        torch.cuda.synchronize()
+        spin_up_steps += 1
     for t in range(1, args.warmup + 1):
         step(t, False)
     torch.cuda.synchronize()
@@ -289,8 +299,8 @@ def main() -> int:
         del ids, emb_out, ema_a, ema_q
 
     # ---- the other workload shapes, per launch, after the timed region.  Not part of `value`: the headline stays on
-    # the 1B-scale layer pair.  Every statistic is timed alone with events on the launch stream, 10 warm-up launches
-    # and `reps` timed ones; layers whose inputs fit the 256 MB memory-side cache alternate between two sets of
+    # the 1B-scale layer pair.  Every statistic is timed alone with events on the launch stream, a quarter of a second of
+    # warm-up launches and `reps` timed ones; layers whose inputs fit the 256 MB memory-side cache alternate between two sets of
     # input buffers so that cache residency does not flatter them.
     configs = None
     if not args.no_configs:
@@ -312,8 +322,14 @@ def main() -> int:
             reps = 20 if flop < 5e11 else 10
 
             def per_launch(fn):
-                for k in range(10):            # fresh buffers: the first launches on new memory run slower
+                # The chip idles while the host draws the inputs and takes some tens of milliseconds of work to come
+                # back to its running clocks: warm up for a quarter of a second, not for a fixed number of launches.
+                w0, k = time.perf_counter(), 0
+                while k < 10 or time.perf_counter() - w0 < 0.25:
                     fn(*sets[k % nsets])
+                    k += 1
+                    if k % 10 == 0:
+                        torch.cuda.synchronize()
                 torch.cuda.synchronize()
                 a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 a.record()
@@ -409,7 +425,7 @@ def main() -> int:
 
     out = {
         "metric": METRIC, "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "warmup": args.warmup, "spin_up_steps": spin_up_steps, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
         "config": {"workload": args.workload, "layers": [L["w"].name for L in layers],

@@ -189,6 +189,13 @@ pex_status pex_stat_power(const void *X, const void *G, int64_t B, int64_t T, in
  *   squared norm of the rank-one term x_bt g_bt^T).  N_tok [B*T] fp32 device, overwritten; no workspace; bound by
  *   HBM bandwidth (X and G read once).
  * Same input conventions, limits and error codes as pex_stat.
+ * pex_clip_weights -- the clip nonlinearity of Sec. 2.1, phi(g_b) = min(1, c / ||g_b||) g_b, for a model of several
+ *   layers: the gradient of example b is the concatenation of its per-layer gradients, so
+ *   w[b] = min(1, max_norm / sqrt(sum_l N[l*B + b])), N [nlayers][B] fp32 device holding the pex_example_norms output
+ *   of every layer (let layer l write to N + l*B), summed in ascending l in fp64.  An example whose gradient is
+ *   zero keeps w = 1.  w [B] fp32 device, overwritten; feed it to pex_weighted_sum of every layer for the sum of the
+ *   clipped per-example gradients.  Everything stays on the device and on `stream`: no host round trip, so a clipped
+ *   step can be captured as a whole.  nlayers >= 1, max_norm > 0 (PEX_ERR_SHAPE otherwise).
  */
 size_t pex_example_norms_workspace_bytes(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt);
 pex_status pex_example_norms(const void *X, const void *G, int64_t B, int64_t T, int64_t din, int64_t dout,
@@ -199,6 +206,7 @@ pex_status pex_weighted_sum(const void *X, const void *G, const float *w, int64_
                             pex_stream_t stream);
 pex_status pex_token_norms(const void *X, const void *G, int64_t B, int64_t T, int64_t din, int64_t dout,
                            pex_dtype dt, float *N_tok, pex_stream_t stream);
+pex_status pex_clip_weights(const float *N, int64_t B, int32_t nlayers, float max_norm, float *w, pex_stream_t stream);
 
 /*
  * pex_token_sq -- S_tok = (X o X)^T (G o G) = sum_{b,t} (x_bt o x_bt)(g_bt o g_bt)^T  (Sec. 2.3,

@@ -37,7 +37,7 @@ EXPORTS = ("pex_status_string", "pex_version", "pex_stat_workspace_bytes", "pex_
            "pex_token_sq_workspace_bytes", "pex_token_sq", "pex_adam_update", "pex_signsgd_update",
            "pex_moment_track_workspace_bytes", "pex_moment_track", "pex_embed_stat_workspace_bytes", "pex_embed_stat",
            "pex_mfma_probe_operand_bytes", "pex_mfma_probe_sink_floats", "pex_mfma_probe",
-           "pex_sum_squares_workspace_bytes", "pex_sum_squares", "pex_adam_update_clipped", "pex_stat_noalloc", "pex_set_option", "pex_get_option")
+           "pex_sum_squares_workspace_bytes", "pex_sum_squares", "pex_adam_update_clipped", "pex_stat_noalloc", "pex_set_option", "pex_get_option", "pex_clip_weights")
 
 
 class PexError(RuntimeError):
@@ -78,6 +78,8 @@ def lib() -> ctypes.CDLL:
         L.pex_stat_workspace_bytes.restype = sz
         L.pex_stat.argtypes = [p, p, i64, i64, i64, i64, ctypes.c_int, ctypes.c_int, p, p, sz, p]
         L.pex_stat.restype = ctypes.c_int
+        L.pex_clip_weights.argtypes = [p, i64, i32, f, p, p]
+        L.pex_clip_weights.restype = ctypes.c_int
         L.pex_set_option.argtypes = [ctypes.c_int, i32]
         L.pex_set_option.restype = ctypes.c_int
         L.pex_get_option.argtypes = [ctypes.c_int]
@@ -395,6 +397,19 @@ def pex_weighted_sum(X, G, w, S=None, workspace=None, stream=None):
     _invoke(lib().pex_weighted_sum, _dev(X, "X"), _dev(G, "G"), _f32(w, "w", numel=B), B, T, din, dout, dt, _f32(S, "S", shape=(din, dout)), wptr,
                                   wbytes, _stream(stream))
     return S
+
+
+def pex_clip_weights(N, max_norm, w=None, stream=None):
+    """w[B] = min(1, max_norm / sqrt(sum over layers of N)), ``N`` fp32 [layers, B] (or [B]) of per-layer squared
+    per-example gradient norms on the GPU."""
+    import torch
+    if N.dim() not in (1, 2):
+        raise ValueError("N must be [layers, B] or [B]")
+    nlayers, B = (1, N.shape[0]) if N.dim() == 1 else (int(N.shape[0]), int(N.shape[1]))
+    if w is None:
+        w = torch.empty(B, dtype=torch.float32, device=N.device)
+    _invoke(lib().pex_clip_weights, _f32(N, "N"), B, nlayers, float(max_norm), _f32(w, "w", numel=B), _stream(stream))
+    return w
 
 
 def pex_stat_power(X, G, alpha, S=None, workspace=None, stream=None):

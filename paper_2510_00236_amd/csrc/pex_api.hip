@@ -480,6 +480,14 @@ pex_status pex_weighted_sum(const void* X, const void* G, const float* w, int64_
     return run_stat(X, G, B, T, din, dout, dt, MODE_WEIGHTED, S, workspace, workspace_bytes, (hipStream_t)stream, w);
 }
 
+pex_status pex_clip_weights(const float* N, int64_t B, int32_t nlayers, float max_norm, float* w, pex_stream_t stream)
+{
+    if (!N || !w) return PEX_ERR_NULL;
+    if (B < 1 || nlayers < 1 || B >= ((int64_t)1 << 31) || !(max_norm > 0.f)) return PEX_ERR_SHAPE;
+    if (((uintptr_t)N | (uintptr_t)w) & 3u) return PEX_ERR_ALIGN;
+    return launch_clip_weights(N, B, nlayers, max_norm, w, (hipStream_t)stream) == hipSuccess ? PEX_OK : PEX_ERR_HIP;
+}
+
 size_t pex_stat_power_workspace_bytes(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt)
 {
     if (B < 1 || T < 1 || din < 1 || dout < 1) return 0;

@@ -92,6 +92,8 @@ hipError_t launch_reduce_partials_cols(const float* partial, int nsplit, int64_t
 hipError_t launch_adam_update(float* theta, float* m, float* v, const float* S_id, const float* S_sq, int64_t n,
                               pex_adam_variant variant, const pex_adam_params& p, hipStream_t stream,
                               const double* clip_sumsq = nullptr, float max_norm = 0.f);
+// w[b] = min(1, max_norm / sqrt(sum_l N[l][b])) for N [nlayers][B]
+hipError_t launch_clip_weights(const float* N, int64_t B, int nlayers, float max_norm, float* w, hipStream_t stream);
 size_t sum_squares_workspace(int64_t n);
 hipError_t launch_sum_squares(const float* x, int64_t n, double* acc, int accumulate, double* partial, hipStream_t stream);
 hipError_t launch_sign_update(float* theta, float* m, const float* S, int64_t n, pex_sign_variant variant, float lr, float beta,

@@ -265,6 +265,29 @@ hipError_t launch_adam_update(float* theta, float* m, float* v, const float* S_i
     return hipGetLastError();
 }
 
+namespace {
+
+// w[b] = min(1, max_norm / sqrt(sum over the layers of N[l][b])), the layers added in ascending order; an example
+// whose squared norm is zero (or whose norm does not exceed max_norm) keeps w = 1
+__global__ __launch_bounds__(256) void clip_weights_kernel(const float* __restrict__ N, int64_t B, int nlayers, float max_norm,
+                                                           float* __restrict__ w)
+{
+    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    double total = 0.0;
+    for (int l = 0; l < nlayers; ++l) total += (double)N[(int64_t)l * B + b];
+    const double norm = sqrt(total);
+    w[b] = norm > (double)max_norm ? (float)((double)max_norm / norm) : 1.0f;
+}
+
+}  // namespace
+
+hipError_t launch_clip_weights(const float* N, int64_t B, int nlayers, float max_norm, float* w, hipStream_t stream)
+{
+    clip_weights_kernel<<<dim3((unsigned)((B + 255) / 256)), dim3(256), 0, stream>>>(N, B, nlayers, max_norm, w);
+    return hipGetLastError();
+}
+
 size_t sum_squares_workspace(int64_t n) { return (size_t)update_grid(n) * sizeof(double); }
 
 hipError_t launch_sum_squares(const float* x, int64_t n, double* acc, int accumulate, double* partial, hipStream_t stream)

@@ -140,6 +140,9 @@ def test_host_validation_launches_nothing():
     assert L.pex_vec_stat(X + 2, None, 4, 16, 64, 0, 7, S, S, S, 0x4000, 1 << 20, None) == 5
     assert L.pex_vec_stat(X, None, 4, 16, 64, 0, 7, S, S, S, None, 0, None) == 6
     assert L.pex_vec_stat(X, None, 4, 16, 64, 0, 7, S, S, S, 0x4000, 16, None) == 6
+    assert L.pex_clip_weights(None, 4, 1, 1.0, S, None) == 1
+    assert L.pex_clip_weights(X, 0, 1, 1.0, S, None) == 2 and L.pex_clip_weights(X, 4, 0, 1.0, S, None) == 2
+    assert L.pex_clip_weights(X, 4, 1, 0.0, S, None) == 2 and L.pex_clip_weights(X + 2, 4, 1, 1.0, S, None) == 5
     assert L.pex_token_sq(X, None, *ok, 0, S, None, 0, None) == 1
     assert L.pex_token_sq(X, G, 4, 0, 64, 64, 0, S, None, 0, None) == 2
 

@@ -100,3 +100,31 @@ def test_power_statistic_rejects_bad_exponents():
         with pytest.raises(pex.PexError) as ei:
             pex.pex_stat_power(X.to(DEV), G.to(DEV), alpha)
         assert ei.value.code == 4
+
+
+def test_per_example_clipping_of_a_two_layer_model_stays_on_the_device():
+    """Norms of both layers -> clipping weights -> clipped gradient sums, through the library only; against the oracle's
+    clip_weights_over_layers (pinned to per-example clip_grad_norm_) and weighted sums."""
+    B, T = 12, 64
+    X1, G1 = si.custom(B, T, 264, 136, dtype="bf16", seed=31)
+    X2, G2 = si.custom(B, T, 136, 520, dtype="bf16", seed=32)
+    X2 = (X2.float() * torch.linspace(0.2, 3.0, B)[:, None, None]).to(torch.bfloat16)     # norms on both sides of the threshold
+    d = [t.to(DEV) for t in (X1, G1, X2, G2)]
+    N = torch.empty(2, B, device=DEV)
+    pex.pex_example_norms(d[0], d[1], N=N[0])
+    pex.pex_example_norms(d[2], d[3], N=N[1])
+    ref_N = np.stack([on.example_norms(si.widen(X1), si.widen(G1)), on.example_norms(si.widen(X2), si.widen(G2))])
+    c = float(np.sqrt(np.median(ref_N.sum(axis=0))))
+    w = pex.pex_clip_weights(N, c)
+    S1, S2 = pex.pex_weighted_sum(d[0], d[1], w), pex.pex_weighted_sum(d[2], d[3], w)
+    torch.cuda.synchronize()
+    ref_w = on.clip_weights_over_layers(ref_N, c)
+    assert (ref_w < 1).any() and (ref_w == 1).any()
+    np.testing.assert_allclose(w.cpu().double().numpy(), ref_w, rtol=2e-5)
+    for S, (X, G) in ((S1, (X1, G1)), (S2, (X2, G2))):
+        ref = on.weighted_sum(si.widen(X), si.widen(G), ref_w)
+        assert np.abs(S.cpu().double().numpy() - ref).max() <= 2e-5 * np.abs(ref).max()
+    # a single layer given as [B]; zero gradients keep weight one
+    w1 = pex.pex_clip_weights(N[0].contiguous(), c)
+    np.testing.assert_allclose(w1.cpu().double().numpy(), on.clip_weights(ref_N[0], c), rtol=2e-5)
+    assert torch.equal(pex.pex_clip_weights(torch.zeros(3, 5, device=DEV), 1.0), torch.ones(5, device=DEV))

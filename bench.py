@@ -10,10 +10,14 @@ Inputs are resident in HBM before the timed region.  `value` is the contraction 
 (2*B*T*din*dout FLOP per statistic) divided by the wall time of the step, in TFLOP/s.
 
 Prints ONE JSON line.  `roofline` is measured live with HIP events around launches of the dominant kernel on
-the stream it runs on.  The kernel that takes the largest share of the step (42 % in the kernel trace under
+the stream it runs on.  The kernel that takes the largest share of the step (41 % in the kernel trace under
 profiles/) is the plain 256 x 256-tile contraction: pex_stat(identity) launches it once per layer and
 pex_token_sq launches it once more on the pre-squared operands; the events bracket the pex_stat(identity)
-launches.  `square_roofline` reports the phi = square contraction (27 % of the step) the same way.
+launches.  `square_roofline` reports phi = square (27 % of the step: its two contraction launches and the small
+reduction between them) the same way, `sign_roofline` phi = sign (22 %).  `traffic` is not measured by this run: it
+is the bytes beyond L2 per launch from the committed counter summary under profiles/ (FETCH_SIZE and WRITE_SIZE
+runs of this very command, scaled by a copy of known size).  `configs` times every other workload shape per launch,
+after the timed region.
 `cpu_baseline` times the fp64 oracle on a bounded sample of the same workload on the host cores.
 """
 from __future__ import annotations
@@ -72,6 +76,10 @@ def main() -> int:
                          "against which the FETCH_SIZE / WRITE_SIZE counters of a profiling run are scaled")
     ap.add_argument("--no-probe", action="store_true",
                     help="skip the MFMA-only ceiling measurement (profiling runs: the trace then holds the step's kernels only)")
+    ap.add_argument("--probe-only", choices=["gaussian", "zero"], default=None,
+                    help="profiling aid: run nothing but the MFMA-only probe (operands drawn from N(0,1), or all zero) and "
+                         "print its own small JSON line; with rocprofv3 --pmc SQ_BUSY_CU_CYCLES the cycles per compute unit "
+                         "divided by the kernel's duration give the clock the chip sustains on those operands")
     ap.add_argument("--spin-up-seconds", type=float, default=0.3,
                     help="untimed work before the warm-up steps that brings the chip from idle to its running clocks")
     ap.add_argument("--no-configs", action="store_true",
@@ -97,6 +105,28 @@ def main() -> int:
     pex.lib()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.probe_only is not None:
+        n_cu = torch.cuda.get_device_properties(dev).multi_processor_count
+        nel = pex.lib().pex_mfma_probe_operand_bytes() // 2
+        ops = (torch.randn(nel, device=dev) if args.probe_only == "gaussian" else torch.zeros(nel, device=dev)).to(torch.bfloat16)
+        iters = 1500
+        _, sink = pex.pex_mfma_probe(ops, n_cu, iters)
+        w0 = time.perf_counter()
+        while time.perf_counter() - w0 < args.spin_up_seconds:
+            pex.pex_mfma_probe(ops, n_cu, iters, sink=sink)
+            torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(args.steps):
+            flop, _ = pex.pex_mfma_probe(ops, n_cu, iters, sink=sink)
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / args.steps
+        print(json.dumps({"probe": "mfma_probe_kernel", "operands": args.probe_only, "launches": args.steps, "launch_ms": round(ms, 4),
+                          "TFLOP/s": round(flop / (ms * 1e-3) / 1e12, 1), "frac_of_bf16_peak": round(flop / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                          "compute_units": n_cu}))
+        return 0
 
     layers = []
     for name in LAYER_SETS[args.workload]:
@@ -379,7 +409,9 @@ def main() -> int:
 
     roofline = contraction_roofline(id_events, "stat_bf16_quad_kernel (256x256 tile, four waves of 128x128; pex_stat phi=identity; also "
                                                "the contraction inside pex_token_sq)", "identity")
-    square_roofline = contraction_roofline(sq_events, "stat_bf16_kernel<256x128 tile, square> (pex_stat phi=square)", "square")
+    square_roofline = contraction_roofline(sq_events, "pex_stat phi=square as a whole: stat_bf16_kernel<256x192 tile, square> on the columns that fill one "
+                                                      "round of 256 workgroups, stat_bf16_kernel<256x128 tile, square> on the rest in two groups of "
+                                                      "examples, reduce_partials_cols_kernel", "square")
     sign_roofline = contraction_roofline(sc_events, "stat_bf16_kernel<256x256 tile, sign with packed counts> (pex_stat phi=sign)", "sign")
     token_roofline = contraction_roofline(tk_events, "pex_token_sq as a whole: square_bf16_kernel on X and on G, then stat_bf16_quad_kernel "
                                                      "on the copies; FLOP of the contraction only", "token")

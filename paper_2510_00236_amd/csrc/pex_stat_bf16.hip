@@ -207,13 +207,31 @@ __device__ __forceinline__ void map_workgroup(int tiles_m, int tiles_n, int& spl
 }
 
 // Tile geometry.  RC_ = fragments of a slab's last k-step that are read in the multiply phase (the rest of the
-// slab's fragments are read in the read phase).
-template <int BM_, int BN_, int WM_, int WN_, int BK_, int NS_, int RC_>
+// slab's fragments are read in the read phase).  LEAD_ = 0: the multiply phase walks the wave's sub-tile row by row
+// (X fragment outer, G fragments inner), the late fragments are the last X fragments and late read i follows MFMA i.
+// LEAD_ > 0: column by column (G fragment outer), the late fragments are the last G fragments, each read LEAD_
+// MFMAs before the first MFMA that uses it -- for sub-tiles with more fragment columns than rows, where more
+// fragments can be late.
+template <int BM_, int BN_, int WM_, int WN_, int BK_, int NS_, int RC_, int LEAD_ = 0>
 struct Bf16Tile {
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, BK = BK_, NS = NS_;
     static constexpr int FM = WM / 16, FN = WN / 16, KS = BK / 32;
     static constexpr int FPK = FM + FN;                                // fragments per k-step
     static constexpr int RC = RC_ < FPK ? RC_ : FPK;
+    static constexpr int LEAD = LEAD_;
+    static constexpr bool N_OUTER = LEAD_ > 0;
+    // which late fragment (0 .. RC-1) is read after MFMA i of a slab, -1: none
+    static constexpr int late_read_after(int i)
+    {
+        if (!N_OUTER) return i < RC ? i : -1;
+        for (int k = 0; k < RC; ++k) {
+            const int use = (KS - 1) * FM * FN + (FN - RC + k) * FM;      // first MFMA that needs late fragment k
+            int at = use - LEAD;
+            if (at < k) at = k;
+            if (at == i) return k;
+        }
+        return -1;
+    }
     static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN, NWAVES = WAVES_M * WAVES_N, NT = NWAVES * 64;
     static constexpr int XROW = BM * 2, GROW = BN * 2;                 // bytes per slab row
     static constexpr int X_BYTES = BK * XROW, G_BYTES = BK * GROW, STAGE = X_BYTES + G_BYTES;
@@ -231,7 +249,8 @@ struct Bf16Tile {
     static_assert((XROW & (XROW - 1)) == 0 && ((GROW & (GROW - 1)) == 0 || GROW % 256 == 128), "row pitches the swizzles cover");
     static_assert(NS >= 3, "the ring holds the slab being read, the one landing and at least one more");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS ring too large");
-    static_assert(RC <= KS * FM * FN && RC < FM, "the multiply phase has a slot for every late read, and they are X fragments");
+    static_assert(RC <= KS * FM * FN && RC < (N_OUTER ? FN : FM), "the multiply phase has a slot for every late read");
+    static_assert(!N_OUTER || FM >= 2, "late reads are issued in order, each before its first use");
 };
 
 // Where the 16-byte chunk c of slab row r sits inside the row in LDS (chunk position), and the inverse.  The
@@ -405,16 +424,19 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
     const unsigned char* rd_bx = lds;                  // buffer of the slab being read
     int rd_buf = 0;
     auto read_frag = [&](int ks, int f) {
-        if (f < FN) {
-            const unsigned char* p = rd_bx + TL::X_BYTES + b_addr[f] + ks * 32 * GROW;
+        // the operand read last is the one of the outer loop of the multiply phase
+        const bool is_g = TL::N_OUTER ? f >= FM : f < FN;
+        const int k = TL::N_OUTER ? (is_g ? f - FM : f) : (is_g ? f : f - FN);
+        if (is_g) {
+            const unsigned char* p = rd_bx + TL::X_BYTES + b_addr[k] + ks * 32 * GROW;
             const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p));
             const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p + 4 * GROW));
-            fb[ks][f] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            fb[ks][k] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         } else {
-            const unsigned char* p = rd_bx + a_addr[f - FN] + ks * 32 * XROW;
+            const unsigned char* p = rd_bx + a_addr[k] + ks * 32 * XROW;
             const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p));
             const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(p + 4 * XROW));
-            fa[ks][f - FN] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            fa[ks][k] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         }
     };
     auto read_phase = [&](auto GROUPC) {
@@ -442,15 +464,17 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-            for (int a = 0; a < FM; ++a)
+            for (int o = 0; o < (TL::N_OUTER ? FN : FM); ++o)
 #pragma unroll
-                for (int cc = 0; cc < FN; ++cc) {
-                    const int c = (a & 1) ? FN - 1 - cc : cc;
-                    const int i = (ks * FM + a) * FN + cc;
+                for (int ii = 0; ii < (TL::N_OUTER ? FM : FN); ++ii) {
+                    const int in = (o & 1) ? (TL::N_OUTER ? FM : FN) - 1 - ii : ii;       // the inner index runs back and forth
+                    const int a = TL::N_OUTER ? in : o, c = TL::N_OUTER ? o : in;
+                    const int i = (ks * (TL::N_OUTER ? FN : FM) + o) * (TL::N_OUTER ? FM : FN) + ii;
                     acc[a][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[ks][a], fb[ks][c], acc[a][c], 0, 0, 0);
                     __builtin_amdgcn_sched_barrier(0);
-                    if (i < RC) {
-                        read_frag(KS - 1, FPK - RC + i);
+                    const int late = TL::late_read_after(i);
+                    if (late >= 0) {
+                        read_frag(KS - 1, FPK - RC + late);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
@@ -572,7 +596,10 @@ __global__ __launch_bounds__(256) void square_bf16_kernel(const uint4_t* __restr
 using TileWide = Bf16Tile<256, 256, 128, 64, 32, 4, 5>;
 using TileToken = Bf16Tile<256, 256, 128, 64, 32, 5, 5>;
 using TilePhi = Bf16Tile<256, 128, 64, 64, 32, 4, 3>;
-using TilePhi192 = Bf16Tile<256, 192, 64, 96, 32, 5, 3>;
+// (ring of 5 slabs = 140 KB; five of its ten fragments -- G fragments, its sub-tile being walked column by column -- are
+// read in the multiply phase, each 7 MFMAs ahead of its first use: measured best of rings of 4 and 5, 1 to 5 late
+// fragments and leads of 5 to 10, a spread of 3 %)
+using TilePhi192 = Bf16Tile<256, 192, 64, 96, 32, 5, 5, 7>;
 
 // A launch may cover only the columns [col0, col0 + ncols) of the layer, so that launches of different block shapes
 // can sit side by side: G keeps the row pitch of the whole layer; the outputs point at their first element and

@@ -113,7 +113,7 @@ pex_status pex_stat(const void *X, const void *G, int64_t B, int64_t T, int64_t 
  * PEX_NOALLOC_SCRATCH_BYTES that is part of the library's device image (one copy per GPU, held until the process
  * ends) instead of a caller's workspace.  The call allocates and frees nothing.
  *   - A call whose pex_stat_workspace_bytes(...) exceeds PEX_NOALLOC_SCRATCH_BYTES returns PEX_ERR_TOO_LARGE and
- *     launches nothing (small layers with many groups: e.g. 512 x 2048 in 16 groups needs 64 MiB).
+ *     launches nothing (small layers with many groups: e.g. 768 x 768 in 28 groups needs 63 MiB).
  *   - All calls on one GPU share that GPU's buffer: calls that overlap in time on one GPU (different streams,
  *     different host threads) race on it; calls on one stream, or otherwise ordered, are safe.  Nothing in the
  *     buffer needs to start at zero and nothing is kept in it between calls.

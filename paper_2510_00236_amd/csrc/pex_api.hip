@@ -70,7 +70,8 @@ static int option(int opt) { return options().v[opt].load(); }
 
 // The bf16 kernels run one workgroup per compute unit, so a launch of `tiles` blocks with the batch in `ns` groups takes
 //   rounds(ns) * ceil(units / ns)  unit-times,  rounds = ceil(tiles * ns / 256),
-// and the fixed-order reduction of the partial sums reads ns copies of the output (s_bytes each) at ~4 TB/s.
+// its workgroups write ns copies of the output (s_bytes each) and the fixed-order reduction reads them back and writes
+// the sum, all at ~4 TB/s.
 // Returns the cheapest cost over ns <= max_split and the split that reaches it.
 static double cheapest_split(int64_t tiles, int64_t units, double t_unit, double s_bytes, int max_split, int64_t* nsplit, int64_t* per)
 {
@@ -81,7 +82,7 @@ static double cheapest_split(int64_t tiles, int64_t units, double t_unit, double
         const int64_t ns_eff = (units + pu - 1) / pu;
         const int64_t rounds = (tiles * ns_eff + 255) / 256;
         double cost = (double)rounds * (double)pu * t_unit;
-        if (ns_eff > 1) cost += (ns_eff + 1) * s_bytes / 4.0e12 + 3.0e-6;
+        if (ns_eff > 1) cost += (2 * ns_eff + 1) * s_bytes / 4.0e12 + 3.0e-6;
         if (ns == 1 || cost < best) { best = cost; *nsplit = ns_eff; *per = pu; }
     }
     return best;
@@ -120,7 +121,7 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
     units = per_example ? B : (B * T + slab - 1) / slab;
     const int max_split = option(PEX_OPT_MAX_SPLIT);
     int64_t nsplit = 1, per = units;
-    int64_t wide_cols = 0;
+    int64_t wide_cols = 0, wide_nsplit = 1, wide_per = units;
     if (p.kernel != 1) {
         nsplit = (target + tiles - 1) / tiles;
         if (nsplit > max_split) nsplit = max_split;
@@ -132,39 +133,39 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
         const double rows_per_unit = per_example ? (double)T : (double)slab;
         const double t_unit = 2.0 * rows_per_unit * bm * bn / bf16_block_rate(bm, bn);
         double best = cheapest_split(tiles, units, t_unit, (double)din * (double)dout * 4.0, max_split, &nsplit, &per);
-        // One statistic on two register tiles may put its first columns on the wider block (256 x 192), whole batch
-        // per workgroup and straight into S, and only the remaining columns on the 256 x 128 block with a split of
-        // their own.  Worth it when the wide part fills whole rounds of 256 workgroups: tried for the largest
-        // number of wide block columns that fits k rounds, k = 1, 2, ..., and for all columns wide.
+        // One statistic on two register tiles may put its first columns on the wider block (256 x 192) and only the
+        // remaining columns on the 256 x 128 block, each part with a split of the batch of its own.  Candidates: every
+        // number of wide block columns up to 64, beyond that the largest number that fits k rounds of 256 workgroups,
+        // and all columns wide.
         const int wide_opt = option(PEX_OPT_WIDE_BLOCKS);
         if (allow_wide && wide_opt != 0 && (mode == MODE_SQUARE || mode == MODE_WEIGHTED || mode == MODE_POWER) && bm == 256 && bn == 128) {
             int wm, wn;
             bf16_wide_tile_shape(&wm, &wn);
             const int64_t tiles_m = (din + wm - 1) / wm, max_wide = dout / wn;
             const double t_wide = 2.0 * (double)T * wm * wn / bf16_block_rate(wm, wn);
-            int64_t tried = -1;
-            for (int64_t k = 1; k <= 65; ++k) {
-                int64_t na = k <= 64 ? (256 * k) / tiles_m : max_wide;
-                if (na > max_wide) na = max_wide;
-                if (na < 1 || na == tried) { if (na >= max_wide) break; continue; }
-                tried = na;
+            auto consider = [&](int64_t na, bool forced) {
                 const int64_t rest = dout - na * wn;
-                double cost = (double)((tiles_m * na + 255) / 256) * (double)B * t_wide;
-                int64_t ns_r = 1, per_r = units;
+                int64_t ns_w = 1, per_w = units, ns_r = 1, per_r = units;
+                double cost = cheapest_split(tiles_m * na, units, t_wide, (double)din * (double)(na * wn) * 4.0, max_split, &ns_w, &per_w);
                 if (rest > 0)
                     cost += 5.0e-6 + cheapest_split(tiles_m * ((rest + bn - 1) / bn), units, t_unit, (double)din * (double)rest * 4.0, max_split,
                                                     &ns_r, &per_r);
-                if (cost < best) { best = cost; wide_cols = na * wn; nsplit = ns_r; per = per_r; }
-                if (na >= max_wide) break;
+                if (forced || cost < best) {
+                    best = cost;
+                    wide_cols = na * wn;
+                    wide_nsplit = (units + per_w - 1) / per_w;
+                    wide_per = per_w;
+                    nsplit = ns_r;
+                    per = per_r;
+                }
+            };
+            for (int64_t na = 1; na <= max_wide && na <= 64; ++na) consider(na, false);
+            for (int64_t k = 1; k <= 64 && max_wide > 64; ++k) {
+                const int64_t na = (256 * k) / tiles_m;
+                if (na > 64 && na < max_wide) consider(na, false);
             }
-            if (wide_opt == 2 && max_wide >= 1) {      // forced: as many wide block columns as fit, whatever the cost
-                wide_cols = max_wide * wn;
-                const int64_t rest = dout - wide_cols;
-                nsplit = 1;
-                per = units;
-                if (rest > 0)
-                    cheapest_split(tiles_m * ((rest + bn - 1) / bn), units, t_unit, (double)din * (double)rest * 4.0, max_split, &nsplit, &per);
-            }
+            if (max_wide > 64) consider(max_wide, false);
+            if (wide_opt == 2 && max_wide >= 1) consider(max_wide, true);      // forced: as many wide block columns as fit
         }
     }
     nsplit = (units + per - 1) / per;      // no empty group
@@ -183,7 +184,11 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
             p.presq_bytes = (((size_t)B * (size_t)T * (size_t)(din + dout) * 2) + 255) & ~(size_t)255;
     }
     p.wide_cols = wide_cols;
-    p.ws_bytes = p.presq_bytes + (nsplit > 1 ? (size_t)nsplit * (size_t)din * (size_t)(dout - wide_cols) * sizeof(float) : 0);
+    p.wide_nsplit = (int)wide_nsplit;
+    p.wide_per_split = wide_per;
+    p.wide_ws_bytes = (wide_cols > 0 && wide_nsplit > 1) ? (size_t)wide_nsplit * (size_t)din * (size_t)wide_cols * sizeof(float) : 0;
+    p.ws_bytes = p.presq_bytes + p.wide_ws_bytes +
+                 ((nsplit > 1 && dout > wide_cols) ? (size_t)nsplit * (size_t)din * (size_t)(dout - wide_cols) * sizeof(float) : 0);
     if (mode == MODE_NORMS)   // no S at all: one partial of ||M_b||^2 per tile (and wave) and example
         p.ws_bytes = (size_t)(p.kernel == 1 ? bf16_norm_partials(din, dout) : generic_norm_partials(din, dout)) * (size_t)B * sizeof(float);
     return p;
@@ -235,10 +240,19 @@ static pex_status run_stat(const void* X, const void* G, int64_t B, int64_t T, i
     } else if (plan.kernel == 1) e = launch_stat_bf16(X, G, B, T, din, dout, mode, plan, S, partials, stream);
     else e = launch_stat_generic(X, G, B, T, din, dout, dt, mode, plan, out, stream);
     if (e != hipSuccess) return PEX_ERR_HIP;
-    if (plan.nsplit > 1) {
-        // partial sums of the whole layer, or of the columns beyond the wide blocks only
-        e = plan.wide_cols > 0 ? launch_reduce_partials_cols(partials, plan.nsplit, din, dout - plan.wide_cols, S + plan.wide_cols, dout, stream)
-                               : launch_reduce_partials(partials, plan.nsplit, din * dout, S, stream);
+    if (plan.wide_cols > 0) {
+        // the wide part's partial sums come first in the workspace, then those of the columns beyond it
+        if (plan.wide_nsplit > 1) {
+            e = launch_reduce_partials_cols(partials, plan.wide_nsplit, din, plan.wide_cols, S, dout, stream);
+            if (e != hipSuccess) return PEX_ERR_HIP;
+        }
+        if (plan.nsplit > 1 && dout > plan.wide_cols) {
+            const float* rest_partials = (const float*)((const char*)partials + plan.wide_ws_bytes);
+            e = launch_reduce_partials_cols(rest_partials, plan.nsplit, din, dout - plan.wide_cols, S + plan.wide_cols, dout, stream);
+            if (e != hipSuccess) return PEX_ERR_HIP;
+        }
+    } else if (plan.nsplit > 1) {
+        e = launch_reduce_partials(partials, plan.nsplit, din * dout, S, stream);
         if (e != hipSuccess) return PEX_ERR_HIP;
     }
     return PEX_OK;

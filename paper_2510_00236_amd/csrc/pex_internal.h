@@ -23,9 +23,12 @@ struct StatPlan {
     int nsplit;        // number of groups the batch (or, for plain contractions, B*T) is split into
     int64_t per_split; // examples (or rows of B*T) per group
     size_t presq_bytes; // per-token square through pre-squared copies of X and G: their size (256-byte multiple), else 0
-    int64_t wide_cols; // bf16, one statistic on two register tiles: columns [0, wide_cols) of S run on 256 x 192 blocks with the
-                       // whole batch per workgroup; nsplit / per_split then describe the remaining columns only
-    size_t ws_bytes;   // presq_bytes + (nsplit > 1 ? nsplit * din * (dout - wide_cols) * 4 : 0)
+    int64_t wide_cols; // bf16, one statistic on two register tiles: columns [0, wide_cols) of S run on 256 x 192 blocks as
+                       // wide_nsplit groups of wide_per_split examples; nsplit / per_split then describe the remaining columns only
+    int wide_nsplit;
+    int64_t wide_per_split;
+    size_t wide_ws_bytes; // partial sums of the wide part (first in the workspace after the squared copies), 0 if unsplit
+    size_t ws_bytes;   // presq_bytes + wide_ws_bytes + (nsplit > 1 ? nsplit * din * (dout - wide_cols) * 4 : 0)
 };
 
 // allow_wide = false keeps the plan on one block shape (the launches that produce several statistics at once need it)

@@ -946,9 +946,9 @@ hipError_t launch_square_bf16(const void* in, void* out, int64_t n, hipStream_t 
 namespace {
 
 // One statistic that needs two fp32 register tiles (phi = square, |.|^alpha, weighted sums).  The first
-// plan.wide_cols columns of S run on 256 x 192 blocks with the whole batch in every workgroup, straight into S; the
-// remaining columns on 256 x 128 blocks as plan.nsplit groups of examples (into S, or into partial sums of their own
-// row pitch when there are several groups).
+// plan.wide_cols columns of S run on 256 x 192 blocks as plan.wide_nsplit groups of examples, the remaining columns
+// on 256 x 128 blocks as plan.nsplit groups; each part writes straight into S when it is one group, else into partial
+// sums of its own row pitch (the wide part's first in the buffer).
 template <int OUTS>
 hipError_t launch_two_tile(const uint16_t* x, const uint16_t* g, int64_t B, int64_t T, int64_t din, int64_t dout, const StatPlan& plan,
                            float* S, float* partials, hipStream_t stream, const float* weight, float alpha)
@@ -959,14 +959,15 @@ hipError_t launch_two_tile(const uint16_t* x, const uint16_t* g, int64_t B, int6
         return launch_one<TL, OUTS>(x, g, B, T, din, dout, p, TO_ID ? out : nullptr, TO_ID ? nullptr : out, nullptr, stream, weight, nullptr,
                                     alpha, range);
     };
-    float* rest_out = plan.nsplit > 1 ? partials : S + plan.wide_cols;
-    if (plan.wide_cols == 0) return go(TilePhi{}, plan, rest_out, ColumnRange{});
-    StatPlan whole = plan;
-    whole.nsplit = 1;
-    whole.per_split = B;
-    hipError_t e = go(TilePhi192{}, whole, S, ColumnRange{0, plan.wide_cols, dout});
+    if (plan.wide_cols == 0) return go(TilePhi{}, plan, plan.nsplit > 1 ? partials : S, ColumnRange{});
+    StatPlan wide = plan;
+    wide.nsplit = plan.wide_nsplit;
+    wide.per_split = plan.wide_per_split;
+    hipError_t e = go(TilePhi192{}, wide, wide.nsplit > 1 ? partials : S, ColumnRange{0, plan.wide_cols, wide.nsplit > 1 ? plan.wide_cols : dout});
     const int64_t rest = dout - plan.wide_cols;
-    if (e == hipSuccess && rest > 0) e = go(TilePhi{}, plan, rest_out, ColumnRange{plan.wide_cols, rest, plan.nsplit > 1 ? rest : dout});
+    float* rest_partials = (float*)((char*)partials + plan.wide_ws_bytes);
+    if (e == hipSuccess && rest > 0)
+        e = go(TilePhi{}, plan, plan.nsplit > 1 ? rest_partials : S + plan.wide_cols, ColumnRange{plan.wide_cols, rest, plan.nsplit > 1 ? rest : dout});
     return e;
 }
 

@@ -125,8 +125,8 @@ def test_host_validation_launches_nothing():
     assert L.pex_stat_noalloc(X, G, *ok, 7, 0, S, None) == 3
     assert L.pex_stat_noalloc(X, G, *ok, 0, 9, S, None) == 4
     assert L.pex_stat_noalloc(X, G, *ok, 0, 0, S + 4, None) == 5
-    assert pex.pex_stat_workspace_bytes(32, 256, 512, 2048, pex.PEX_BF16, "sign") > pex.NOALLOC_SCRATCH_BYTES
-    assert L.pex_stat_noalloc(X, G, 32, 256, 512, 2048, 1, 2, S, None) == 8
+    assert pex.pex_stat_workspace_bytes(64, 1024, 768, 768, pex.PEX_BF16, "identity") > pex.NOALLOC_SCRATCH_BYTES
+    assert L.pex_stat_noalloc(X, G, 64, 1024, 768, 768, 1, 0, S, None) == 8
     assert L.pex_stat_multi(X, G, *ok, 0, 0, S, S, S, None, 0, None) == 4          # nothing wanted
     assert L.pex_stat_multi(X, G, *ok, 0, 8, S, S, S, None, 0, None) == 4
     assert L.pex_stat_multi(X, G, *ok, 0, 3, S, None, None, None, 0, None) == 1     # square wanted, no output for it

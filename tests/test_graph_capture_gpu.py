@@ -108,3 +108,61 @@ def test_four_wave_contraction_is_deterministic_and_replays_from_a_graph(pex_opt
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(S, first)
+
+
+def test_a_per_example_clipped_gradient_sum_replays_from_a_graph():
+    """Norms of two layers -> clipping weights -> clipped gradient sums, all through the library, captured once and
+    replayed three times with eager work in between: every replay equals the eager run bit for bit.  The statistic
+    without a workspace argument (static scratch) is part of the captured work too."""
+    B, T = 10, 64
+    X1, G1 = si.custom(B, T, 264, 136, dtype="bf16", seed=41)
+    X2, G2 = si.custom(B, T, 136, 520, dtype="bf16", seed=42)
+    scale = torch.linspace(0.2, 3.0, B)[:, None, None]           # gradient norms from about 500 to 8000
+    X1, X2 = (X1.float() * scale).to(torch.bfloat16), (X2.float() * scale).to(torch.bfloat16)
+    d = [t.to(DEV) for t in (X1, G1, X2, G2)]
+    shapes = [(264, 136), (136, 520)]
+
+    def buffers():
+        b = dict(N=torch.empty(2, B, device=DEV), w=torch.empty(B, device=DEV),
+                 S=[torch.empty(*s, device=DEV) for s in shapes], Q=torch.empty(264, 136, device=DEV))
+        nb = [max(pex.pex_example_norms_workspace_bytes(B, T, s[0], s[1], pex.PEX_BF16),
+                  pex.pex_weighted_sum_workspace_bytes(B, T, s[0], s[1], pex.PEX_BF16), 16) for s in shapes]
+        b["ws"] = [torch.empty(n, dtype=torch.uint8, device=DEV) for n in nb]
+        return b
+
+    def step(b):
+        for l in range(2):
+            pex.pex_example_norms(d[2 * l], d[2 * l + 1], N=b["N"][l], workspace=b["ws"][l])
+        pex.pex_clip_weights(b["N"], 2600.0, w=b["w"])
+        for l in range(2):
+            pex.pex_weighted_sum(d[2 * l], d[2 * l + 1], b["w"], S=b["S"][l], workspace=b["ws"][l])
+        pex.pex_stat_noalloc(d[0], d[1], "square", b["Q"])
+
+    eager = buffers()
+    step(eager)
+    torch.cuda.synchronize()
+    assert float(eager["w"].min()) < 1.0 and float(eager["w"].max()) == 1.0     # the threshold cuts some examples, not all
+
+    graphed = buffers()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):            # first calls outside capture (the scratch address is looked up here)
+        step(graphed)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step(graphed)
+    torch.cuda.synchronize()
+    other = buffers()
+    for replay in range(3):
+        for t in (graphed["N"], graphed["w"], graphed["Q"], *graphed["S"]):
+            t.fill_(-1.0)
+        g.replay()
+        torch.cuda.synchronize()
+        step(other)                           # the program's own eager work between the replays
+        torch.cuda.synchronize()
+        for k in ("N", "w", "Q"):
+            assert torch.equal(graphed[k], eager[k]), f"replay {replay}: {k}"
+        for l in range(2):
+            assert torch.equal(graphed["S"][l], eager["S"][l]), f"replay {replay}: S[{l}]"

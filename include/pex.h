@@ -70,12 +70,18 @@ int pex_version(void);
  *                            (default: layers whose wide blocks fill whole rounds of the 256 compute units),
  *                            2 = as many columns as fit on the wide shape, always (environment PEX_WIDE_BLOCKS).
  *                            The result is the same bits under every value.
+ *   PEX_OPT_GRAM_NORMS       pex_example_norms on bf16 layers has two routes: the per-example contraction, and the T x T
+ *                            Gram matrices of the "ghost" norm (Sec. 2.3), N_b = <X_b X_b^T, G_b G_b^T>.  0 = the
+ *                            contraction only, 1 = chosen by a cost model (default: the Gram route for short
+ *                            sequences and layers of few tiles), 2 = the Gram route wherever it applies (rows that are
+ *                            multiples of 16 bytes, B <= 65535) (environment PEX_GRAM_NORMS).  The two routes agree to
+ *                            fp32 rounding, not bit for bit.
  * An option changes the plan and with it the *_workspace_bytes of later calls: query again after setting one.  A
  * call whose workspace was sized under another value returns PEX_ERR_WORKSPACE if it is too small.
  * pex_set_option: PEX_ERR_PHI for an unknown option, PEX_ERR_SHAPE for a value out of range.  pex_get_option: the
  * current value, -1 for an unknown option.
  */
-typedef enum { PEX_OPT_MAX_SPLIT = 0, PEX_OPT_TOKEN_PRESQUARE = 1, PEX_OPT_WIDE_BLOCKS = 2 } pex_option;
+typedef enum { PEX_OPT_MAX_SPLIT = 0, PEX_OPT_TOKEN_PRESQUARE = 1, PEX_OPT_WIDE_BLOCKS = 2, PEX_OPT_GRAM_NORMS = 3 } pex_option;
 pex_status pex_set_option(pex_option opt, int32_t value);
 int32_t pex_get_option(pex_option opt);
 

@@ -140,12 +140,13 @@ def lib() -> ctypes.CDLL:
     return _lib
 
 
-PEX_OPT_MAX_SPLIT, PEX_OPT_TOKEN_PRESQUARE, PEX_OPT_WIDE_BLOCKS = 0, 1, 2
-OPTION = {"max_split": PEX_OPT_MAX_SPLIT, "token_presquare": PEX_OPT_TOKEN_PRESQUARE, "wide_blocks": PEX_OPT_WIDE_BLOCKS}
+PEX_OPT_MAX_SPLIT, PEX_OPT_TOKEN_PRESQUARE, PEX_OPT_WIDE_BLOCKS, PEX_OPT_GRAM_NORMS = 0, 1, 2, 3
+OPTION = {"max_split": PEX_OPT_MAX_SPLIT, "token_presquare": PEX_OPT_TOKEN_PRESQUARE, "wide_blocks": PEX_OPT_WIDE_BLOCKS,
+          "gram_norms": PEX_OPT_GRAM_NORMS}
 
 
 def pex_set_option(opt, value) -> None:
-    """Set a planner option ('max_split' 1..32, 'token_presquare' 0|1|2, 'wide_blocks' 0|1|2, or the code)."""
+    """Set a planner option ('max_split' 1..32, 'token_presquare' 0|1|2, 'wide_blocks' 0|1|2, 'gram_norms' 0|1|2, or the code)."""
     _check(lib().pex_set_option(OPTION.get(opt, opt), int(value)))
 
 

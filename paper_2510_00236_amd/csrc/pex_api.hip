@@ -38,7 +38,7 @@ static hipError_t scratch_address(void** out)
 // Planner options.  Their first values come from the environment, read once per process; afterwards only
 // pex_set_option changes them.  Atomics, so a host thread that plans while another one sets an option reads a
 // whole value; a plan made under one value and launched under another is caught as PEX_ERR_WORKSPACE.
-constexpr int NUM_OPTIONS = 3;
+constexpr int NUM_OPTIONS = 4;
 struct Options {
     std::atomic<int> v[NUM_OPTIONS];
 };
@@ -48,7 +48,7 @@ static bool known_option(int opt) { return opt >= 0 && opt < NUM_OPTIONS; }
 static int clamp_option(int opt, int value)
 {
     if (opt == PEX_OPT_MAX_SPLIT) return value < 1 ? 1 : (value > 32 ? 32 : value);
-    return value < 0 ? 0 : (value > 2 ? 2 : value);      // PEX_OPT_TOKEN_PRESQUARE, PEX_OPT_WIDE_BLOCKS
+    return value < 0 ? 0 : (value > 2 ? 2 : value);      // PEX_OPT_TOKEN_PRESQUARE, PEX_OPT_WIDE_BLOCKS, PEX_OPT_GRAM_NORMS
 }
 
 static Options& options()
@@ -56,8 +56,8 @@ static Options& options()
     static Options o;
     static std::once_flag once;
     std::call_once(once, [] {
-        const char* names[NUM_OPTIONS] = {"PEX_MAX_SPLIT", "PEX_TOKEN_PRESQUARE", "PEX_WIDE_BLOCKS"};
-        const int dflt[NUM_OPTIONS] = {32, 1, 1};
+        const char* names[NUM_OPTIONS] = {"PEX_MAX_SPLIT", "PEX_TOKEN_PRESQUARE", "PEX_WIDE_BLOCKS", "PEX_GRAM_NORMS"};
+        const int dflt[NUM_OPTIONS] = {32, 1, 1, 1};
         for (int k = 0; k < NUM_OPTIONS; ++k) {
             const char* e = getenv(names[k]);
             o.v[k].store(clamp_option(k, (e && *e) ? atoi(e) : dflt[k]));
@@ -90,6 +90,9 @@ static double cheapest_split(int64_t tiles, int64_t units, double t_unit, double
 
 // Sustained rate of one compute unit on the bf16 blocks, FLOP/s (measured on Gaussian operands, 1B-scale layers):
 // the larger the block, the fewer bytes go from L2 into LDS and from LDS into registers per FLOP.
+// chip-wide rates of the two routes to the per-example norms, FLOP/s (measured)
+constexpr double GRAM_RATE = 3.0e14, DIRECT_NORM_RATE = 1.3e15;
+
 static double bf16_block_rate(int bm, int bn)
 {
     const int area = bm * bn;
@@ -132,7 +135,8 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
         // A unit-time is one example (or 64 rows) on one block.
         const double rows_per_unit = per_example ? (double)T : (double)slab;
         const double t_unit = 2.0 * rows_per_unit * bm * bn / bf16_block_rate(bm, bn);
-        double best = cheapest_split(tiles, units, t_unit, (double)din * (double)dout * 4.0, max_split, &nsplit, &per);
+        // (the per-example norms exchange no partial sums of S, only one number per workgroup and example)
+        double best = cheapest_split(tiles, units, t_unit, mode == MODE_NORMS ? 0.0 : (double)din * (double)dout * 4.0, max_split, &nsplit, &per);
         // One statistic on two register tiles may put its first columns on the wider block (256 x 192) and only the
         // remaining columns on the 256 x 128 block, each part with a split of the batch of its own.  Candidates: every
         // number of wide block columns up to 64, beyond that the largest number that fits k rounds of 256 workgroups,
@@ -189,8 +193,33 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
     p.wide_ws_bytes = (wide_cols > 0 && wide_nsplit > 1) ? (size_t)wide_nsplit * (size_t)din * (size_t)wide_cols * sizeof(float) : 0;
     p.ws_bytes = p.presq_bytes + p.wide_ws_bytes +
                  ((nsplit > 1 && dout > wide_cols) ? (size_t)nsplit * (size_t)din * (size_t)(dout - wide_cols) * sizeof(float) : 0);
-    if (mode == MODE_NORMS)   // no S at all: one partial of ||M_b||^2 per tile (and wave) and example
+    if (mode == MODE_NORMS) {   // no S at all: one partial of ||M_b||^2 per tile (and wave) and example
         p.ws_bytes = (size_t)(p.kernel == 1 ? bf16_norm_partials(din, dout) : generic_norm_partials(din, dout)) * (size_t)B * sizeof(float);
+        // Through the Gram matrices instead: 2 T^2 (din + dout) FLOP per example (a little over half of it with the
+        // symmetry, in 64 x 64 blocks) against 2 T din dout, on a kernel of lower rate but with one workgroup per block
+        // and example -- no batch split, however few tiles the layer has.
+        const int gram_opt = option(PEX_OPT_GRAM_NORMS);
+        if (dt == PEX_BF16 && gram_opt != 0 && gram_supports(B, T, din, dout)) {
+            // Gram kernel: 3.0e14 FLOP/s on a full chip, and never faster than its serial loop over the features,
+            // one 64-feature step per ~0.8 us (measured: it is bound by the latency of its loads when there are few
+            // blocks).  Contraction: the plan's rounds, plus ~20 us of start-up, epilogue and reduction on small layers.
+            const double steps = (double)((din + 63) / 64 + (dout + 63) / 64);
+            double t_gram = 2.0 * (double)B * (double)gram_norm_partials(T) * 64.0 * 64.0 * (double)(din + dout) / GRAM_RATE;
+            if (t_gram < steps * 0.8e-6) t_gram = steps * 0.8e-6;
+            t_gram += 6.0e-6;
+            double t_direct = 2.0 * (double)B * (double)T * (double)din * (double)dout / DIRECT_NORM_RATE;
+            if (p.kernel == 1) {
+                const double t_unit = 2.0 * (double)T * bm * bn / bf16_block_rate(bm, bn);
+                const double t_rounds = (double)((tiles * p.nsplit + 255) / 256) * (double)((B + p.nsplit - 1) / p.nsplit) * t_unit;
+                if (t_rounds > t_direct) t_direct = t_rounds;
+            }
+            t_direct += 20.0e-6;
+            if (gram_opt == 2 || t_gram < t_direct) {
+                p.gram = true;
+                p.ws_bytes = (size_t)gram_norm_partials(T) * (size_t)B * sizeof(float);
+            }
+        }
+    }
     return p;
 }
 
@@ -466,7 +495,10 @@ pex_status pex_example_norms(const void* X, const void* G, int64_t B, int64_t T,
     float* partial = (float*)workspace;
     hipError_t e;
     int64_t nparts;
-    if (plan.kernel == 1) {
+    if (plan.gram) {
+        nparts = gram_norm_partials(T);
+        e = launch_gram_norms(X, G, B, T, din, dout, partial, hs);
+    } else if (plan.kernel == 1) {
         nparts = bf16_norm_partials(din, dout);
         e = launch_norms_bf16(X, G, B, T, din, dout, plan, partial, hs);
     } else {

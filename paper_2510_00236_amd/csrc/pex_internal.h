@@ -28,6 +28,7 @@ struct StatPlan {
     int wide_nsplit;
     int64_t wide_per_split;
     size_t wide_ws_bytes; // partial sums of the wide part (first in the workspace after the squared copies), 0 if unsplit
+    bool gram;         // MODE_NORMS on bf16 layers: through the T x T Gram matrices instead of the contraction
     size_t ws_bytes;   // presq_bytes + wide_ws_bytes + (nsplit > 1 ? nsplit * din * (dout - wide_cols) * 4 : 0)
 };
 
@@ -49,6 +50,12 @@ hipError_t launch_norms_bf16(const void* X, const void* G, int64_t B, int64_t T,
                              float* norm_partial, hipStream_t stream);
 hipError_t launch_weighted_bf16(const void* X, const void* G, const float* w, int64_t B, int64_t T, int64_t din, int64_t dout,
                                 const StatPlan& plan, float* S, float* partials, hipStream_t stream);
+// Per-example squared norms through the Gram matrices X_b X_b^T and G_b G_b^T (bf16): one partial per 64 x 64 block of
+// their upper triangle and example, partial[block][B]
+int64_t gram_norm_partials(int64_t T);
+bool gram_supports(int64_t B, int64_t T, int64_t din, int64_t dout);
+hipError_t launch_gram_norms(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout, float* partial,
+                             hipStream_t stream);
 // N[b] = sum_{p < nparts} partial[p][b], p ascending
 hipError_t launch_reduce_norms(const float* partial, int64_t nparts, int64_t B, float* N, hipStream_t stream);
 // N_tok[r] = |x_r|^2 |g_r|^2 for every row r of the flattened [B*T] axis

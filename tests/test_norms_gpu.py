@@ -128,3 +128,49 @@ def test_per_example_clipping_of_a_two_layer_model_stays_on_the_device():
     w1 = pex.pex_clip_weights(N[0].contiguous(), c)
     np.testing.assert_allclose(w1.cpu().double().numpy(), on.clip_weights(ref_N[0], c), rtol=2e-5)
     assert torch.equal(pex.pex_clip_weights(torch.zeros(3, 5, device=DEV), 1.0), torch.ones(5, device=DEV))
+
+
+GRAM_SHAPES = [(5, 77, 520, 264), (3, 100, 200, 136), (7, 33, 256, 128), (1, 64, 96, 160), (40, 1, 128, 96),
+               (2, 130, 72, 40), (3, 257, 64, 64), (6, 300, 328, 200)]
+
+
+@pytest.mark.parametrize("B,T,din,dout", GRAM_SHAPES)
+def test_norms_through_the_gram_matrices(pex_option, B, T, din, dout):
+    """N_b = <X_b X_b^T, G_b G_b^T> (the "ghost" norm of Sec. 2.3) on its own kernel: blocks of the upper triangle with
+    ragged last rows, feature counts that are not multiples of the 64-feature step, T = 1.  Against the oracle (which
+    materialises M_b) and against the contraction route."""
+    X, G = si.custom(B, T, din, dout, dtype="bf16", seed=B * 7 + T)
+    Xd, Gd = X.to(DEV), G.to(DEV)
+    ref = on.example_norms(si.widen(X), si.widen(G))
+    pex_option("gram_norms", 0)
+    direct = pex.pex_example_norms(Xd, Gd).cpu().double().numpy()
+    pex_option("gram_norms", 2)
+    nblk = (T + 63) // 64
+    assert pex.pex_example_norms_workspace_bytes(B, T, din, dout, pex.PEX_BF16) == nblk * (nblk + 1) // 2 * B * 4
+    gram = pex.pex_example_norms(Xd, Gd)
+    again = pex.pex_example_norms(Xd, Gd)
+    torch.cuda.synchronize()
+    assert torch.equal(gram, again)                                     # fixed order of every sum
+    gram = gram.cpu().double().numpy()
+    assert np.abs(gram - ref).max() <= 2e-5 * ref.max(), (gram, ref)
+    assert (np.abs(gram - ref) <= 1e-4 * ref + 1e-30).all()
+    assert (np.abs(gram - direct) <= 1e-4 * ref + 1e-30).all()
+
+
+def test_gram_route_where_the_planner_takes_it():
+    """B=8, T=512, 4096 x 4096: short sequences on a large layer, the shape class the cost model sends through the Gram
+    matrices; compared with the contraction route and, on two examples, with the oracle."""
+    B, T, din, dout = 8, 512, 4096, 4096
+    nblk = T // 64
+    assert pex.pex_example_norms_workspace_bytes(B, T, din, dout, pex.PEX_BF16) == nblk * (nblk + 1) // 2 * B * 4
+    X, G = si.custom(B, T, din, dout, dtype="bf16", seed=17)
+    Xd, Gd = X.to(DEV), G.to(DEV)
+    planned = pex.pex_example_norms(Xd, Gd).cpu().double().numpy()
+    ref = on.example_norms(si.widen(X[:2]), si.widen(G[:2]))
+    assert (np.abs(planned[:2] - ref) <= 1e-4 * ref).all()
+    pex.pex_set_option("gram_norms", 0)
+    try:
+        direct = pex.pex_example_norms(Xd, Gd).cpu().double().numpy()
+    finally:
+        pex.pex_set_option("gram_norms", 1)
+    assert (np.abs(planned - direct) <= 1e-4 * direct).all()

@@ -101,7 +101,8 @@ int32_t pex_get_option(pex_option opt);
  *                               32 * din*dout*4 bytes, whatever B (reached by small layers only, where
  *                               many groups are needed to occupy the chip; at the 1B-scale shapes identity
  *                               and sign need none, and square splits only the columns its wider block
- *                               shape leaves over, in two groups: half the size of S).
+ *                               shape leaves over, in two groups: half the size of S).  Partial sign counts
+ *                               of bf16 layers are held as bytes while a group has at most 127 examples.
  *   The contraction over T of one example is never split across workgroups (phi is applied to the complete
  *   sum over the sequence), the sum over b is taken in a fixed order.
  *   Any B,T,din,dout >= 1 is accepted with B*T, din, dout each < 2^31; fp32 inputs and bf16 layers whose rows are

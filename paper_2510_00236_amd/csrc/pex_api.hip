@@ -125,6 +125,7 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
     const int max_split = option(PEX_OPT_MAX_SPLIT);
     int64_t nsplit = 1, per = units;
     int64_t wide_cols = 0, wide_nsplit = 1, wide_per = units;
+    bool sign_bytes = false;
     if (p.kernel != 1) {
         nsplit = (target + tiles - 1) / tiles;
         if (nsplit > max_split) nsplit = max_split;
@@ -137,6 +138,18 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
         const double t_unit = 2.0 * rows_per_unit * bm * bn / bf16_block_rate(bm, bn);
         // (the per-example norms exchange no partial sums of S, only one number per workgroup and example)
         double best = cheapest_split(tiles, units, t_unit, mode == MODE_NORMS ? 0.0 : (double)din * (double)dout * 4.0, max_split, &nsplit, &per);
+        // Packed sign counts can be exchanged as bytes while a group holds at most 127 examples: a quarter of the
+        // traffic, so more groups pay.  Planned with that cost; kept if the groups it gives are small enough.
+        if (mode == MODE_SIGN && bm == 256 && bn == 256) {
+            int64_t ns_b = 1, per_b = units;
+            const double cost_b = cheapest_split(tiles, units, t_unit, (double)sign_byte_partial_bytes(din, dout), max_split, &ns_b, &per_b);
+            if (ns_b > 1 && sign_byte_partials_possible(B, per_b) && cost_b <= best) {
+                best = cost_b;
+                nsplit = ns_b;
+                per = per_b;
+                sign_bytes = true;
+            }
+        }
         // One statistic on two register tiles may put its first columns on the wider block (256 x 192) and only the
         // remaining columns on the 256 x 128 block, each part with a split of the batch of its own.  Candidates: every
         // number of wide block columns up to 64, beyond that the largest number that fits k rounds of 256 workgroups,
@@ -187,12 +200,14 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
         if (t_pre < t_fused_extra || presquare == 2)
             p.presq_bytes = (((size_t)B * (size_t)T * (size_t)(din + dout) * 2) + 255) & ~(size_t)255;
     }
+    p.sign_bytes = sign_bytes && nsplit > 1;
     p.wide_cols = wide_cols;
     p.wide_nsplit = (int)wide_nsplit;
     p.wide_per_split = wide_per;
     p.wide_ws_bytes = (wide_cols > 0 && wide_nsplit > 1) ? (size_t)wide_nsplit * (size_t)din * (size_t)wide_cols * sizeof(float) : 0;
     p.ws_bytes = p.presq_bytes + p.wide_ws_bytes +
                  ((nsplit > 1 && dout > wide_cols) ? (size_t)nsplit * (size_t)din * (size_t)(dout - wide_cols) * sizeof(float) : 0);
+    if (p.sign_bytes) p.ws_bytes = (size_t)nsplit * sign_byte_partial_bytes(din, dout);
     if (mode == MODE_NORMS) {   // no S at all: one partial of ||M_b||^2 per tile (and wave) and example
         p.ws_bytes = (size_t)(p.kernel == 1 ? bf16_norm_partials(din, dout) : generic_norm_partials(din, dout)) * (size_t)B * sizeof(float);
         // Through the Gram matrices instead: 2 T^2 (din + dout) FLOP per example (a little over half of it with the
@@ -281,7 +296,8 @@ static pex_status run_stat(const void* X, const void* G, int64_t B, int64_t T, i
             if (e != hipSuccess) return PEX_ERR_HIP;
         }
     } else if (plan.nsplit > 1) {
-        e = launch_reduce_partials(partials, plan.nsplit, din * dout, S, stream);
+        e = plan.sign_bytes ? launch_reduce_sign_bytes(partials, plan.nsplit, din, dout, S, stream)
+                            : launch_reduce_partials(partials, plan.nsplit, din * dout, S, stream);
         if (e != hipSuccess) return PEX_ERR_HIP;
     }
     return PEX_OK;

@@ -28,6 +28,7 @@ struct StatPlan {
     int wide_nsplit;
     int64_t wide_per_split;
     size_t wide_ws_bytes; // partial sums of the wide part (first in the workspace after the squared copies), 0 if unsplit
+    bool sign_bytes;   // MODE_SIGN on bf16 layers, split batch: the partial counts are bytes (per tile layout), not fp32
     bool gram;         // MODE_NORMS on bf16 layers: through the T x T Gram matrices instead of the contraction
     size_t ws_bytes;   // presq_bytes + wide_ws_bytes + (nsplit > 1 ? nsplit * din * (dout - wide_cols) * 4 : 0)
 };
@@ -80,6 +81,11 @@ hipError_t launch_stat_f32(const void* X, const void* G, int64_t B, int64_t T, i
 hipError_t launch_square_bf16(const void* in, void* out, int64_t n, hipStream_t stream);
 void bf16_tile_shape(Mode mode, int64_t B, int* bm, int* bn);
 void bf16_wide_tile_shape(int* bm, int* bn);
+// byte-wide partial sign counts of a split batch (bf16, at most 127 examples per group): size of one group's partials,
+// and their sum into S
+bool sign_byte_partials_possible(int64_t B, int64_t per_split);
+size_t sign_byte_partial_bytes(int64_t din, int64_t dout);
+hipError_t launch_reduce_sign_bytes(const void* partial, int nsplit, int64_t din, int64_t dout, float* S, hipStream_t stream);
 
 // Vector parameters (offsets, elementwise scales): the length axis of each example is cut into nrange ranges of
 // rows_per_range tokens; the workspace holds [B][nrange][d] fp32 partial sums.

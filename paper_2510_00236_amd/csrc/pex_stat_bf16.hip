@@ -277,7 +277,8 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
                                                               int64_t rows_per_split, int tiles_m, int tiles_n,
                                                               float* __restrict__ out_id, float* __restrict__ out_sq,
                                                               float* __restrict__ out_sg, const float* __restrict__ weight,
-                                                              float* __restrict__ norm_partial, int examples_total, float alpha)
+                                                              float* __restrict__ norm_partial, int examples_total, float alpha,
+                                                              int byte_partials)
 {
     constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK, NS = TL::NS, FM = TL::FM, FN = TL::FN, KS = TL::KS;
     constexpr int XROW = TL::XROW, GROW = TL::GROW, NXI = TL::NXI, NGI0 = TL::NGI0, NGI1 = TL::NGI1, RX = TL::RX;
@@ -551,6 +552,25 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
     wait_vmcnt<0>();   // drain the (empty) loads issued past the end before the LDS is released
 
     // ---- epilogue: lane holds column (lane%16), rows 4*(lane/16) + r of each 16x16 tile
+    // Packed sign counts of a split batch leave as bytes: one dword per lane and 16 x 16 tile holding the lane's four
+    // counts (rows ib .. ib+3 of column jn; at most 127 examples per group), laid out [split][tile][wave][tile of the
+    // wave][lane] -- a quarter of the bytes of fp32 partial sums, in dense 256-byte stores.
+    if constexpr (HAS_PK) {
+        if (byte_partials) {
+            uint32_t* dst = reinterpret_cast<uint32_t*>(out_sg) +
+                            ((((int64_t)split * tiles_m + tm) * tiles_n + tn) * TL::NWAVES + wave) * (int64_t)(FM * FN * 64) + lane;
+#pragma unroll
+            for (int a = 0; a < FM; ++a)
+#pragma unroll
+                for (int c = 0; c < FN; ++c) {
+                    uint32_t w = 0;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) w |= ((uint32_t)(int)cnt[a][c][r / 2][r % 2] & 0xffu) << (8 * r);
+                    dst[(a * FN + c) * 64] = w;
+                }
+            return;
+        }
+    }
     // outputs have their own row pitch: S itself (pointing at the first column of the range, pitch of the whole
     // layer) or partials [split][din][ldo]
     const int64_t split_off = (int64_t)split * din * ldo;
@@ -612,7 +632,7 @@ template <typename TL, int OUTS>
 hipError_t launch_one(const uint16_t* X, const uint16_t* G, int64_t B, int64_t T, int64_t din, int64_t dout,
                       const StatPlan& plan, float* out_id, float* out_sq, float* out_sg, hipStream_t stream,
                       const float* weight = nullptr, float* norm_partial = nullptr, float alpha = 0.f,
-                      ColumnRange range = ColumnRange{})
+                      ColumnRange range = ColumnRange{}, bool byte_partials = false)
 {
     constexpr bool PER_EXAMPLE = !(OUTS == OUT_ID || OUTS == OUT_TOKEN);
     const int64_t ldg = dout;
@@ -632,7 +652,7 @@ hipError_t launch_one(const uint16_t* X, const uint16_t* G, int64_t B, int64_t T
     if (attr_err != hipSuccess) return attr_err;
     const dim3 grid((unsigned)(tiles_m * tiles_n * plan.nsplit)), block(TL::NT);
     kern<<<grid, block, TL::LDS_BYTES, stream>>>(X, G, B * T, (int)T, (int)din, (int)dout, (int)ldg, (int)ldo, rows_per_split, tiles_m,
-                                                 tiles_n, out_id, out_sq, out_sg, weight, norm_partial, (int)B, alpha);
+                                                 tiles_n, out_id, out_sq, out_sg, weight, norm_partial, (int)B, alpha, byte_partials ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -916,7 +936,50 @@ hipError_t launch_quad(const uint16_t* X, const uint16_t* G, int64_t B, int64_t 
 // sign counts are packed (and the tile is 256 x 256) while a group of examples cannot exceed 2048
 bool sign_is_packed(int64_t B) { return B <= 2048; }
 
+// S = sum over the groups of the byte-wide partial sign counts the 256 x 256 kernel leaves (see its epilogue): one
+// thread per dword, groups added in ascending order (integers: any order gives the same sum)
+__global__ __launch_bounds__(256) void reduce_sign_bytes_kernel(const uint32_t* __restrict__ partial, int nsplit, int tiles_m, int tiles_n,
+                                                                int din, int dout, float* __restrict__ S)
+{
+    using TL = TileWide;
+    constexpr int PER_WAVE = TL::FM * TL::FN * 64, PER_TILE = PER_WAVE * TL::NWAVES;
+    const int64_t total = (int64_t)tiles_m * tiles_n * PER_TILE;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    int sum[4] = {0, 0, 0, 0};
+    for (int s = 0; s < nsplit; ++s) {
+        const uint32_t w = partial[(int64_t)s * total + idx];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sum[r] += (int)(signed char)((w >> (8 * r)) & 0xffu);
+    }
+    const int lane = (int)(idx % 64), f = (int)((idx / 64) % (TL::FM * TL::FN)), wave = (int)((idx / PER_WAVE) % TL::NWAVES);
+    const int tile = (int)(idx / PER_TILE), tm = tile / tiles_n, tn = tile % tiles_n;
+    const int a = f / TL::FN, c = f % TL::FN, wm = wave / TL::WAVES_N, wn = wave % TL::WAVES_N;
+    const int j = tn * TL::BN + wn * TL::WN + c * 16 + lane % 16;
+    const int i = tm * TL::BM + wm * TL::WM + a * 16 + 4 * (lane / 16);
+    if (j < dout) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            if (i + r < din) S[(int64_t)(i + r) * dout + j] = (float)sum[r];
+    }
+}
+
 }  // namespace
+
+// Packed sign counts of a split batch can leave the kernel as bytes when no group exceeds 127 examples.
+bool sign_byte_partials_possible(int64_t B, int64_t per_split) { return sign_is_packed(B) && per_split <= MAX_U8_EXAMPLES; }
+size_t sign_byte_partial_bytes(int64_t din, int64_t dout)
+{
+    return (size_t)((din + TileWide::BM - 1) / TileWide::BM) * (size_t)((dout + TileWide::BN - 1) / TileWide::BN) * (size_t)(TileWide::BM * TileWide::BN);
+}
+hipError_t launch_reduce_sign_bytes(const void* partial, int nsplit, int64_t din, int64_t dout, float* S, hipStream_t stream)
+{
+    const int tiles_m = (int)((din + TileWide::BM - 1) / TileWide::BM), tiles_n = (int)((dout + TileWide::BN - 1) / TileWide::BN);
+    const int64_t total = (int64_t)tiles_m * tiles_n * (TileWide::BM * TileWide::BN / 4);
+    reduce_sign_bytes_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream>>>((const uint32_t*)partial, nsplit, tiles_m, tiles_n,
+                                                                                             (int)din, (int)dout, S);
+    return hipGetLastError();
+}
 
 void bf16_tile_shape(Mode mode, int64_t B, int* bm, int* bn)
 {
@@ -988,7 +1051,9 @@ hipError_t launch_stat_bf16(const void* X, const void* G, int64_t B, int64_t T, 
     case MODE_TOKEN_SQ: return launch_one<TileToken, OUT_TOKEN>(x, g, B, T, din, dout, plan, out, nullptr, nullptr, stream);
     case MODE_SQUARE: return launch_two_tile<OUT_SQ>(x, g, B, T, din, dout, plan, S, partials, stream, nullptr, 0.f);
     case MODE_SIGN:
-        if (sign_is_packed(B)) return launch_one<TileWide, OUT_SIGN_PK>(x, g, B, T, din, dout, plan, nullptr, nullptr, out, stream);
+        if (sign_is_packed(B))
+            return launch_one<TileWide, OUT_SIGN_PK>(x, g, B, T, din, dout, plan, nullptr, nullptr, out, stream, nullptr, nullptr, 0.f,
+                                                     ColumnRange{}, plan.sign_bytes);
         return launch_one<TilePhi, OUT_SIGN_F32>(x, g, B, T, din, dout, plan, nullptr, nullptr, out, stream);
     default: return hipErrorInvalidValue;
     }

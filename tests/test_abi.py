@@ -61,16 +61,18 @@ def test_planner_options_are_clamped_and_change_the_plan():
     finally:
         pex.pex_set_option("wide_blocks", 1)
     shape = (32, 256, 512, 2048)
-    full = pex.pex_stat_workspace_bytes(*shape, pex.PEX_BF16, "sign")
+    full = pex.pex_stat_workspace_bytes(*shape, pex.PEX_BF16, "identity")
     try:
         pex.pex_set_option("max_split", 4)
         assert pex.pex_get_option("max_split") == 4
-        assert 0 < pex.pex_stat_workspace_bytes(*shape, pex.PEX_BF16, "sign") <= 4 * 512 * 2048 * 4 < full
+        assert 0 < pex.pex_stat_workspace_bytes(*shape, pex.PEX_BF16, "identity") <= 4 * 512 * 2048 * 4 < full
+        assert 0 < pex.pex_stat_workspace_bytes(*shape, pex.PEX_BF16, "sign") <= 4 * 512 * 2048       # byte-wide partial counts
         pex.pex_set_option("max_split", 1)
+        assert pex.pex_stat_workspace_bytes(*shape, pex.PEX_BF16, "identity") == 0
         assert pex.pex_stat_workspace_bytes(*shape, pex.PEX_BF16, "sign") == 0
     finally:
         pex.pex_set_option("max_split", 32)
-    assert pex.pex_stat_workspace_bytes(*shape, pex.PEX_BF16, "sign") == full
+    assert pex.pex_stat_workspace_bytes(*shape, pex.PEX_BF16, "identity") == full
     # a width whose tiles do not fit the second grid dimension of the fp32 and SIMT kernels is refused up front
     assert L.pex_stat(0x1000, 0x2000, 1, 1, 65535 * 128 + 1, 8, 0, 0, 0x3000, None, 0, None) == 2
     assert L.pex_stat(0x1000, 0x2000, 1, 1, 65535 * 64 + 1, 8, 1, 0, 0x3000, None, 0, None) == 2
@@ -90,7 +92,10 @@ def test_workspace_query_is_bounded_and_independent_of_B():
     for (B, T, din, dout) in [(32, 256, 512, 2048), (64, 1024, 768, 768), (16, 2048, 2048, 8192), (4, 8192, 4096, 4096)]:
         for phi in ("identity", "square", "sign"):
             ws = pex.pex_stat_workspace_bytes(B, T, din, dout, pex.PEX_BF16, phi)
-            assert ws % (din * 8 * 4) == 0            # whole groups of whole rows of a column range
+            if phi == "sign":
+                assert ws % (256 * 256) == 0          # groups of byte-wide counts, one byte per entry of a padded 256 x 256 tile
+            else:
+                assert ws % (din * 8 * 4) == 0        # whole groups of whole rows of a column range
             assert ws <= 32 * din * dout * 4
             assert ws < B * din * dout * 4 or B <= 32
         # per-token square: partial sums plus, on large layers, bf16 copies of the squared operands

@@ -341,3 +341,22 @@ def test_wide_blocks_side_by_side_with_narrow_ones(pex_option, B, T, din, dout):
     # either block shape folds the same per-example tiles; only the grouping of the sum over b may differ
     for a, b in zip(wide, narrow):
         assert float((a - b).abs().max()) <= 2e-6 * float(b.abs().max())
+
+
+@pytest.mark.parametrize("B,expect_bytes", [(254, True), (256, False)])
+def test_sign_partials_at_the_byte_limit(pex_option, B, expect_bytes):
+    """Two groups of 127 examples exchange their sign counts as bytes (+-127 is the largest a byte holds), two groups of
+    128 as fp32; all examples agree in sign, so every partial count sits at the limit."""
+    pex_option("max_split", 2)
+    T, din, dout = 64, 256, 248
+    need = pex.pex_stat_workspace_bytes(B, T, din, dout, pex.PEX_BF16, "sign")
+    assert need == (2 * 256 * 256 if expect_bytes else 2 * din * dout * 4)
+    X = torch.ones(B, T, din, dtype=torch.bfloat16)
+    G = torch.ones(B, T, dout, dtype=torch.bfloat16)
+    G[:, :, 48:] = -1
+    G[:, :, 95] = 0                                           # a column of exact zeros: sgn(0) = 0 through the bytes too
+    S = pex.pex_stat(X.to(DEV), G.to(DEV), "sign").cpu()
+    assert torch.equal(S[:, :48], torch.full((din, 48), float(B)))
+    assert torch.equal(S[:, 48:95], torch.full((din, 47), -float(B)))
+    assert torch.equal(S[:, 95], torch.zeros(din))
+    assert torch.equal(S[:, 96:], torch.full((din, dout - 96), -float(B)))

@@ -76,12 +76,20 @@ int pex_version(void);
  *                            sequences and layers of few tiles), 2 = the Gram route wherever it applies (rows that are
  *                            multiples of 16 bytes, B <= 65535) (environment PEX_GRAM_NORMS).  The two routes agree to
  *                            fp32 rounding, not bit for bit.
+ *   PEX_OPT_MEMORY_FOLD      the same three calls have a third route on bf16 layers: the 256 x 256 block with one register
+ *                            tile, phi(M_b) being added to S in memory at the end of every example (by the one lane
+ *                            that owns the entry, examples in ascending order: as reproducible as a register).  Each
+ *                            such fold moves the whole of S once, so it pays for few, long examples only.  0 = never,
+ *                            1 = chosen by a cost model (default), 2 = wherever it applies (dout < 2^21) (environment
+ *                            PEX_MEMORY_FOLD).  It rounds the square before adding it where the register tiles use a
+ *                            fused multiply-add: the routes agree to fp32 rounding, not bit for bit.
  * An option changes the plan and with it the *_workspace_bytes of later calls: query again after setting one.  A
  * call whose workspace was sized under another value returns PEX_ERR_WORKSPACE if it is too small.
  * pex_set_option: PEX_ERR_PHI for an unknown option, PEX_ERR_SHAPE for a value out of range.  pex_get_option: the
  * current value, -1 for an unknown option.
  */
-typedef enum { PEX_OPT_MAX_SPLIT = 0, PEX_OPT_TOKEN_PRESQUARE = 1, PEX_OPT_WIDE_BLOCKS = 2, PEX_OPT_GRAM_NORMS = 3 } pex_option;
+typedef enum { PEX_OPT_MAX_SPLIT = 0, PEX_OPT_TOKEN_PRESQUARE = 1, PEX_OPT_WIDE_BLOCKS = 2, PEX_OPT_GRAM_NORMS = 3,
+               PEX_OPT_MEMORY_FOLD = 4 } pex_option;
 pex_status pex_set_option(pex_option opt, int32_t value);
 int32_t pex_get_option(pex_option opt);
 

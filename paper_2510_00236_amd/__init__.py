@@ -140,13 +140,13 @@ def lib() -> ctypes.CDLL:
     return _lib
 
 
-PEX_OPT_MAX_SPLIT, PEX_OPT_TOKEN_PRESQUARE, PEX_OPT_WIDE_BLOCKS, PEX_OPT_GRAM_NORMS = 0, 1, 2, 3
+PEX_OPT_MAX_SPLIT, PEX_OPT_TOKEN_PRESQUARE, PEX_OPT_WIDE_BLOCKS, PEX_OPT_GRAM_NORMS, PEX_OPT_MEMORY_FOLD = 0, 1, 2, 3, 4
 OPTION = {"max_split": PEX_OPT_MAX_SPLIT, "token_presquare": PEX_OPT_TOKEN_PRESQUARE, "wide_blocks": PEX_OPT_WIDE_BLOCKS,
-          "gram_norms": PEX_OPT_GRAM_NORMS}
+          "gram_norms": PEX_OPT_GRAM_NORMS, "memory_fold": PEX_OPT_MEMORY_FOLD}
 
 
 def pex_set_option(opt, value) -> None:
-    """Set a planner option ('max_split' 1..32, 'token_presquare' 0|1|2, 'wide_blocks' 0|1|2, 'gram_norms' 0|1|2, or the code)."""
+    """Set a planner option ('max_split' 1..32, 'token_presquare' 0|1|2, 'wide_blocks' 0|1|2, 'gram_norms' 0|1|2, 'memory_fold' 0|1|2, or the code)."""
     _check(lib().pex_set_option(OPTION.get(opt, opt), int(value)))
 
 

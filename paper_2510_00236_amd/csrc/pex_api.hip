@@ -38,7 +38,7 @@ static hipError_t scratch_address(void** out)
 // Planner options.  Their first values come from the environment, read once per process; afterwards only
 // pex_set_option changes them.  Atomics, so a host thread that plans while another one sets an option reads a
 // whole value; a plan made under one value and launched under another is caught as PEX_ERR_WORKSPACE.
-constexpr int NUM_OPTIONS = 4;
+constexpr int NUM_OPTIONS = 5;
 struct Options {
     std::atomic<int> v[NUM_OPTIONS];
 };
@@ -48,7 +48,7 @@ static bool known_option(int opt) { return opt >= 0 && opt < NUM_OPTIONS; }
 static int clamp_option(int opt, int value)
 {
     if (opt == PEX_OPT_MAX_SPLIT) return value < 1 ? 1 : (value > 32 ? 32 : value);
-    return value < 0 ? 0 : (value > 2 ? 2 : value);      // PEX_OPT_TOKEN_PRESQUARE, PEX_OPT_WIDE_BLOCKS, PEX_OPT_GRAM_NORMS
+    return value < 0 ? 0 : (value > 2 ? 2 : value);      // every other option: 0 = off, 1 = cost model, 2 = forced
 }
 
 static Options& options()
@@ -56,8 +56,8 @@ static Options& options()
     static Options o;
     static std::once_flag once;
     std::call_once(once, [] {
-        const char* names[NUM_OPTIONS] = {"PEX_MAX_SPLIT", "PEX_TOKEN_PRESQUARE", "PEX_WIDE_BLOCKS", "PEX_GRAM_NORMS"};
-        const int dflt[NUM_OPTIONS] = {32, 1, 1, 1};
+        const char* names[NUM_OPTIONS] = {"PEX_MAX_SPLIT", "PEX_TOKEN_PRESQUARE", "PEX_WIDE_BLOCKS", "PEX_GRAM_NORMS", "PEX_MEMORY_FOLD"};
+        const int dflt[NUM_OPTIONS] = {32, 1, 1, 1, 1};
         for (int k = 0; k < NUM_OPTIONS; ++k) {
             const char* e = getenv(names[k]);
             o.v[k].store(clamp_option(k, (e && *e) ? atoi(e) : dflt[k]));
@@ -72,8 +72,12 @@ static int option(int opt) { return options().v[opt].load(); }
 //   rounds(ns) * ceil(units / ns)  unit-times,  rounds = ceil(tiles * ns / 256),
 // its workgroups write ns copies of the output (s_bytes each) and the fixed-order reduction reads them back and writes
 // the sum, all at ~4 TB/s.
+// fold_bytes > 0: every workgroup adds that many bytes to the output in memory after each of its units but the first
+// (which stores); the workgroups of a round do so at the same time, and what they move -- read and written back
+// across the fabric -- goes at ~5.5 TB/s while they wait (measured: 22 - 29 us for the 67 MB of a 1B-scale layer).
 // Returns the cheapest cost over ns <= max_split and the split that reaches it.
-static double cheapest_split(int64_t tiles, int64_t units, double t_unit, double s_bytes, int max_split, int64_t* nsplit, int64_t* per)
+static double cheapest_split(int64_t tiles, int64_t units, double t_unit, double s_bytes, int max_split, int64_t* nsplit, int64_t* per,
+                             double fold_bytes = 0.0)
 {
     double best = 0.0;
     const int64_t lim = units < max_split ? units : max_split;
@@ -82,6 +86,10 @@ static double cheapest_split(int64_t tiles, int64_t units, double t_unit, double
         const int64_t ns_eff = (units + pu - 1) / pu;
         const int64_t rounds = (tiles * ns_eff + 255) / 256;
         double cost = (double)rounds * (double)pu * t_unit;
+        if (fold_bytes > 0.0) {
+            const int64_t at_once = tiles * ns_eff < 256 ? tiles * ns_eff : 256;
+            cost += (double)rounds * (double)(pu - 1) * (2.0 * (double)at_once * fold_bytes / 5.5e12 + 2.0e-6);
+        }
         if (ns_eff > 1) cost += (2 * ns_eff + 1) * s_bytes / 4.0e12 + 3.0e-6;
         if (ns == 1 || cost < best) { best = cost; *nsplit = ns_eff; *per = pu; }
     }
@@ -125,7 +133,7 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
     const int max_split = option(PEX_OPT_MAX_SPLIT);
     int64_t nsplit = 1, per = units;
     int64_t wide_cols = 0, wide_nsplit = 1, wide_per = units;
-    bool sign_bytes = false;
+    bool sign_bytes = false, mem_fold = false;
     if (p.kernel != 1) {
         nsplit = (target + tiles - 1) / tiles;
         if (nsplit > max_split) nsplit = max_split;
@@ -184,6 +192,26 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
             if (max_wide > 64) consider(max_wide, false);
             if (wide_opt == 2 && max_wide >= 1) consider(max_wide, true);      // forced: as many wide block columns as fit
         }
+        // ... or keep no second register tile at all: 256 x 256 blocks (eight waves: 5.2e12 FLOP/s per compute unit) that
+        // add phi(M_b) to the output in memory at the end of every example
+        const int fold_opt = option(PEX_OPT_MEMORY_FOLD);
+        if (allow_wide && fold_opt != 0 && (mode == MODE_SQUARE || mode == MODE_WEIGHTED || mode == MODE_POWER) && bm == 256 && bn == 128 &&
+            dout < ((int64_t)1 << 21)) {
+            int fm, fn;
+            bf16_tile_shape(MODE_IDENTITY, B, &fm, &fn);
+            const int64_t tiles_f = ((din + fm - 1) / fm) * ((dout + fn - 1) / fn);
+            int64_t ns_f = 1, per_f = units;
+            const double cost = cheapest_split(tiles_f, units, 2.0 * (double)T * fm * fn / 5.2e12, (double)din * (double)dout * 4.0, max_split,
+                                               &ns_f, &per_f, (double)fm * fn * 4.0);
+            if (fold_opt == 2 || cost < best) {
+                best = cost;
+                mem_fold = true;
+                wide_cols = 0;
+                wide_nsplit = 1;
+                nsplit = ns_f;
+                per = per_f;
+            }
+        }
     }
     nsplit = (units + per - 1) / per;      // no empty group
     p.nsplit = (int)nsplit;
@@ -201,6 +229,7 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
             p.presq_bytes = (((size_t)B * (size_t)T * (size_t)(din + dout) * 2) + 255) & ~(size_t)255;
     }
     p.sign_bytes = sign_bytes && nsplit > 1;
+    p.mem_fold = mem_fold;
     p.wide_cols = wide_cols;
     p.wide_nsplit = (int)wide_nsplit;
     p.wide_per_split = wide_per;

@@ -28,6 +28,8 @@ struct StatPlan {
     int wide_nsplit;
     int64_t wide_per_split;
     size_t wide_ws_bytes; // partial sums of the wide part (first in the workspace after the squared copies), 0 if unsplit
+    bool mem_fold;     // bf16, one statistic that would need two register tiles: 256 x 256 blocks, phi(M_b) added to the output
+                       // in memory at the end of every example (nsplit / per_split describe the whole layer, wide_cols = 0)
     bool sign_bytes;   // MODE_SIGN on bf16 layers, split batch: the partial counts are bytes (per tile layout), not fp32
     bool gram;         // MODE_NORMS on bf16 layers: through the T x T Gram matrices instead of the contraction
     size_t ws_bytes;   // presq_bytes + wide_ws_bytes + (nsplit > 1 ? nsplit * din * (dout - wide_cols) * 4 : 0)

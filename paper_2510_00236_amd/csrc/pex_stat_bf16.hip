@@ -78,8 +78,12 @@ namespace {
 // OUT_NORM writes ||M_b||_F^2 of every example (one partial per tile and wave, summed by a second kernel);
 // OUT_IDW is the identity statistic with one weight per example, sum_b w_b M_b (what clipping needs).
 // OUT_POW is phi(m) = |m|^alpha through the hardware log2 / exp2 (relative error of a term about 1e-6 * alpha * |log2 m|).
+// OUT_MEM (with exactly one of OUT_SQ, OUT_IDW, OUT_POW): that statistic has no register tile; at the end of an example
+// phi(M_b) is added to the output in memory (the first example of the range stores).  Every entry belongs to one lane
+// of one workgroup, which adds its examples in ascending order: the result is the same sequential fp32 sum as in
+// registers, and as reproducible.
 constexpr int OUT_ID = 1, OUT_SQ = 2, OUT_SIGN_PK = 4, OUT_SIGN_F32 = 8, OUT_TOKEN = 16, OUT_SIGN_U8 = 32, OUT_NORM = 64,
-              OUT_IDW = 128, OUT_POW = 256;
+              OUT_IDW = 128, OUT_POW = 256, OUT_MEM = 512;
 constexpr int MAX_U8_EXAMPLES = 127;
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
@@ -113,6 +117,21 @@ __device__ __forceinline__ int4_t make_rsrc(const void* base, uint32_t num_recor
     r[2] = (int)num_records;
     r[3] = 0x00020000;                               // raw buffer, 32-bit data format
     return r;
+}
+
+// One dword per lane to (descriptor base + voff + soff): plain store, or fp32 add performed by the L2 (no value
+// returned).  Lanes whose offset is outside the descriptor's range do nothing.  Both count in vmcnt like the loads.
+// The sum of the offsets is formed inside the statement (the range check does not see the instruction's own scalar
+// offset), so that the compiler cannot keep one precomputed address per accumulator register alive across the main loop.
+__device__ __forceinline__ void mem_store_f32(float v, uint32_t voff, uint32_t soff, int4_t rsrc)
+{
+    uint32_t at;
+    asm volatile("v_add_u32 %0, %2, %3\n\tbuffer_store_dword %1, %0, %4, 0 offen" : "=&v"(at) : "v"(v), "v"(voff), "s"(soff), "s"(rsrc) : "memory");
+}
+__device__ __forceinline__ void mem_add_f32(float v, uint32_t voff, uint32_t soff, int4_t rsrc)
+{
+    uint32_t at;
+    asm volatile("v_add_u32 %0, %2, %3\n\tbuffer_atomic_add_f32 %1, %0, %4, 0 offen" : "=&v"(at) : "v"(v), "v"(voff), "s"(soff), "s"(rsrc) : "memory");
 }
 
 // s_waitcnt vmcnt(N) only.  Written as assembly: the compiler does not know about the direct-to-LDS loads and
@@ -289,10 +308,14 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
     constexpr bool PER_EXAMPLE = !(OUTS == OUT_ID || OUTS == OUT_TOKEN);
     constexpr bool HAS_W = (OUTS & OUT_IDW) != 0, HAS_NORM = (OUTS & OUT_NORM) != 0;
     constexpr bool HAS_POW = (OUTS & OUT_POW) != 0;
-    constexpr bool HAS_ID = (PER_EXAMPLE && (OUTS & OUT_ID)) || HAS_W, HAS_SQ = (OUTS & OUT_SQ) != 0 || HAS_POW;
+    constexpr bool TO_MEM = (OUTS & OUT_MEM) != 0;
+    constexpr bool HAS_ID = !TO_MEM && ((PER_EXAMPLE && (OUTS & OUT_ID)) || HAS_W);
+    constexpr bool HAS_SQ = !TO_MEM && ((OUTS & OUT_SQ) != 0 || HAS_POW);
     constexpr bool HAS_PK = (OUTS & OUT_SIGN_PK) != 0, HAS_SF = (OUTS & OUT_SIGN_F32) != 0, HAS_U8 = (OUTS & OUT_SIGN_U8) != 0;
     static_assert(!TOKEN || NS >= 4, "the per-token square needs its slab one phase earlier");
-    static_assert(HAS_PK + HAS_SF + HAS_U8 <= 1 && (OUTS & 511) == OUTS && OUTS != 0, "one representation of the sign counts");
+    static_assert(HAS_PK + HAS_SF + HAS_U8 <= 1 && (OUTS & 1023) == OUTS && OUTS != 0, "one representation of the sign counts");
+    static_assert(!TO_MEM || OUTS == (OUT_MEM | OUT_SQ) || OUTS == (OUT_MEM | OUT_IDW) || OUTS == (OUT_MEM | OUT_POW),
+                  "memory accumulation carries one statistic");
     static_assert(!(HAS_W && (OUTS & OUT_ID)), "identity is either weighted or not");
     static_assert(!(HAS_POW && ((OUTS & OUT_SQ) || HAS_W)), "the power statistic uses the square's register tile and the weight slot");
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
@@ -419,6 +442,22 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
             if (HAS_U8) cnt8[a][c] = 0u;
         }
 
+    // Memory accumulation: descriptor over this tile's part of the output (base at its first entry, ending with its
+    // last valid one: rows beyond the layer fall outside), one byte offset per lane and fragment column (columns
+    // beyond the layer get an offset outside every range).
+    [[maybe_unused]] uint32_t mem_off[FN];
+    [[maybe_unused]] int4_t mem_rsrc;
+    if constexpr (TO_MEM) {
+        float* base = (HAS_W ? out_id : out_sq) + (int64_t)split * din * ldo + (int64_t)i0 * ldo + j0;
+        const int rows_valid = din_avail < BM ? din_avail : BM, cols_valid = dout_avail < BN ? dout_avail : BN;
+        mem_rsrc = make_rsrc(base, (uint32_t)(((rows_valid - 1) * ldo + cols_valid) * 4));
+#pragma unroll
+        for (int c = 0; c < FN; ++c) {
+            const int j = wn * TL::WN + c * 16 + li;
+            mem_off[c] = j < dout_avail ? (uint32_t)(((wm * TL::WM + 4 * blk) * ldo + j) * 4) : 0x80000000u;
+        }
+    }
+
     // Fragments of one slab.  Fragment number f of a k-step: first the G fragments, then the X fragments, so the
     // ones read late (in the multiply phase) are the X fragments the last MFMAs use.
     bf16x8_t fa[KS][FM], fb[KS][FN];
@@ -483,10 +522,35 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
     };
     // end of an example: fold every tile; the example's number is needed for its weight and its norm
     int example = (int)(row_begin / (seg_len > 0 ? seg_len : 1));
+    [[maybe_unused]] const int first_example = example;
     auto fold_all = [&]() {
         float w = 1.0f, norm = 0.f;
         if constexpr (HAS_W) w = weight[example];
         if constexpr (HAS_POW) w = alpha;
+        if constexpr (TO_MEM) {
+            // phi(M_b) leaves for memory, row by row of the wave's sub-tile; the waits on vmcnt that follow count these
+            // operations too, which only makes them wait longer (loads return in order among themselves)
+            auto emit = [&](auto FIRST) {
+#pragma unroll
+                for (int a = 0; a < FM; ++a)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const uint32_t row_off = (uint32_t)((a * 16 + r) * ldo * 4);
+#pragma unroll
+                        for (int c = 0; c < FN; ++c) {
+                            const float m = acc[a][c][r];
+                            const float v = HAS_W ? w * m : (HAS_POW ? abs_power(m, w) : m * m);
+                            if constexpr (decltype(FIRST)::value) mem_store_f32(v, mem_off[c], row_off, mem_rsrc);
+                            else mem_add_f32(v, mem_off[c], row_off, mem_rsrc);
+                            acc[a][c][r] = 0.f;
+                        }
+                    }
+            };
+            if (example == first_example) emit(std::true_type{});
+            else emit(std::false_type{});
+            ++example;
+            return;
+        }
 #pragma unroll
         for (int a = 0; a < FM; ++a)
 #pragma unroll
@@ -1008,7 +1072,8 @@ hipError_t launch_square_bf16(const void* in, void* out, int64_t n, hipStream_t 
 
 namespace {
 
-// One statistic that needs two fp32 register tiles (phi = square, |.|^alpha, weighted sums).  The first
+// One statistic that needs two fp32 register tiles (phi = square, |.|^alpha, weighted sums) -- or, where the plan says
+// so, one register tile on 256 x 256 blocks and additions to the output in memory.  The first
 // plan.wide_cols columns of S run on 256 x 192 blocks as plan.wide_nsplit groups of examples, the remaining columns
 // on 256 x 128 blocks as plan.nsplit groups; each part writes straight into S when it is one group, else into partial
 // sums of its own row pitch (the wide part's first in the buffer).
@@ -1022,6 +1087,11 @@ hipError_t launch_two_tile(const uint16_t* x, const uint16_t* g, int64_t B, int6
         return launch_one<TL, OUTS>(x, g, B, T, din, dout, p, TO_ID ? out : nullptr, TO_ID ? nullptr : out, nullptr, stream, weight, nullptr,
                                     alpha, range);
     };
+    if (plan.mem_fold) {
+        float* out = plan.nsplit > 1 ? partials : S;
+        return launch_one<TileWide, OUTS | OUT_MEM>(x, g, B, T, din, dout, plan, TO_ID ? out : nullptr, TO_ID ? nullptr : out, nullptr, stream,
+                                                    weight, nullptr, alpha);
+    }
     if (plan.wide_cols == 0) return go(TilePhi{}, plan, plan.nsplit > 1 ? partials : S, ColumnRange{});
     StatPlan wide = plan;
     wide.nsplit = plan.wide_nsplit;
@@ -1049,7 +1119,8 @@ hipError_t launch_stat_bf16(const void* X, const void* G, int64_t B, int64_t T, 
         if (plan.per_split >= QUAD_MIN_ROWS) return launch_quad(x, g, B, T, din, dout, plan, out, stream);
         return launch_one<TileWide, OUT_ID>(x, g, B, T, din, dout, plan, out, nullptr, nullptr, stream);
     case MODE_TOKEN_SQ: return launch_one<TileToken, OUT_TOKEN>(x, g, B, T, din, dout, plan, out, nullptr, nullptr, stream);
-    case MODE_SQUARE: return launch_two_tile<OUT_SQ>(x, g, B, T, din, dout, plan, S, partials, stream, nullptr, 0.f);
+    case MODE_SQUARE:
+        return launch_two_tile<OUT_SQ>(x, g, B, T, din, dout, plan, S, partials, stream, nullptr, 0.f);
     case MODE_SIGN:
         if (sign_is_packed(B))
             return launch_one<TileWide, OUT_SIGN_PK>(x, g, B, T, din, dout, plan, nullptr, nullptr, out, stream, nullptr, nullptr, 0.f,

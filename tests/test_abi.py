@@ -39,7 +39,7 @@ def test_version_and_status_strings():
 
 def test_planner_options_are_clamped_and_change_the_plan():
     assert pex.pex_get_option("max_split") == 32 and pex.pex_get_option("token_presquare") == 1
-    assert pex.pex_get_option("wide_blocks") == 1 and pex.pex_get_option("gram_norms") == 1
+    assert pex.pex_get_option("wide_blocks") == 1 and pex.pex_get_option("gram_norms") == 1 and pex.pex_get_option("memory_fold") == 1
     L = pex.lib()
     assert L.pex_set_option(7, 1) == 4 and L.pex_get_option(7) == -1
     assert L.pex_set_option(0, 0) == 2 and L.pex_set_option(0, 33) == 2 and L.pex_set_option(1, 3) == 2 and L.pex_set_option(2, -1) == 2
@@ -60,6 +60,22 @@ def test_planner_options_are_clamped_and_change_the_plan():
         assert pex.pex_stat_workspace_bytes(*c4, pex.PEX_BF16, "square") == 0
     finally:
         pex.pex_set_option("wide_blocks", 1)
+    # few long examples: the square is folded in memory on 256 x 256 blocks, one group, no partial sums; many short ones
+    # stay on the two register tiles (the 1B-scale layer of the benchmark: partial sums of its narrow columns)
+    c5 = (4, 8192, 4096, 4096)
+    assert pex.pex_stat_workspace_bytes(*c5, pex.PEX_BF16, "square") == 0
+    assert pex.pex_stat_workspace_bytes(*c4, pex.PEX_BF16, "square") == 2 * 2048 * 2048 * 4
+    multi = pex.pex_stat_multi_workspace_bytes(*c4, pex.PEX_BF16, ("identity", "square"))
+    try:
+        pex.pex_set_option("memory_fold", 0)
+        assert pex.pex_stat_workspace_bytes(*c5, pex.PEX_BF16, "square") == 2 * 4096 * 1024 * 4
+        pex.pex_set_option("memory_fold", 2)
+        assert pex.pex_stat_workspace_bytes(*c4, pex.PEX_BF16, "square") == 0
+        assert pex.pex_weighted_sum_workspace_bytes(*c4, pex.PEX_BF16) == 0 and pex.pex_stat_power_workspace_bytes(*c4, pex.PEX_BF16) == 0
+        # what shares a contraction between statistics keeps its own block shape
+        assert pex.pex_stat_multi_workspace_bytes(*c4, pex.PEX_BF16, ("identity", "square")) == multi
+    finally:
+        pex.pex_set_option("memory_fold", 1)
     shape = (32, 256, 512, 2048)
     full = pex.pex_stat_workspace_bytes(*shape, pex.PEX_BF16, "identity")
     try:

@@ -343,6 +343,41 @@ def test_wide_blocks_side_by_side_with_narrow_ones(pex_option, B, T, din, dout):
         assert float((a - b).abs().max()) <= 2e-6 * float(b.abs().max())
 
 
+# The same three statistics have a third route on bf16 layers (option memory_fold): 256 x 256 blocks with one register
+# tile, phi(M_b) stored (first example of a group) or added (the others) to the output in memory at the end of every
+# example.  Forced here on ragged shapes: one group and several, tiles cut by both edges of the layer, a single example
+# (stores only), rows whose pitch is not a multiple of the tile.
+@pytest.mark.parametrize("B,T,din,dout,max_split", [(5, 77, 520, 264, 1), (3, 100, 200, 192, 1), (7, 33, 256, 456, 3), (4, 64, 512, 1024, 32),
+                                                    (1, 70, 264, 392, 1), (12, 24, 512, 200, 4), (2, 50, 96, 1160, 1)])
+def test_examples_folded_in_memory(pex_option, B, T, din, dout, max_split):
+    X, G = si.custom(B, T, din, dout, dtype="bf16", seed=B * 10 + T + 1)
+    Xd, Gd = X.to(DEV), G.to(DEV)
+    wts = torch.linspace(0.5, 1.5, B)
+    pex_option("max_split", max_split)
+    pex_option("memory_fold", 0)
+    in_registers = (pex.pex_stat(Xd, Gd, "square").clone(), pex.pex_weighted_sum(Xd, Gd, wts.to(DEV)).clone(),
+                    pex.pex_stat_power(Xd, Gd, 1.0).clone())
+    pex_option("memory_fold", 2)
+    need = pex.pex_stat_workspace_bytes(B, T, din, dout, pex.PEX_BF16, "square")
+    assert need % (din * dout * 4) == 0 and need <= max_split * din * dout * 4 and (max_split > 1 or need == 0)
+    # the outputs start from garbage: the first example of a group must store, not add
+    S = [torch.full((din, dout), float("nan"), device=DEV) for _ in range(3)]
+    pex.pex_stat(Xd, Gd, "square", S=S[0])
+    pex.pex_weighted_sum(Xd, Gd, wts.to(DEV), S=S[1])
+    pex.pex_stat_power(Xd, Gd, 1.0, S=S[2])
+    again = pex.pex_stat(Xd, Gd, "square").clone()
+    torch.cuda.synchronize()
+    st = oracle.stat(si.widen(X), si.widen(G))
+    f = lambda t: t.cpu().numpy().astype(np.float64)
+    assert_real_stat(f(S[0]), st.S_sq, "bf16", "square folded in memory", elementwise=(B >= 3))
+    M = np.einsum("bti,btj->bij", si.widen(X).astype(np.float64), si.widen(G).astype(np.float64))
+    assert_real_stat(f(S[1]), (wts.double().numpy()[:, None, None] * M).sum(0), "bf16", "weighted sum folded in memory", elementwise=False)
+    assert_real_stat(f(S[2]), np.abs(M).sum(0), "bf16", "|.|^1 folded in memory", elementwise=(B >= 3))
+    assert torch.equal(again, S[0])                      # one owner per entry, examples in order: the same bits every time
+    for a, b in zip(S, in_registers):
+        assert float((a - b).abs().max()) <= 2e-6 * float(b.abs().max())
+
+
 @pytest.mark.parametrize("B,expect_bytes", [(254, True), (256, False)])
 def test_sign_partials_at_the_byte_limit(pex_option, B, expect_bytes):
     """Two groups of 127 examples exchange their sign counts as bytes (+-127 is the largest a byte holds), two groups of

@@ -80,7 +80,7 @@ int pex_version(void);
  *                            tile, phi(M_b) being added to S in memory at the end of every example (by the one lane
  *                            that owns the entry, examples in ascending order: as reproducible as a register).  Each
  *                            such fold moves the whole of S once, so it pays for few, long examples only.  0 = never,
- *                            1 = chosen by a cost model (default), 2 = wherever it applies (dout < 2^21) (environment
+ *                            1 = chosen by a cost model (default), 2 = wherever it applies (dout < 2^20) (environment
  *                            PEX_MEMORY_FOLD).  It rounds the square before adding it where the register tiles use a
  *                            fused multiply-add: the routes agree to fp32 rounding, not bit for bit.
  * An option changes the plan and with it the *_workspace_bytes of later calls: query again after setting one.  A

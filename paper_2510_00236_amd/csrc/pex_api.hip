@@ -196,7 +196,7 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
         // add phi(M_b) to the output in memory at the end of every example
         const int fold_opt = option(PEX_OPT_MEMORY_FOLD);
         if (allow_wide && fold_opt != 0 && (mode == MODE_SQUARE || mode == MODE_WEIGHTED || mode == MODE_POWER) && bm == 256 && bn == 128 &&
-            dout < ((int64_t)1 << 21)) {
+            dout < ((int64_t)1 << 20)) {      // 32-bit byte offsets inside a tile of the output
             int fm, fn;
             bf16_tile_shape(MODE_IDENTITY, B, &fm, &fn);
             const int64_t tiles_f = ((din + fm - 1) / fm) * ((dout + fn - 1) / fn);

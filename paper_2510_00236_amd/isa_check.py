@@ -21,14 +21,20 @@ class IsaCheckError(RuntimeError):
     pass
 
 
-def quad_kernel_asm(hipcc: str, flags, src: str):
-    """(body lines, kernel descriptor text) of stat_bf16_quad_kernel compiled from ``src``."""
+def device_asm(hipcc: str, flags, src: str) -> str:
+    """The device assembly hipcc generates for ``src``."""
     with tempfile.TemporaryDirectory() as tmp:
         out = os.path.join(tmp, "pex_stat_bf16.s")
         flags = [f for f in flags if f != "-fPIC"]
         subprocess.run([hipcc, *flags, "--cuda-device-only", "-S", src, "-o", out], check=True,
                        stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
-        text = open(out).read()
+        return open(out).read()
+
+
+def quad_kernel_asm(hipcc: str, flags, src: str, text: str | None = None):
+    """(body lines, kernel descriptor text) of stat_bf16_quad_kernel compiled from ``src``."""
+    if text is None:
+        text = device_asm(hipcc, flags, src)
     m = re.search(r"^(_ZN\w*stat_bf16_quad_kernel\w*):[^\n]*\n(.*?)\n\s*s_endpgm", text, re.S | re.M)
     if not m:
         raise IsaCheckError("four-wave kernel not found in the assembly")
@@ -67,7 +73,24 @@ def check_registers(body, meta) -> None:
                 raise IsaCheckError(f"an MFMA of the four-wave kernel does not accumulate in place: {l.strip()}")
 
 
+def check_no_scratch(text: str) -> None:
+    """No contraction kernel of the file may spill: every flavour is sized to fit the register file, and one that does
+    not (a fold that keeps an address per accumulator alive across the main loop did once) still computes the right
+    result, only slowly -- no test would notice."""
+    kernels = re.findall(r"\.amdhsa_kernel (\S+)\n(.*?)\.end_amdhsa_kernel", text, re.S)
+    if not kernels:
+        raise IsaCheckError("no kernel descriptors found in the assembly")
+    for name, meta in kernels:
+        m = re.search(r"\.amdhsa_private_segment_fixed_size (\d+)", meta)
+        if not m:
+            raise IsaCheckError(f"no scratch size in the descriptor of {name}")
+        if int(m.group(1)) != 0:
+            raise IsaCheckError(f"{name} uses {m.group(1)} bytes of scratch memory per lane (register spills)")
+
+
 def check_all(hipcc: str, flags, src: str) -> None:
-    body, meta = quad_kernel_asm(hipcc, flags, src)
+    text = device_asm(hipcc, flags, src)
+    check_no_scratch(text)
+    body, meta = quad_kernel_asm(hipcc, flags, src, text)
     check_m0(body)
     check_registers(body, meta)

@@ -31,3 +31,11 @@ def test_no_spills_and_accumulators_stay_put(quad_asm):
     at = [i for i, l in enumerate(body) if "v_mfma_f32_16x16x32_bf16" in l]
     with pytest.raises(isa_check.IsaCheckError, match="accumulator moves"):
         isa_check.check_registers(body[:at[5]] + ["\tv_accvgpr_read_b32 v1, a0"] + body[at[5]:], meta)
+
+
+def test_no_contraction_kernel_spills():
+    text = isa_check.device_asm(pexbuild.HIPCC, pexbuild.FLAGS, SRC)
+    isa_check.check_no_scratch(text)
+    planted = text.replace(".amdhsa_private_segment_fixed_size 0", ".amdhsa_private_segment_fixed_size 756", 1)
+    with pytest.raises(isa_check.IsaCheckError, match="scratch memory"):
+        isa_check.check_no_scratch(planted)

@@ -99,7 +99,7 @@ static double cheapest_split(int64_t tiles, int64_t units, double t_unit, double
 // Sustained rate of one compute unit on the bf16 blocks, FLOP/s (measured on Gaussian operands, 1B-scale layers):
 // the larger the block, the fewer bytes go from L2 into LDS and from LDS into registers per FLOP.
 // chip-wide rates of the two routes to the per-example norms, FLOP/s (measured)
-constexpr double GRAM_RATE = 3.0e14, DIRECT_NORM_RATE = 1.3e15;
+constexpr double GRAM_RATE = 6.0e14, GRAM_STEP = 0.45e-6, DIRECT_NORM_RATE = 1.3e15;
 
 static double bf16_block_rate(int bm, int bn)
 {
@@ -240,16 +240,17 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
     if (mode == MODE_NORMS) {   // no S at all: one partial of ||M_b||^2 per tile (and wave) and example
         p.ws_bytes = (size_t)(p.kernel == 1 ? bf16_norm_partials(din, dout) : generic_norm_partials(din, dout)) * (size_t)B * sizeof(float);
         // Through the Gram matrices instead: 2 T^2 (din + dout) FLOP per example (a little over half of it with the
-        // symmetry, in 64 x 64 blocks) against 2 T din dout, on a kernel of lower rate but with one workgroup per block
+        // symmetry, in 128 x 128 blocks) against 2 T din dout, on a kernel of lower rate but with one workgroup per block
         // and example -- no batch split, however few tiles the layer has.
         const int gram_opt = option(PEX_OPT_GRAM_NORMS);
         if (dt == PEX_BF16 && gram_opt != 0 && gram_supports(B, T, din, dout)) {
-            // Gram kernel: 3.0e14 FLOP/s on a full chip, and never faster than its serial loop over the features,
-            // one 64-feature step per ~0.8 us (measured: it is bound by the latency of its loads when there are few
-            // blocks).  Contraction: the plan's rounds, plus ~20 us of start-up, epilogue and reduction on small layers.
+            // Gram kernel: 6.0e14 FLOP/s on a full chip (its 128 x 128 blocks draw twice the bytes per FLOP from L2 that
+            // the 256 x 256 blocks of the contraction do), and never faster than its serial loop over the features, one
+            // 64-feature step per ~0.45 us (measured with fewer workgroups than compute units).  Contraction: the plan's
+            // rounds, plus ~20 us of start-up, epilogue and reduction on small layers.
             const double steps = (double)((din + 63) / 64 + (dout + 63) / 64);
-            double t_gram = 2.0 * (double)B * (double)gram_norm_partials(T) * 64.0 * 64.0 * (double)(din + dout) / GRAM_RATE;
-            if (t_gram < steps * 0.8e-6) t_gram = steps * 0.8e-6;
+            double t_gram = 2.0 * (double)B * (double)gram_norm_partials(T) * 128.0 * 128.0 * (double)(din + dout) / GRAM_RATE;
+            if (t_gram < steps * GRAM_STEP) t_gram = steps * GRAM_STEP;
             t_gram += 6.0e-6;
             double t_direct = 2.0 * (double)B * (double)T * (double)din * (double)dout / DIRECT_NORM_RATE;
             if (p.kernel == 1) {

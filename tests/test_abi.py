@@ -45,13 +45,13 @@ def test_planner_options_are_clamped_and_change_the_plan():
     assert L.pex_set_option(0, 0) == 2 and L.pex_set_option(0, 33) == 2 and L.pex_set_option(1, 3) == 2 and L.pex_set_option(2, -1) == 2
     # per-example norms: one number per block of the T x T Gram matrices and example on the Gram route
     mid = (16, 512, 2048, 8192)
-    assert pex.pex_example_norms_workspace_bytes(*mid, pex.PEX_BF16) == 36 * 16 * 4          # 8 x 9 / 2 blocks of 64 x 64
+    assert pex.pex_example_norms_workspace_bytes(*mid, pex.PEX_BF16) == 10 * 16 * 4          # 4 x 5 / 2 blocks of 128 x 128
     try:
         pex.pex_set_option("gram_norms", 0)
         assert pex.pex_example_norms_workspace_bytes(*mid, pex.PEX_BF16) == 8 * 32 * 8 * 16 * 4   # tiles x waves x examples
         pex.pex_set_option("gram_norms", 2)
-        assert pex.pex_example_norms_workspace_bytes(16, 2048, 2048, 8192, pex.PEX_BF16) == 528 * 16 * 4
-        assert pex.pex_example_norms_workspace_bytes(16, 2048, 2044, 8192, pex.PEX_BF16) != 528 * 16 * 4   # rows of 16-byte multiples only
+        assert pex.pex_example_norms_workspace_bytes(16, 2048, 2048, 8192, pex.PEX_BF16) == 136 * 16 * 4
+        assert pex.pex_example_norms_workspace_bytes(16, 2048, 2044, 8192, pex.PEX_BF16) != 136 * 16 * 4   # rows of 16-byte multiples only
     finally:
         pex.pex_set_option("gram_norms", 1)
     c4 = (16, 2048, 2048, 8192)

@@ -34,11 +34,11 @@ def build(verbose: bool = False, extra_flags=()) -> str:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
-    # the four-wave kernel's assumptions about its own machine code, checked while the objects compile
+    # what the four-wave kernel and the Gram kernel assume about their own machine code, checked while the objects compile
     from . import isa_check
     isa_error = None
     try:
-        isa_check.check_all(HIPCC, [*FLAGS, *extra_flags], os.path.join(CSRC, "pex_stat_bf16.hip"))
+        isa_check.check_all(HIPCC, [*FLAGS, *extra_flags], os.path.join(CSRC, "pex_stat_bf16.hip"), os.path.join(CSRC, "pex_gram.hip"))
     except (isa_check.IsaCheckError, subprocess.CalledProcessError) as e:
         isa_error = e
     failed = False

@@ -39,3 +39,11 @@ def test_no_contraction_kernel_spills():
     planted = text.replace(".amdhsa_private_segment_fixed_size 0", ".amdhsa_private_segment_fixed_size 756", 1)
     with pytest.raises(isa_check.IsaCheckError, match="scratch memory"):
         isa_check.check_no_scratch(planted)
+
+
+def test_gram_kernel_keeps_its_accumulators_in_place():
+    text = isa_check.device_asm(pexbuild.HIPCC, pexbuild.FLAGS, os.path.join(pexbuild.CSRC, "pex_gram.hip"))
+    isa_check.check_no_scratch(text)
+    isa_check.check_accumulators_in_place(text)
+    with pytest.raises(isa_check.IsaCheckError, match="accumulator moves"):
+        isa_check.check_accumulators_in_place(text + "\n\tv_accvgpr_read_b32 v79, a3\n")

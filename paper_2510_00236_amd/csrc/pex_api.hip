@@ -216,15 +216,16 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
     nsplit = (units + per - 1) / per;      // no empty group
     p.nsplit = (int)nsplit;
     p.per_split = per_example ? per : per * slab;
-    // Per-token square on the MFMA kernel: squaring the operands inside the kernel costs LDS write bandwidth on
-    // every slab (about +60 % time); squaring them once into bf16 copies costs one pass over X and G at HBM speed
-    // (~5.5 TB/s, 4 bytes moved per element).  The copies win when din*dout/(din+dout) is large.
+    // Per-token square on the MFMA kernel: squaring the operands inside the kernel (global -> registers -> LDS instead
+    // of direct-to-LDS loads, plus the arithmetic) costs about +50 % time; squaring them once into bf16 copies costs one
+    // pass over X and G at HBM speed (~5.5 TB/s, 4 bytes moved per element).  The copies win when din*dout/(din+dout)
+    // is large.
     p.presq_bytes = 0;
     const int presquare = option(PEX_OPT_TOKEN_PRESQUARE);
     if (mode == MODE_TOKEN_SQ && p.kernel == 1 && presquare != 0) {
         const double elems = (double)B * (double)T * (double)(din + dout);
         const double t_pre = 4.0 * elems / 5.5e12 + 6.0e-6;
-        const double t_fused_extra = 0.6 * 2.0 * (double)B * (double)T * (double)din * (double)dout / 1.3e15;
+        const double t_fused_extra = 0.5 * 2.0 * (double)B * (double)T * (double)din * (double)dout / 1.3e15;
         if (t_pre < t_fused_extra || presquare == 2)
             p.presq_bytes = (((size_t)B * (size_t)T * (size_t)(din + dout) * 2) + 255) & ~(size_t)255;
     }

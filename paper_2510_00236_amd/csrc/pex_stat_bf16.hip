@@ -16,6 +16,8 @@
 //   * Slabs of BK tokens go HBM -> LDS with buffer_load_dwordx4 ... lds: no VGPR staging, no LDS write
 //     instructions.  Out-of-range lanes of a buffer load write zeros, which gives the zero fill of ragged slab
 //     rows (num_records of a per-slab descriptor) and of ragged tile columns (a poisoned lane offset) for free.
+//     (The per-token square is the exception: its operands have to be squared on the way, so its slabs go through
+//     registers -- same descriptors, same offsets, same places in the ring.)
 //   * Each such instruction writes 1 KiB contiguous, so slab rows cannot be padded; instead the 16-byte chunks of
 //     slab row r are stored at chunk index c ^ 4*(r mod 4).  The transposing read ds_read_b64_tr_b16 of a 16-lane
 //     group touches 4 consecutive rows x 32 bytes; the swizzle puts those in 4 different 64-byte bank groups.  The
@@ -266,7 +268,7 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
     constexpr int XROW = TL::XROW, GROW = TL::GROW, NXI = TL::NXI, NGI0 = TL::NGI0, NGI1 = TL::NGI1, RX = TL::RX;
     constexpr int LPS0 = TL::LPS0, LPS1 = TL::LPS1, FPK = TL::FPK, RC = TL::RC;
     constexpr bool TOKEN = (OUTS == OUT_TOKEN);
-    static_assert(!TOKEN || NGI0 == NGI1, "the in-place squaring assumes every wave loads the same share");
+    static_assert(!TOKEN || NGI0 == NGI1, "the register staging assumes every wave loads the same share");
     constexpr int NGI = NGI0, LPS = LPS0;      // the per-token square only: both groups alike
     constexpr bool PER_EXAMPLE = !(OUTS == OUT_ID || OUTS == OUT_TOKEN);
     constexpr bool HAS_W = (OUTS & OUT_IDW) != 0, HAS_NORM = (OUTS & OUT_NORM) != 0;
@@ -275,7 +277,6 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
     constexpr bool HAS_ID = !TO_MEM && ((PER_EXAMPLE && (OUTS & OUT_ID)) || HAS_W);
     constexpr bool HAS_SQ = !TO_MEM && ((OUTS & OUT_SQ) != 0 || HAS_POW);
     constexpr bool HAS_PK = (OUTS & OUT_SIGN_PK) != 0, HAS_SF = (OUTS & OUT_SIGN_F32) != 0, HAS_U8 = (OUTS & OUT_SIGN_U8) != 0;
-    static_assert(!TOKEN || NS >= 4, "the per-token square needs its slab one phase earlier");
     static_assert(HAS_PK + HAS_SF + HAS_U8 <= 1 && (OUTS & 1023) == OUTS && OUTS != 0, "one representation of the sign counts");
     static_assert(!TO_MEM || OUTS == (OUT_MEM | OUT_SQ) || OUTS == (OUT_MEM | OUT_IDW) || OUTS == (OUT_MEM | OUT_POW),
                   "memory accumulation carries one statistic");
@@ -349,24 +350,43 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
         ++iss_slab;
         iss_buf = (iss_buf + 1 == NS) ? 0 : iss_buf + 1;
     };
-    // Per-token square: lane L squares the 16 bytes its own loads put into buffer `buf` (so only this wave's vmcnt
-    // matters); squares are formed in fp32 and rounded to bf16 (nearest even); the zero fill stays zero.
-    auto square_share = [&](int buf) {
+    // Per-token square: no direct-to-LDS loads.  A wave's share of a slab (the same 16-byte chunks, the same places
+    // in the ring) goes global -> registers, is squared there -- in fp32, rounded to bf16 (nearest even); the zero fill
+    // stays zero -- and is written to LDS once.  Squaring it in place in LDS (a read and a write of every byte on top of the
+    // load's own write) cost 60 % over the plain contraction; this way the LDS sees one write per byte, as it does
+    // from a direct load.  Two register sets: slab s uses set s mod 2, its loads are issued two slabs before it is
+    // written to the ring, which happens one slab before its first reader; the compiler tracks these loads itself.
+    [[maybe_unused]] uint4_t stage[2][TOKEN ? LPS : 1];
+    auto load_slab = [&](auto SETC) {
+        constexpr int S = decltype(SETC)::value;
+        int valid = 0;
+        if (iss_slab < total) valid = (slen - iss_off) < BK ? (slen - iss_off) : BK;
+        const int nrx = valid > 0 ? ((valid - 1) * din + din_avail) * 2 : 0;
+        const int nrg = valid > 0 ? ((valid - 1) * ldg + dout_avail) * 2 : 0;
+        const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)xnext, 0, nrx, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rg = __builtin_amdgcn_make_buffer_rsrc((void*)gnext, 0, nrg, 0x00020000);
+#pragma unroll
+        for (int n = 0; n < NXI; ++n) stage[S][n] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)xoff[n], 0, 0);
+#pragma unroll
+        for (int n = 0; n < NGI; ++n) stage[S][NXI + n] = __builtin_amdgcn_raw_buffer_load_b128(rg, (int)goff[n], 0, 0);
+        xnext += (int64_t)valid * din;
+        gnext += (int64_t)valid * ldg;
+        iss_off += valid;
+        if (iss_off >= slen) iss_off = 0;
+        ++iss_slab;
+    };
+    auto square_store = [&](auto SETC, int buf) {
+        constexpr int S = decltype(SETC)::value;
         unsigned char* bx = lds + buf * TL::STAGE;
         unsigned char* bg = bx + TL::X_BYTES;
-        uint4_t v[LPS];
 #pragma unroll
-        for (int n = 0; n < NXI; ++n) v[n] = *(lds_u4)(bx + (wave * NXI + n) * 1024 + lane * 16);
+        for (int n = 0; n < (TOKEN ? LPS : 1); ++n)
 #pragma unroll
-        for (int n = 0; n < NGI; ++n) v[NXI + n] = *(lds_u4)(bg + (wave * NGI + n) * 1024 + lane * 16);
+            for (int e = 0; e < 4; ++e) stage[S][n][e] = square_pair_rne(stage[S][n][e]);
 #pragma unroll
-        for (int n = 0; n < LPS; ++n)
+        for (int n = 0; n < NXI; ++n) *(lds_u4)(bx + (wave * NXI + n) * 1024 + lane * 16) = stage[S][n];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[n][e] = square_pair_rne(v[n][e]);
-#pragma unroll
-        for (int n = 0; n < NXI; ++n) *(lds_u4)(bx + (wave * NXI + n) * 1024 + lane * 16) = v[n];
-#pragma unroll
-        for (int n = 0; n < NGI; ++n) *(lds_u4)(bg + (wave * NGI + n) * 1024 + lane * 16) = v[NXI + n];
+        for (int n = 0; n < NGI; ++n) *(lds_u4)(bg + (wave * NGI + n) * 1024 + lane * 16) = stage[S][NXI + n];
     };
 
     // ---- fragment geometry.  An operand fragment of v_mfma_f32_16x16x32_bf16 is 16 columns of the slab x 32 tokens:
@@ -451,12 +471,19 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
             for (int f = 0; f < FPK; ++f)
                 if (ks < KS - 1 || f < FPK - RC) read_frag(ks, f);
         issue_slab(GROUPC);   // after the reads: a wave that stalls on the memory pipeline here has its reads in flight
-        if constexpr (TOKEN) {
-            // this wave's part of the NEXT slab is squared in place, a phase or more ahead of its first reader
-            if (group == 0) wait_vmcnt<(NS - 3) * LPS>();
-            else wait_vmcnt<(NS - 2) * LPS>();
-            square_share(rd_buf);
-        }
+    };
+    // per-token square: after the reads of slab g, this wave's part of slab g+1 is squared and written to the ring (a
+    // phase or more ahead of its first reader), and the registers it leaves take the loads of slab g+3
+    auto read_phase_staged = [&](auto SETC) {
+        rd_bx = lds + rd_buf * TL::STAGE;
+        rd_buf = (rd_buf + 1 == NS) ? 0 : rd_buf + 1;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int f = 0; f < FPK; ++f)
+                if (ks < KS - 1 || f < FPK - RC) read_frag(ks, f);
+        square_store(SETC, rd_buf);
+        load_slab(SETC);
     };
     // Multiply phase: MFMA number i is followed by fragment read i of the last k-step (while i < RC).  The
     // scheduling fences pin this order; the compiler adds the LDS waits the MFMAs need.  The G fragment index runs
@@ -537,6 +564,34 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
     constexpr int INFLIGHT1 = (NS - 2) * LPS1;         // group 1, after its read phase of slab g
     constexpr std::integral_constant<int, 0> G0{};
     constexpr std::integral_constant<int, 1> G1{};
+    if constexpr (TOKEN) {
+        constexpr std::integral_constant<int, 0> S0{};
+        constexpr std::integral_constant<int, 1> S1{};
+        if (total > 0) {
+            load_slab(S0);
+            load_slab(S1);
+            square_store(S0, 0);
+            load_slab(S0);                        // slab 2
+            wait_lds_and_barrier();               // slab 0 is visible to every wave
+            // iteration g writes slab g+1 from set (g+1) mod 2: two iterations per trip, so that the set is fixed in the code
+            auto iteration = [&](auto SETC) {
+                read_phase_staged(SETC);
+                __builtin_amdgcn_sched_barrier(0);
+                wait_lds_and_barrier();
+                multiply_phase();
+                __builtin_amdgcn_sched_barrier(0);
+                plain_barrier();
+            };
+            if (group == 1) plain_barrier();      // start one phase late
+            int g = 0;
+            for (; g + 1 < total; g += 2) {
+                iteration(S1);
+                iteration(S0);
+            }
+            if (g < total) iteration(S1);
+            if (group == 0) plain_barrier();      // the other group's last multiply phase
+        }
+    } else
     if (total > 0) {
         if (group == 0) {
 #pragma unroll
@@ -547,7 +602,6 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
             for (int s = 0; s < AHEAD1; ++s) issue_slab(G1);
             wait_vmcnt<(AHEAD1 - 1) * LPS1>();
         }
-        if constexpr (TOKEN) square_share(0);
         wait_lds_and_barrier();               // slab 0 is visible to every wave
         int st_in_seg = 0;
         if (group == 0) {
@@ -557,7 +611,7 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
                 wait_lds_and_barrier();       // ends phase 2g
                 multiply_phase();
                 __builtin_amdgcn_sched_barrier(0);
-                if constexpr (!TOKEN) wait_vmcnt<INFLIGHT0>();   // this wave's part of slab g+1 has landed
+                wait_vmcnt<INFLIGHT0>();   // this wave's part of slab g+1 has landed
                 plain_barrier();              // ends phase 2g+1
                 if (PER_EXAMPLE && ++st_in_seg == nst) { st_in_seg = 0; fold_all(); }
             }
@@ -567,7 +621,7 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
             for (int g = 0; g < total; ++g) {
                 read_phase(G1);
                 __builtin_amdgcn_sched_barrier(0);
-                if constexpr (!TOKEN) wait_vmcnt<INFLIGHT1>();   // this wave's part of slab g+1 has landed
+                wait_vmcnt<INFLIGHT1>();   // this wave's part of slab g+1 has landed
                 wait_lds_and_barrier();       // ends phase 2g+1
                 multiply_phase();
                 __builtin_amdgcn_sched_barrier(0);
@@ -636,12 +690,12 @@ __global__ __launch_bounds__(256) void square_bf16_kernel(const uint4_t* __restr
 }
 
 // plain contractions and packed sign counts: 256 x 256 block, 128 x 64 per wave, slabs of 32 tokens, ring of 4;
-// the per-token square needs its slab a phase earlier and takes a ring of 5 (all 160 KB of LDS);
+// the per-token square stages its slabs through registers (no loads in flight into the ring) and takes a ring of 3;
 // two fp32 register tiles (phi = square, sign counts beyond 2048 examples): 256 x 128 block, 64 x 64 per wave, or --
 // for a single statistic -- 256 x 192 (64 x 96 per wave, 96 + 96 accumulators): 22 % fewer bytes from L2 into LDS and
 // 17 % fewer fragment reads per FLOP.
 using TileWide = Bf16Tile<256, 256, 128, 64, 32, 4, 5>;
-using TileToken = Bf16Tile<256, 256, 128, 64, 32, 5, 5>;
+using TileToken = Bf16Tile<256, 256, 128, 64, 32, 3, 5>;
 using TilePhi = Bf16Tile<256, 128, 64, 64, 32, 4, 3>;
 // (ring of 5 slabs = 140 KB; five of its ten fragments -- G fragments, its sub-tile being walked column by column -- are
 // read in the multiply phase, each 7 MFMAs ahead of its first use: measured best of rings of 4 and 5, 1 to 5 late

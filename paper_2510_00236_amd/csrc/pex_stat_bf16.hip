@@ -356,6 +356,8 @@ __global__ __launch_bounds__(TL::NT, 1) void stat_bf16_kernel(const uint16_t* __
     // load's own write) cost 60 % over the plain contraction; this way the LDS sees one write per byte, as it does
     // from a direct load.  Two register sets: slab s uses set s mod 2, its loads are issued two slabs before it is
     // written to the ring, which happens one slab before its first reader; the compiler tracks these loads itself.
+    // (load_slab repeats the slab bookkeeping of issue_slab on purpose: sharing it through a helper changed the code
+    // generated for every other flavour -- about 50 more instructions per kernel, phi = square 4 % slower.)
     [[maybe_unused]] uint4_t stage[2][TOKEN ? LPS : 1];
     auto load_slab = [&](auto SETC) {
         constexpr int S = decltype(SETC)::value;

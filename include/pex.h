@@ -71,11 +71,13 @@ int pex_version(void);
  *                            2 = as many columns as fit on the wide shape, always (environment PEX_WIDE_BLOCKS).
  *                            The result is the same bits under every value.
  *   PEX_OPT_GRAM_NORMS       pex_example_norms on bf16 layers has two routes: the per-example contraction, and the T x T
- *                            Gram matrices of the "ghost" norm (Sec. 2.3), N_b = <X_b X_b^T, G_b G_b^T>.  0 = the
- *                            contraction only, 1 = chosen by a cost model (default: the Gram route for short
- *                            sequences and layers of few tiles), 2 = the Gram route wherever it applies (rows that are
- *                            multiples of 16 bytes, B <= 65535) (environment PEX_GRAM_NORMS).  The two routes agree to
- *                            fp32 rounding, not bit for bit.
+ *                            Gram matrices of the "ghost" norm (Sec. 2.3), N_b = <X_b X_b^T, G_b G_b^T>, on blocks of
+ *                            128 x 128 or, with 256 KiB of workspace per block and example, of 256 x 256.  0 = the
+ *                            contraction only, 1 = chosen by a cost model (default: a Gram route for sequences that
+ *                            are short for the layer), 2 = the Gram route on 128 x 128 blocks wherever it applies (rows
+ *                            that are multiples of 16 bytes, B <= 65535), 3 = on 256 x 256 blocks wherever that applies
+ *                            (its workspace at most 256 MiB), else as 2 (environment PEX_GRAM_NORMS).  The routes agree
+ *                            to fp32 rounding, not bit for bit.
  *   PEX_OPT_MEMORY_FOLD      the same three calls have a third route on bf16 layers: the 256 x 256 block with one register
  *                            tile, phi(M_b) being added to S in memory at the end of every example (by the one lane
  *                            that owns the entry, examples in ascending order: as reproducible as a register).  Each

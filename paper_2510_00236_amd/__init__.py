@@ -146,7 +146,7 @@ OPTION = {"max_split": PEX_OPT_MAX_SPLIT, "token_presquare": PEX_OPT_TOKEN_PRESQ
 
 
 def pex_set_option(opt, value) -> None:
-    """Set a planner option ('max_split' 1..32, 'token_presquare' 0|1|2, 'wide_blocks' 0|1|2, 'gram_norms' 0|1|2, 'memory_fold' 0|1|2, or the code)."""
+    """Set a planner option ('max_split' 1..32, 'token_presquare' 0|1|2, 'wide_blocks' 0|1|2, 'gram_norms' 0|1|2|3, 'memory_fold' 0|1|2, or the code)."""
     _check(lib().pex_set_option(OPTION.get(opt, opt), int(value)))
 
 

@@ -38,7 +38,8 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     from . import isa_check
     isa_error = None
     try:
-        isa_check.check_all(HIPCC, [*FLAGS, *extra_flags], os.path.join(CSRC, "pex_stat_bf16.hip"), os.path.join(CSRC, "pex_gram.hip"))
+        isa_check.check_all(HIPCC, [*FLAGS, *extra_flags], os.path.join(CSRC, "pex_stat_bf16.hip"), os.path.join(CSRC, "pex_gram.hip"),
+                            os.path.join(CSRC, "pex_gram_wide.hip"))
     except (isa_check.IsaCheckError, subprocess.CalledProcessError) as e:
         isa_error = e
     failed = False

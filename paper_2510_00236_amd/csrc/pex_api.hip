@@ -48,6 +48,7 @@ static bool known_option(int opt) { return opt >= 0 && opt < NUM_OPTIONS; }
 static int clamp_option(int opt, int value)
 {
     if (opt == PEX_OPT_MAX_SPLIT) return value < 1 ? 1 : (value > 32 ? 32 : value);
+    if (opt == PEX_OPT_GRAM_NORMS) return value < 0 ? 0 : (value > 3 ? 3 : value);   // 2, 3: forced, on small / large blocks
     return value < 0 ? 0 : (value > 2 ? 2 : value);      // every other option: 0 = off, 1 = cost model, 2 = forced
 }
 
@@ -99,7 +100,7 @@ static double cheapest_split(int64_t tiles, int64_t units, double t_unit, double
 // Sustained rate of one compute unit on the bf16 blocks, FLOP/s (measured on Gaussian operands, 1B-scale layers):
 // the larger the block, the fewer bytes go from L2 into LDS and from LDS into registers per FLOP.
 // chip-wide rates of the two routes to the per-example norms, FLOP/s (measured)
-constexpr double GRAM_RATE = 6.0e14, GRAM_STEP = 0.45e-6, DIRECT_NORM_RATE = 1.3e15;
+constexpr double GRAM_RATE = 6.0e14, GRAM_STEP = 0.45e-6, GRAM_WIDE_STEP_FULL = 0.9e-6, GRAM_WIDE_STEP = 0.75e-6, DIRECT_NORM_RATE = 1.3e15;
 
 static double bf16_block_rate(int bm, int bn)
 {
@@ -260,7 +261,19 @@ StatPlan plan_stat(int64_t B, int64_t T, int64_t din, int64_t dout, pex_dtype dt
                 if (t_rounds > t_direct) t_direct = t_rounds;
             }
             t_direct += 20.0e-6;
-            if (gram_opt == 2 || t_gram < t_direct) {
+            // On 256 x 256 blocks: half the bytes per FLOP; one workgroup per block and example in rounds of 256, each a
+            // serial loop of 32-feature steps (measured: ~0.9 us per step on a full chip, ~0.75 us below that), and the
+            // parked blocks written and read once (~4 TB/s); while they stay below a quarter of a GiB.
+            const size_t park = gram_wide_park_bytes(B, T);
+            const double steps_w = (double)((din + 31) / 32 + (dout + 31) / 32);
+            const int64_t wgs = B * gram_wide_partials(T);
+            double t_wide = (double)((wgs + 255) / 256) * steps_w * (wgs > 256 ? GRAM_WIDE_STEP_FULL : GRAM_WIDE_STEP);
+            t_wide += 2.0 * (double)park / 4.0e12 + 8.0e-6;
+            const bool wide_ok = park <= ((size_t)256 << 20);
+            if (gram_opt == 3 ? wide_ok : (gram_opt == 1 && wide_ok && t_wide < t_gram && t_wide < t_direct)) {
+                p.gram = p.gram_wide = true;
+                p.ws_bytes = (((size_t)gram_wide_partials(T) * (size_t)B * sizeof(float) + 255) & ~(size_t)255) + park;
+            } else if (gram_opt == 2 || gram_opt == 3 || t_gram < t_direct) {
                 p.gram = true;
                 p.ws_bytes = (size_t)gram_norm_partials(T) * (size_t)B * sizeof(float);
             }
@@ -542,7 +555,11 @@ pex_status pex_example_norms(const void* X, const void* G, int64_t B, int64_t T,
     float* partial = (float*)workspace;
     hipError_t e;
     int64_t nparts;
-    if (plan.gram) {
+    if (plan.gram_wide) {
+        nparts = gram_wide_partials(T);
+        void* park = (char*)workspace + (((size_t)nparts * (size_t)B * sizeof(float) + 255) & ~(size_t)255);
+        e = launch_gram_wide(X, G, B, T, din, dout, partial, park, hs);
+    } else if (plan.gram) {
         nparts = gram_norm_partials(T);
         e = launch_gram_norms(X, G, B, T, din, dout, partial, hs);
     } else if (plan.kernel == 1) {

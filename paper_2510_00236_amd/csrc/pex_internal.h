@@ -32,6 +32,7 @@ struct StatPlan {
                        // in memory at the end of every example (nsplit / per_split describe the whole layer, wide_cols = 0)
     bool sign_bytes;   // MODE_SIGN on bf16 layers, split batch: the partial counts are bytes (per tile layout), not fp32
     bool gram;         // MODE_NORMS on bf16 layers: through the T x T Gram matrices instead of the contraction
+    bool gram_wide;    // ... on 256 x 256 blocks whose X X^T part waits in the workspace (after the partials, 256-byte aligned)
     size_t ws_bytes;   // presq_bytes + wide_ws_bytes + (nsplit > 1 ? nsplit * din * (dout - wide_cols) * 4 : 0)
 };
 
@@ -59,6 +60,12 @@ int64_t gram_norm_partials(int64_t T);
 bool gram_supports(int64_t B, int64_t T, int64_t din, int64_t dout);
 hipError_t launch_gram_norms(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout, float* partial,
                              hipStream_t stream);
+// The same on 256 x 256 blocks: one partial per block of the upper triangle and example, and 256 KiB of workspace per
+// workgroup where the block of X_b X_b^T waits while G_b G_b^T is formed
+int64_t gram_wide_partials(int64_t T);
+size_t gram_wide_park_bytes(int64_t B, int64_t T);
+hipError_t launch_gram_wide(const void* X, const void* G, int64_t B, int64_t T, int64_t din, int64_t dout, float* partial, void* park,
+                            hipStream_t stream);
 // N[b] = sum_{p < nparts} partial[p][b], p ascending
 hipError_t launch_reduce_norms(const float* partial, int64_t nparts, int64_t B, float* N, hipStream_t stream);
 // N_tok[r] = |x_r|^2 |g_r|^2 for every row r of the flattened [B*T] axis

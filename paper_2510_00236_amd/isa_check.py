@@ -89,20 +89,21 @@ def check_no_scratch(text: str) -> None:
 
 
 def check_accumulators_in_place(text: str) -> None:
-    """The Gram kernel keeps two sets of accumulators, one per matrix; compiled with the whole register file of a lone
-    wave the compiler once split them over both halves of the file and moved them in and out in every step."""
+    """The Gram kernels keep their accumulators where they are across two loops (one per matrix); compiled with the whole
+    register file of a lone wave the compiler once split them over both halves of the file and moved them in and out in
+    every step."""
     moves = [l.strip() for l in text.splitlines() if "v_accvgpr" in l]
     if moves:
         raise IsaCheckError(f"{len(moves)} accumulator moves in the Gram kernel, e.g. {moves[0]}")
 
 
-def check_all(hipcc: str, flags, src: str, gram_src: str | None = None) -> None:
+def check_all(hipcc: str, flags, src: str, *gram_srcs: str) -> None:
     text = device_asm(hipcc, flags, src)
     check_no_scratch(text)
     body, meta = quad_kernel_asm(hipcc, flags, src, text)
     check_m0(body)
     check_registers(body, meta)
-    if gram_src is not None:
+    for gram_src in gram_srcs:
         gram = device_asm(hipcc, flags, gram_src)
         check_no_scratch(gram)
         check_accumulators_in_place(gram)

@@ -134,19 +134,27 @@ GRAM_SHAPES = [(5, 77, 520, 264), (3, 100, 200, 136), (7, 33, 256, 128), (1, 64,
                (2, 130, 72, 40), (3, 257, 64, 64), (6, 300, 328, 200)]
 
 
-@pytest.mark.parametrize("B,T,din,dout", GRAM_SHAPES)
-def test_norms_through_the_gram_matrices(pex_option, B, T, din, dout):
-    """N_b = <X_b X_b^T, G_b G_b^T> (the "ghost" norm of Sec. 2.3) on its own kernel: blocks of the upper triangle with
-    ragged last rows, feature counts that are not multiples of the 64-feature step, T = 1, diagonal and off-diagonal blocks.  Against the oracle (which
-    materialises M_b) and against the contraction route."""
+@pytest.mark.parametrize("route", [2, 3])
+@pytest.mark.parametrize("B,T,din,dout", GRAM_SHAPES + [(2, 600, 136, 72), (3, 513, 40, 264)])
+def test_norms_through_the_gram_matrices(pex_option, B, T, din, dout, route):
+    """N_b = <X_b X_b^T, G_b G_b^T> (the "ghost" norm of Sec. 2.3) on its own kernels, 128 x 128 blocks (route 2) and
+    256 x 256 blocks whose X X^T part waits in the workspace (route 3): blocks of the upper triangle with ragged last
+    rows, feature counts that are not multiples of a step, T = 1, diagonal and off-diagonal blocks.  Against the oracle
+    (which materialises M_b) and against the contraction route."""
     X, G = si.custom(B, T, din, dout, dtype="bf16", seed=B * 7 + T)
     Xd, Gd = X.to(DEV), G.to(DEV)
     ref = on.example_norms(si.widen(X), si.widen(G))
     pex_option("gram_norms", 0)
     direct = pex.pex_example_norms(Xd, Gd).cpu().double().numpy()
-    pex_option("gram_norms", 2)
-    nblk = (T + 127) // 128
-    assert pex.pex_example_norms_workspace_bytes(B, T, din, dout, pex.PEX_BF16) == nblk * (nblk + 1) // 2 * B * 4
+    pex_option("gram_norms", route)
+    edge = 128 if route == 2 else 256
+    nblk = (T + edge - 1) // edge
+    npairs = nblk * (nblk + 1) // 2
+    need = pex.pex_example_norms_workspace_bytes(B, T, din, dout, pex.PEX_BF16)
+    if route == 2:
+        assert need == npairs * B * 4
+    else:
+        assert need == (npairs * B * 4 + 255) // 256 * 256 + npairs * B * 256 * 1024      # partials, then 256 KiB per workgroup
     gram = pex.pex_example_norms(Xd, Gd)
     again = pex.pex_example_norms(Xd, Gd)
     torch.cuda.synchronize()

@@ -41,8 +41,9 @@ def test_no_contraction_kernel_spills():
         isa_check.check_no_scratch(planted)
 
 
-def test_gram_kernel_keeps_its_accumulators_in_place():
-    text = isa_check.device_asm(pexbuild.HIPCC, pexbuild.FLAGS, os.path.join(pexbuild.CSRC, "pex_gram.hip"))
+@pytest.mark.parametrize("name", ["pex_gram.hip", "pex_gram_wide.hip"])
+def test_gram_kernels_keep_their_accumulators_in_place(name):
+    text = isa_check.device_asm(pexbuild.HIPCC, pexbuild.FLAGS, os.path.join(pexbuild.CSRC, name))
     isa_check.check_no_scratch(text)
     isa_check.check_accumulators_in_place(text)
     with pytest.raises(isa_check.IsaCheckError, match="accumulator moves"):

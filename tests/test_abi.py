@@ -42,13 +42,23 @@ def test_planner_options_are_clamped_and_change_the_plan():
     assert pex.pex_get_option("wide_blocks") == 1 and pex.pex_get_option("gram_norms") == 1 and pex.pex_get_option("memory_fold") == 1
     L = pex.lib()
     assert L.pex_set_option(7, 1) == 4 and L.pex_get_option(7) == -1
-    assert L.pex_set_option(0, 0) == 2 and L.pex_set_option(0, 33) == 2 and L.pex_set_option(1, 3) == 2 and L.pex_set_option(2, -1) == 2
+    assert L.pex_set_option(0, 0) == 2 and L.pex_set_option(0, 33) == 2 and L.pex_set_option(1, 3) == 2 and L.pex_set_option(2, -1) == 2 and L.pex_set_option(3, 4) == 2
     # per-example norms: one number per block of the T x T Gram matrices and example on the Gram route
     mid = (16, 512, 2048, 8192)
     assert pex.pex_example_norms_workspace_bytes(*mid, pex.PEX_BF16) == 10 * 16 * 4          # 4 x 5 / 2 blocks of 128 x 128
+    # longer sequences on the same layer: 256 x 256 blocks, whose X X^T part waits in the workspace (256 KiB per block and
+    # example, after the partials); the 1B-scale layer of the benchmark itself stays on the contraction
+    longer = (16, 1024, 2048, 8192)
+    assert pex.pex_example_norms_workspace_bytes(*longer, pex.PEX_BF16) == 10 * 16 * 4 + 128 + 10 * 16 * 256 * 1024
+    assert pex.pex_example_norms_workspace_bytes(16, 2048, 2048, 8192, pex.PEX_BF16) == 8 * 32 * 8 * 16 * 4
     try:
         pex.pex_set_option("gram_norms", 0)
         assert pex.pex_example_norms_workspace_bytes(*mid, pex.PEX_BF16) == 8 * 32 * 8 * 16 * 4   # tiles x waves x examples
+        pex.pex_set_option("gram_norms", 3)
+        assert pex.pex_get_option("gram_norms") == 3
+        assert pex.pex_example_norms_workspace_bytes(*mid, pex.PEX_BF16) == 3 * 16 * 4 + 64 + 3 * 16 * 256 * 1024
+        # too many blocks to park (B = 4, T = 8192: 528 x 4 x 256 KiB): the small blocks instead
+        assert pex.pex_example_norms_workspace_bytes(4, 8192, 4096, 4096, pex.PEX_BF16) == 2080 * 4 * 4
         pex.pex_set_option("gram_norms", 2)
         assert pex.pex_example_norms_workspace_bytes(16, 2048, 2048, 8192, pex.PEX_BF16) == 136 * 16 * 4
         assert pex.pex_example_norms_workspace_bytes(16, 2048, 2044, 8192, pex.PEX_BF16) != 136 * 16 * 4   # rows of 16-byte multiples only

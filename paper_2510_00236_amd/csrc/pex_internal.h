@@ -54,7 +54,7 @@ hipError_t launch_norms_bf16(const void* X, const void* G, int64_t B, int64_t T,
                              float* norm_partial, hipStream_t stream);
 hipError_t launch_weighted_bf16(const void* X, const void* G, const float* w, int64_t B, int64_t T, int64_t din, int64_t dout,
                                 const StatPlan& plan, float* S, float* partials, hipStream_t stream);
-// Per-example squared norms through the Gram matrices X_b X_b^T and G_b G_b^T (bf16): one partial per 64 x 64 block of
+// Per-example squared norms through the Gram matrices X_b X_b^T and G_b G_b^T (bf16): one partial per 128 x 128 block of
 // their upper triangle and example, partial[block][B]
 int64_t gram_norm_partials(int64_t T);
 bool gram_supports(int64_t B, int64_t T, int64_t din, int64_t dout);
